@@ -1,0 +1,197 @@
+"""ctypes binding of libmavg.so: the same names as include/mavg.h, argument marshalling only.
+
+Device buffers are torch tensors (PyTorch is used for device memory and streams, nothing else) or raw
+integer addresses.  Every call enqueues on torch's current stream unless `stream` is given.  There is
+no CPU fallback: if the library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmavg.so")
+
+OK, E_NULL, E_DIM, E_ALIGN, E_FLAG, E_LAUNCH, E_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
+MEAN_GRAD, USE_NGSGD = 1, 2
+VIS_BERNOULLI, VIS_GAUSSIAN = 0, 1
+SAMPLE_V1 = 1
+NG_APPLY, NG_UPDATE, NG_INIT_UPDATE = 0, 1, 2
+
+_ERR = {E_NULL: "null pointer", E_DIM: "bad dimension or count", E_ALIGN: "bad alignment or stride",
+        E_FLAG: "unknown flag or unsupported mode", E_LAUNCH: "HIP launch error", E_WORKSPACE: "workspace too small"}
+
+
+class MavgError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__(f"{where}: error {code} ({_ERR.get(code, 'unknown')})")
+        self.code = code
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_1507_01239_amd.build` "
+                      "(or __graft_entry__.build()); there is no fallback path")
+lib = C.CDLL(LIB_PATH)
+
+
+class _Shape(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("dims", C.POINTER(C.c_int32))]
+
+
+class Shape:
+    """Network widths d_0..d_L."""
+
+    def __init__(self, dims):
+        self.dims = tuple(int(d) for d in dims)
+        self._arr = (C.c_int32 * len(self.dims))(*self.dims)
+        self._s = _Shape(len(self.dims) - 1, C.cast(self._arr, C.POINTER(C.c_int32)))
+
+    @property
+    def ref(self):
+        return C.byref(self._s)
+
+
+_p, _i32, _i64, _u32, _u64, _f = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_float
+_SIG = {
+    "mavg_version": (C.c_char_p, []),
+    "mavg_param_count": (_i64, [_p]),
+    "mavg_act_count": (_i64, [_p, _i32]),
+    "mavg_workspace_bytes": (_i64, [_p, _i32, _i32, _u32, _i32]),
+    "dnn_forward": (_i32, [_p, _i32, _p, _i64, _p, _i64, _i32, _p, _i64, _p, _i64, _p]),
+    "dnn_backward_update": (_i32, [_p, _i32, _p, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _f, _u32,
+                                   _p, _i64, _i32, _f, _f, _p, _p, _i64, _p]),
+    "replicas_average": (_i32, [_p, _i64, _i64, _i32, _p]),
+    "rbm_workspace_bytes": (_i64, [_i32, _i32, _i32]),
+    "rbm_cd1_step": (_i32, [_i32, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _i32, _f, _f, _u64, _u32, _u32, _u32,
+                            _p, _p, _p, _p, _p, _i64, _p]),
+    "rbm_hidden_prob": (_i32, [_i32, _i32, _p, _p, _p, _i32, _p, _p, _i64, _p]),
+    "ngsgd_state_bytes": (_i64, [_i32, _i32]),
+    "ngsgd_workspace_bytes": (_i64, [_i32, _i32, _i32]),
+    "ngsgd_state_init": (_i32, [_p, _i32, _i32, _p]),
+    "ngsgd_precondition": (_i32, [_p, _i32, _i32, _p, _i64, _i32, _f, _f, _i32, _p, _i64, _p]),
+    "mavg_gemm": (_i32, [_p, _i64, _i32, _p, _i64, _i32, _p, _i64, _i32, _i32, _i32, _i32, _p, _p, _i64, _f, _f,
+                         _i32, _i32, _p, _i64, _p]),
+    "mavg_gemm_workspace_bytes": (_i64, [_i32, _i32, _i32, _i32, _i32]),
+}
+EXPORTS = tuple(_SIG)
+for _name, (_res, _args) in _SIG.items():
+    _fn = getattr(lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+
+def ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    if hasattr(t, "ctypes"):
+        return t.ctypes.data
+    raise TypeError(type(t))
+
+
+def _nbytes(t):
+    if t is None:
+        return 0
+    if hasattr(t, "element_size"):
+        return t.numel() * t.element_size()
+    return int(t.nbytes)
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+
+
+def _check(rc, where):
+    if rc < 0:
+        raise MavgError(int(rc), where)
+    return rc
+
+
+def mavg_version() -> str:
+    return lib.mavg_version().decode()
+
+
+def mavg_param_count(shape: Shape) -> int:
+    return _check(lib.mavg_param_count(shape.ref), "mavg_param_count")
+
+
+def mavg_act_count(shape: Shape, n: int) -> int:
+    return _check(lib.mavg_act_count(shape.ref, n), "mavg_act_count")
+
+
+def mavg_workspace_bytes(shape: Shape, n: int, k: int, flags: int = 0, ng_rank: int = 0) -> int:
+    return _check(lib.mavg_workspace_bytes(shape.ref, n, k, flags, ng_rank), "mavg_workspace_bytes")
+
+
+def dnn_forward(shape, k, theta, theta_stride, x, x_stride, n, acts, act_stride, workspace, stream=None,
+                workspace_bytes=None):
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    return _check(lib.dnn_forward(shape.ref, k, ptr(theta), theta_stride, ptr(x), x_stride, n, ptr(acts), act_stride,
+                                  ptr(workspace), wb, _stream(stream)), "dnn_forward")
+
+
+def dnn_backward_update(shape, k, theta, theta_stride, x, x_stride, labels, label_stride, n, acts, act_stride, lr,
+                        flags, loss_sum, workspace, ng_state=None, ng_state_stride=0, ng_rank=0, ng_alpha=4.0,
+                        ng_eta=0.0, stream=None, workspace_bytes=None):
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    return _check(lib.dnn_backward_update(shape.ref, k, ptr(theta), theta_stride, ptr(x), x_stride, ptr(labels),
+                                          label_stride, n, ptr(acts), act_stride, lr, flags, ptr(ng_state),
+                                          ng_state_stride, ng_rank, ng_alpha, ng_eta, ptr(loss_sum), ptr(workspace), wb,
+                                          _stream(stream)), "dnn_backward_update")
+
+
+def replicas_average(theta, theta_stride, count, k, stream=None):
+    return _check(lib.replicas_average(ptr(theta), theta_stride, count, k, _stream(stream)), "replicas_average")
+
+
+def rbm_workspace_bytes(n_vis, n_hid, n) -> int:
+    return _check(lib.rbm_workspace_bytes(n_vis, n_hid, n), "rbm_workspace_bytes")
+
+
+def rbm_cd1_step(n_vis, n_hid, vis_type, w, a, c, mw, ma, mc, v0, n, lr, momentum, seed, step, layer, flags,
+                 recon_err, workspace, dbg_ph0=None, dbg_h0=None, dbg_v1=None, stream=None, workspace_bytes=None):
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    return _check(lib.rbm_cd1_step(n_vis, n_hid, vis_type, ptr(w), ptr(a), ptr(c), ptr(mw), ptr(ma), ptr(mc), ptr(v0), n,
+                                   lr, momentum, seed, step, layer, flags, ptr(recon_err), ptr(dbg_ph0), ptr(dbg_h0),
+                                   ptr(dbg_v1), ptr(workspace), wb, _stream(stream)), "rbm_cd1_step")
+
+
+def rbm_hidden_prob(n_vis, n_hid, w, c, v, n, out, workspace, stream=None, workspace_bytes=None):
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    return _check(lib.rbm_hidden_prob(n_vis, n_hid, ptr(w), ptr(c), ptr(v), n, ptr(out), ptr(workspace), wb,
+                                      _stream(stream)), "rbm_hidden_prob")
+
+
+def ngsgd_state_bytes(dim, rank) -> int:
+    return _check(lib.ngsgd_state_bytes(dim, rank), "ngsgd_state_bytes")
+
+
+def ngsgd_workspace_bytes(dim, rank, n) -> int:
+    return _check(lib.ngsgd_workspace_bytes(dim, rank, n), "ngsgd_workspace_bytes")
+
+
+def ngsgd_state_init(state, dim, rank, stream=None):
+    return _check(lib.ngsgd_state_init(ptr(state), dim, rank, _stream(stream)), "ngsgd_state_init")
+
+
+def ngsgd_precondition(state, dim, rank, x, ldx, n, alpha, eta, update, workspace, stream=None, workspace_bytes=None):
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    return _check(lib.ngsgd_precondition(ptr(state), dim, rank, ptr(x), ldx, n, alpha, eta, update, ptr(workspace), wb,
+                                         _stream(stream)), "ngsgd_precondition")
+
+
+def mavg_gemm_workspace_bytes(m, n, k, cfg=-1, splits=0) -> int:
+    return _check(lib.mavg_gemm_workspace_bytes(m, n, k, cfg, splits), "mavg_gemm_workspace_bytes")
+
+
+def mavg_gemm(a, lda, a_kc, b, ldb, b_kc, c, ldc, m, n, k, epi, bias, aux, ldaux, alpha, beta, cfg, splits, workspace,
+              stream=None, workspace_bytes=None):
+    wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    return _check(lib.mavg_gemm(ptr(a), lda, int(a_kc), ptr(b), ldb, int(b_kc), ptr(c), ldc, m, n, k, epi, ptr(bias),
+                                ptr(aux), ldaux, alpha, beta, cfg, splits, ptr(workspace), wb, _stream(stream)), "mavg_gemm")

@@ -1,0 +1,248 @@
+// dnn_forward / dnn_backward_update: host-side validation and the sequence of kernel launches for
+// one minibatch of k replicas (the replica index is the batch dimension of every launch).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mavg.h"
+#include "gemm.h"
+#include "kernels.h"
+#include "ng_internal.h"
+
+using namespace mavg;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+int check_shape(const mavg_shape* sh) {
+    if (!sh || !sh->dims) return MAVG_E_NULL;
+    if (sh->n_layers < 1 || sh->n_layers > MAVG_MAX_LAYERS) return MAVG_E_DIM;
+    for (int l = 0; l <= sh->n_layers; ++l)
+        if (sh->dims[l] < 1) return MAVG_E_DIM;
+    return MAVG_OK;
+}
+
+// offsets (in floats) of W_l and b_l inside theta, and of A_l inside acts, l = 1..L
+struct Layout {
+    int L;
+    int d[MAVG_MAX_LAYERS + 1];
+    int64_t w_off[MAVG_MAX_LAYERS + 1], b_off[MAVG_MAX_LAYERS + 1], a_off[MAVG_MAX_LAYERS + 1];
+    int64_t P, acts;
+    int dmax;      // widest layer output
+};
+
+Layout make_layout(const mavg_shape* sh, int n) {
+    Layout y;
+    y.L = sh->n_layers;
+    int64_t off = 0, aoff = 0;
+    y.dmax = 0;
+    y.d[0] = sh->dims[0];
+    for (int l = 1; l <= y.L; ++l) {
+        y.d[l] = sh->dims[l];
+        y.w_off[l] = off;
+        off += (int64_t)sh->dims[l] * sh->dims[l - 1];
+        y.b_off[l] = off;
+        off += sh->dims[l];
+        y.a_off[l] = aoff;
+        aoff += (int64_t)n * sh->dims[l];
+        if (sh->dims[l] > y.dmax) y.dmax = sh->dims[l];
+    }
+    y.P = off;
+    y.acts = aoff;
+    return y;
+}
+
+// Workspace carve-up shared by forward and backward.
+struct Workspace {
+    int64_t ld_delta;       // row stride of the two delta buffers
+    int64_t delta_floats;   // per buffer (all replicas)
+    int64_t off_delta[2], off_rowloss, off_gemm, gemm_floats;
+    int64_t off_ng, ng_floats;       // NG-SGD: preconditioned copies + its own scratch
+    int64_t total_floats;
+};
+
+Workspace make_workspace(const Layout& y, int n, int k, uint32_t flags, int ng_rank) {
+    Workspace w;
+    w.ld_delta = round_up(y.dmax, 4);
+    w.delta_floats = round_up((int64_t)k * n * w.ld_delta, 64);
+    int64_t g = 0;
+    for (int l = 1; l <= y.L; ++l) {
+        int64_t f = gemm_ws_floats(n, y.d[l], y.d[l - 1], k);                  // forward
+        if (f > g) g = f;
+        if (l > 1) { f = gemm_ws_floats(n, y.d[l - 1], y.d[l], k); if (f > g) g = f; }   // back-propagation
+        f = gemm_ws_floats(y.d[l], y.d[l - 1], n, k);                          // weight gradient
+        if (f > g) g = f;
+    }
+    w.gemm_floats = round_up(g, 64);
+    int64_t off = 0;
+    w.off_delta[0] = off; off += w.delta_floats;
+    w.off_delta[1] = off; off += w.delta_floats;
+    w.off_rowloss = off;  off += round_up((int64_t)k * n, 64);
+    w.off_gemm = off;     off += w.gemm_floats;
+    w.off_ng = off;
+    w.ng_floats = (flags & MAVG_USE_NGSGD) ? ng_dnn_ws_floats(y.d, y.L, n, k, ng_rank) : 0;
+    off += w.ng_floats;
+    w.total_floats = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" const char* mavg_version(void) { return "mavg 0.1 (gfx950, fp32 MFMA)"; }
+
+extern "C" int64_t mavg_param_count(const mavg_shape* shape) {
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    return make_layout(shape, 1).P;
+}
+
+extern "C" int64_t mavg_act_count(const mavg_shape* shape, int32_t n) {
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (n < 1) return MAVG_E_DIM;
+    return make_layout(shape, n).acts;
+}
+
+extern "C" int64_t mavg_workspace_bytes(const mavg_shape* shape, int32_t n, int32_t k, uint32_t flags, int32_t ng_rank) {
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (n < 1 || k < 1) return MAVG_E_DIM;
+    if (flags & ~(MAVG_MEAN_GRAD | MAVG_USE_NGSGD)) return MAVG_E_FLAG;
+    if ((flags & MAVG_USE_NGSGD) && (ng_rank < 1 || ng_rank > 64)) return MAVG_E_DIM;
+    const Layout y = make_layout(shape, n);
+    return make_workspace(y, n, k, flags, ng_rank).total_floats * 4 + 256;
+}
+
+static int check_common(const mavg_shape* shape, int32_t k, const void* theta, int64_t theta_stride, const void* x,
+                        int64_t x_stride, int32_t n, const void* acts, int64_t act_stride, Layout* out) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!theta || !x || !acts) return MAVG_E_NULL;
+    if (k < 1 || n < 1) return MAVG_E_DIM;
+    *out = make_layout(shape, n);
+    if (!aligned16(theta) || !aligned16(x) || !aligned16(acts)) return MAVG_E_ALIGN;
+    if (k > 1) {
+        if (theta_stride < out->P || (theta_stride & 3)) return MAVG_E_ALIGN;
+        if (x_stride != 0 && (x_stride < (int64_t)n * out->d[0] || (x_stride & 3))) return MAVG_E_ALIGN;
+        if (act_stride < out->acts || (act_stride & 3)) return MAVG_E_ALIGN;
+    }
+    return MAVG_OK;
+}
+
+static float* ws_base(void* workspace) {
+    return reinterpret_cast<float*>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~uintptr_t(255));
+}
+
+extern "C" int32_t dnn_forward(const mavg_shape* shape, int32_t k, const float* theta, int64_t theta_stride,
+                               const float* x, int64_t x_stride, int32_t n, float* acts, int64_t act_stride,
+                               void* workspace, int64_t workspace_bytes, void* stream) {
+    Layout y;
+    int rc = check_common(shape, k, theta, theta_stride, x, x_stride, n, acts, act_stride, &y);
+    if (rc) return rc;
+    const Workspace w = make_workspace(y, n, k, 0, 0);
+    if (w.total_floats > 0 && (!workspace || workspace_bytes < w.total_floats * 4 + 256)) return MAVG_E_WORKSPACE;
+    float* ws = workspace ? ws_base(workspace) : nullptr;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (int l = 1; l <= y.L; ++l) {
+        GemmDesc g;
+        g.M = n; g.N = y.d[l]; g.K = y.d[l - 1]; g.batch = k;
+        if (l == 1) { g.A = x; g.lda = y.d[0]; g.a_bstride = x_stride; }
+        else { g.A = acts + y.a_off[l - 1]; g.lda = y.d[l - 1]; g.a_bstride = act_stride; }
+        g.a_kc = true;
+        g.B = theta + y.w_off[l]; g.ldb = y.d[l - 1]; g.b_bstride = theta_stride; g.b_kc = true;
+        g.C = acts + y.a_off[l]; g.ldc = y.d[l]; g.c_bstride = act_stride;
+        g.epi.kind = (l < y.L) ? EPI_BIAS_SIGMOID : EPI_BIAS;
+        g.epi.bias = theta + y.b_off[l]; g.epi.bias_bstride = theta_stride;
+        if (gemm_launch(g, ws ? ws + w.off_gemm : nullptr, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    }
+    if (softmax_rows_launch(acts + y.a_off[y.L], y.d[y.L], act_stride, n, y.d[y.L], k, s) != 0) return MAVG_E_LAUNCH;
+    return MAVG_OK;
+}
+
+extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float* theta, int64_t theta_stride,
+                                       const float* x, int64_t x_stride, const int32_t* labels, int64_t label_stride,
+                                       int32_t n, const float* acts, int64_t act_stride, float lr, uint32_t flags,
+                                       void* ng_state, int64_t ng_state_stride, int32_t ng_rank, float ng_alpha,
+                                       float ng_eta, float* loss_sum, void* workspace, int64_t workspace_bytes,
+                                       void* stream) {
+    Layout y;
+    int rc = check_common(shape, k, theta, theta_stride, x, x_stride, n, acts, act_stride, &y);
+    if (rc) return rc;
+    if (!labels) return MAVG_E_NULL;
+    if (flags & ~(MAVG_MEAN_GRAD | MAVG_USE_NGSGD)) return MAVG_E_FLAG;
+    if (k > 1 && label_stride != 0 && label_stride < n) return MAVG_E_ALIGN;
+    const bool ng = (flags & MAVG_USE_NGSGD) != 0;
+    if (ng) {
+        if (!ng_state) return MAVG_E_NULL;
+        if (ng_rank < 1 || ng_rank > 64) return MAVG_E_DIM;
+        for (int l = 1; l <= y.L; ++l)
+            if (ng_rank >= y.d[l] || ng_rank >= y.d[l - 1] + 1) return MAVG_E_DIM;
+        int dm = y.d[0];
+        for (int l = 1; l <= y.L; ++l) if (y.d[l] > dm) dm = y.d[l];
+        if (!aligned16(ng_state) || (ng_state_stride & 15) || ng_state_stride < ngsgd_state_bytes(dm + 1, ng_rank)) return MAVG_E_ALIGN;
+        if (!(ng_alpha > 0.f) || !(ng_eta > 0.f && ng_eta < 1.f)) return MAVG_E_DIM;
+    }
+    const Workspace w = make_workspace(y, n, k, flags, ng_rank);
+    if (!workspace || workspace_bytes < w.total_floats * 4 + 256) return MAVG_E_WORKSPACE;
+    if (!aligned16(labels) || (loss_sum && (reinterpret_cast<uintptr_t>(loss_sum) & 3u))) return MAVG_E_ALIGN;
+    float* ws = ws_base(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* gws = ws + w.off_gemm;
+    float* rowloss = ws + w.off_rowloss;
+    float* dbuf[2] = {ws + w.off_delta[0], ws + w.off_delta[1]};
+    const int64_t ldd = w.ld_delta;
+    const int64_t d_bstride = (int64_t)n * ldd;
+    const float scale = (flags & MAVG_MEAN_GRAD) ? 1.0f / (float)n : 1.0f;
+
+    int cur = 0;
+    if (ce_delta_launch(acts + y.a_off[y.L], y.d[y.L], act_stride, labels, label_stride, dbuf[cur], ldd, d_bstride,
+                        rowloss, n, y.d[y.L], k, scale, s) != 0) return MAVG_E_LAUNCH;
+    if (loss_sum && sum_segments_launch(rowloss, n, k, loss_sum, s) != 0) return MAVG_E_LAUNCH;
+
+    for (int l = y.L; l >= 1; --l) {
+        const float* A_in = (l == 1) ? x : acts + y.a_off[l - 1];
+        const int64_t a_ld = y.d[l - 1];
+        const int64_t a_bs = (l == 1) ? x_stride : act_stride;
+        float* delta = dbuf[cur];
+        if (l > 1) {
+            // delta_{l-1} = (delta_l W_l) * A_{l-1} (1 - A_{l-1}), with W_l as it was in the forward pass
+            GemmDesc g;
+            g.M = n; g.N = y.d[l - 1]; g.K = y.d[l]; g.batch = k;
+            g.A = delta; g.lda = ldd; g.a_bstride = d_bstride; g.a_kc = true;
+            g.B = theta + y.w_off[l]; g.ldb = y.d[l - 1]; g.b_bstride = theta_stride; g.b_kc = false;
+            g.C = dbuf[cur ^ 1]; g.ldc = ldd; g.c_bstride = d_bstride;
+            g.epi.kind = EPI_MUL_DSIGMOID;
+            g.epi.aux = A_in; g.epi.ldaux = a_ld; g.epi.aux_bstride = a_bs;
+            if (gemm_launch(g, gws, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+        }
+        if (!ng) {
+            // W_l <- W_l - lr delta_l^T A_{l-1}
+            GemmDesc g;
+            g.M = y.d[l]; g.N = y.d[l - 1]; g.K = n; g.batch = k;
+            g.A = delta; g.lda = ldd; g.a_bstride = d_bstride; g.a_kc = false;
+            g.B = A_in; g.ldb = a_ld; g.b_bstride = a_bs; g.b_kc = false;
+            g.C = theta + y.w_off[l]; g.ldc = y.d[l - 1]; g.c_bstride = theta_stride;
+            g.epi.kind = EPI_AXPBY; g.epi.alpha = -lr; g.epi.beta = 1.f;
+            if (gemm_launch(g, gws, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+            // b_l <- b_l - lr colsum(delta_l)
+            if (colsum_axpby_launch(delta, ldd, d_bstride, nullptr, 0, 0, theta + y.b_off[l], theta_stride, nullptr, 0, n,
+                                    y.d[l], k, -lr, 1.f, s) != 0) return MAVG_E_LAUNCH;
+        } else {
+            NgLayerArgs a;
+            a.k = k; a.n = n; a.d_in = y.d[l - 1]; a.d_out = y.d[l];
+            a.A_in = A_in; a.a_ld = a_ld; a.a_bstride = a_bs;
+            a.delta = delta; a.ldd = ldd; a.d_bstride = d_bstride;
+            a.W = theta + y.w_off[l]; a.b = theta + y.b_off[l]; a.theta_stride = theta_stride;
+            a.state_in = static_cast<char*>(ng_state) + (int64_t)(2 * (l - 1)) * ng_state_stride;
+            a.state_out = static_cast<char*>(ng_state) + (int64_t)(2 * (l - 1) + 1) * ng_state_stride;
+            a.state_rstride = (int64_t)2 * y.L * ng_state_stride;
+            a.rank = ng_rank; a.alpha = ng_alpha; a.eta = ng_eta; a.lr = lr;
+            a.ws = ws + w.off_ng; a.ws_floats = w.ng_floats;
+            a.gemm_ws = gws; a.gemm_ws_floats = w.gemm_floats;
+            if (ng_layer_update(a, s) != 0) return MAVG_E_LAUNCH;
+        }
+        cur ^= 1;
+    }
+    return MAVG_OK;
+}

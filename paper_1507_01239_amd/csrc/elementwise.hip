@@ -1,0 +1,204 @@
+// Bandwidth/latency-bound kernels around the GEMMs: row softmax, cross-entropy output error,
+// column sums with a fused axpby update, and fixed-order reductions.  No atomics anywhere: every sum
+// has one owner and a fixed order, so results are reproducible bit for bit.
+#include "kernels.h"
+#include "device_math.h"
+
+namespace mavg {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const float r = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ float block_max(float v, float* sh) {
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const float r = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+    __syncthreads();
+    return r;
+}
+
+// ---- softmax -------------------------------------------------------------------------------------
+// One workgroup per row.  A row of up to 256*ITEMS values is held in registers between the three
+// passes (max, sum of exponentials, normalise); longer rows are re-read from memory.
+template <int ITEMS>
+__global__ __launch_bounds__(kThreads) void softmax_rows_kernel(float* z, int64_t ld, int64_t bstride, int cols) {
+    __shared__ float sh[4];
+    float* __restrict__ row = z + (int64_t)blockIdx.y * bstride + (int64_t)blockIdx.x * ld;
+    const int t = threadIdx.x;
+    float v[ITEMS];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int j = t + i * kThreads;
+        v[i] = j < cols ? row[j] : -INFINITY;
+        m = fmaxf(m, v[i]);
+    }
+    m = block_max(m, sh);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        v[i] = expf(v[i] - m);          // exp(-inf) = 0 for the padding
+        s += v[i];
+    }
+    s = block_sum(s, sh);
+    const float inv = 1.f / s;
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int j = t + i * kThreads;
+        if (j < cols) row[j] = v[i] * inv;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void softmax_rows_long_kernel(float* z, int64_t ld, int64_t bstride, int cols) {
+    __shared__ float sh[4];
+    float* __restrict__ row = z + (int64_t)blockIdx.y * bstride + (int64_t)blockIdx.x * ld;
+    float m = -INFINITY;
+    for (int j = threadIdx.x; j < cols; j += kThreads) m = fmaxf(m, row[j]);
+    m = block_max(m, sh);
+    float s = 0.f;
+    for (int j = threadIdx.x; j < cols; j += kThreads) s += expf(row[j] - m);
+    s = block_sum(s, sh);
+    const float inv = 1.f / s;
+    for (int j = threadIdx.x; j < cols; j += kThreads) row[j] = expf(row[j] - m) * inv;
+}
+
+int softmax_rows_launch(float* z, int64_t ld, int64_t bstride, int rows, int cols, int batch, hipStream_t s) {
+    if (rows <= 0 || cols <= 0 || batch <= 0) return 0;
+    dim3 grid((unsigned)rows, (unsigned)batch);
+    if (cols <= kThreads * 4) hipLaunchKernelGGL(softmax_rows_kernel<4>, grid, dim3(kThreads), 0, s, z, ld, bstride, cols);
+    else if (cols <= kThreads * 16) hipLaunchKernelGGL(softmax_rows_kernel<16>, grid, dim3(kThreads), 0, s, z, ld, bstride, cols);
+    else if (cols <= kThreads * 36) hipLaunchKernelGGL(softmax_rows_kernel<36>, grid, dim3(kThreads), 0, s, z, ld, bstride, cols);
+    else hipLaunchKernelGGL(softmax_rows_long_kernel, grid, dim3(kThreads), 0, s, z, ld, bstride, cols);
+    return (int)hipGetLastError();
+}
+
+// ---- cross-entropy output error ------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void ce_delta_kernel(const float* __restrict__ p, int64_t ldp, int64_t p_bstride,
+                                                            const int32_t* __restrict__ labels, int64_t label_bstride,
+                                                            float* __restrict__ delta, int64_t ldd, int64_t d_bstride,
+                                                            float* __restrict__ rowloss, int rows, int cols, float scale) {
+    const int b = blockIdx.z, n = blockIdx.y;
+    const int y = labels[(int64_t)b * label_bstride + n];
+    const float* __restrict__ pr = p + (int64_t)b * p_bstride + (int64_t)n * ldp;
+    float* __restrict__ dr = delta + (int64_t)b * d_bstride + (int64_t)n * ldd;
+    for (int j = blockIdx.x * kThreads + threadIdx.x; j < cols; j += gridDim.x * kThreads) {
+        const float q = pr[j];
+        float d = q;
+        if (j == y) {
+            d = q - 1.f;
+            rowloss[(int64_t)b * rows + n] = -logf(q);
+        }
+        dr[j] = d * scale;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (y < 0 || y >= cols)) rowloss[(int64_t)b * rows + n] = 0.f;
+}
+
+int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride, const int32_t* labels, int64_t label_bstride,
+                    float* delta, int64_t ldd, int64_t d_bstride, float* rowloss, int rows, int cols, int batch,
+                    float scale, hipStream_t s) {
+    if (rows <= 0 || cols <= 0 || batch <= 0) return 0;
+    int gx = (cols + kThreads * 4 - 1) / (kThreads * 4);
+    if (gx < 1) gx = 1;
+    dim3 grid((unsigned)gx, (unsigned)rows, (unsigned)batch);
+    hipLaunchKernelGGL(ce_delta_kernel, grid, dim3(kThreads), 0, s, p, ldp, p_bstride, labels, label_bstride, delta, ldd,
+                       d_bstride, rowloss, rows, cols, scale);
+    return (int)hipGetLastError();
+}
+
+// ---- fixed-order segment sums --------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void sum_segments_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
+    __shared__ float sh[4];
+    const float* __restrict__ seg = v + (int64_t)blockIdx.x * n;
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n; i += kThreads) s += seg[i];
+    s = block_sum(s, sh);
+    if (threadIdx.x == 0) out[blockIdx.x] = s;
+}
+
+int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s) {
+    if (batch <= 0) return 0;
+    hipLaunchKernelGGL(sum_segments_kernel, dim3((unsigned)batch), dim3(kThreads), 0, s, v, n, out);
+    return (int)hipGetLastError();
+}
+
+// ---- column sums with fused update ---------------------------------------------------------------
+// One thread per column, rows summed top to bottom (coalesced across the columns of a wavefront);
+// rows are split over the 4 wavefront-rows of a 64x4 workgroup and combined in a fixed order.
+__global__ __launch_bounds__(kThreads) void colsum_axpby_kernel(const float* __restrict__ X, int64_t ldx, int64_t x_bstride,
+                                                                const float* __restrict__ Y, int64_t ldy, int64_t y_bstride,
+                                                                float* __restrict__ dst, int64_t dst_bstride,
+                                                                float* __restrict__ dst2, int64_t dst2_bstride,
+                                                                int rows, int cols, float alpha, float beta) {
+    __shared__ float sh[4][64];
+    const int b = blockIdx.y;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + tx;
+    float s = 0.f;
+    if (j < cols) {
+        const float* __restrict__ x = X + (int64_t)b * x_bstride + j;
+        const int r0 = (int)(((int64_t)rows * ty) / 4), r1 = (int)(((int64_t)rows * (ty + 1)) / 4);
+        if (Y) {
+            const float* __restrict__ y = Y + (int64_t)b * y_bstride + j;
+            for (int n = r0; n < r1; ++n) s += x[(int64_t)n * ldx] - y[(int64_t)n * ldy];
+        } else {
+            for (int n = r0; n < r1; ++n) s += x[(int64_t)n * ldx];
+        }
+    }
+    sh[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && j < cols) {
+        const float tot = (sh[0][tx] + sh[1][tx]) + (sh[2][tx] + sh[3][tx]);
+        float* d = dst + (int64_t)b * dst_bstride + j;
+        float r = alpha * tot;
+        if (beta != 0.f) r += beta * *d;
+        *d = r;
+        if (dst2) dst2[(int64_t)b * dst2_bstride + j] += r;
+    }
+}
+
+int colsum_axpby_launch(const float* X, int64_t ldx, int64_t x_bstride, const float* Y, int64_t ldy, int64_t y_bstride,
+                        float* dst, int64_t dst_bstride, float* dst2, int64_t dst2_bstride, int rows, int cols, int batch,
+                        float alpha, float beta, hipStream_t s) {
+    if (cols <= 0 || batch <= 0) return 0;
+    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)batch);
+    hipLaunchKernelGGL(colsum_axpby_kernel, grid, dim3(kThreads), 0, s, X, ldx, x_bstride, Y, ldy, y_bstride, dst, dst_bstride,
+                       dst2, dst2_bstride, rows, cols, alpha, beta);
+    return (int)hipGetLastError();
+}
+
+// ---- sum of squared differences ------------------------------------------------------------------
+constexpr int kSqBlocks = 256;
+int sqdiff_partials() { return kSqBlocks; }
+
+__global__ __launch_bounds__(kThreads) void sqdiff_partial_kernel(const float* __restrict__ X, int64_t ldx,
+                                                                  const float* __restrict__ Y, int64_t ldy, int rows, int cols,
+                                                                  float* __restrict__ partial) {
+    __shared__ float sh[4];
+    const int64_t total = (int64_t)rows * cols;
+    float s = 0.f;
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kThreads) {
+        const int64_t n = e / cols, j = e - n * cols;
+        const float d = X[n * ldx + j] - Y[n * ldy + j];
+        s += d * d;
+    }
+    s = block_sum(s, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
+int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, int rows, int cols, float* partial,
+                      float* out, hipStream_t s) {
+    hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(kThreads), 0, s, X, ldx, Y, ldy, rows, cols, partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    return sum_segments_launch(partial, kSqBlocks, 1, out, s);
+}
+
+}  // namespace mavg

@@ -1,0 +1,53 @@
+// Internal C++ interface of the fp32 MFMA GEMM used by every dense contraction of the library.
+// Not part of the C ABI (see include/mavg.h for that).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mavg {
+
+// The library is written for MI355X only: 256 compute units in 8 XCDs.
+constexpr int kNumCU = 256;
+constexpr int kNumXCD = 8;
+
+enum EpiKind : int {
+    EPI_STORE = 0,            // C = v
+    EPI_BIAS = 1,             // C = v + bias[n]
+    EPI_BIAS_SIGMOID = 2,     // C = sigmoid(v + bias[n])
+    EPI_MUL_DSIGMOID = 3,     // C = v * a * (1 - a),  a = aux[m, n]
+    EPI_AXPBY = 4,            // C = beta*C + alpha*v ;  if C2: C2 += C
+    EPI_BIAS_SIGMOID_SAMPLE = 5,  // p = sigmoid(v + bias[n]); if C: C = p;  C2 = [u(m*N+n) < p]
+};
+
+struct Epilogue {
+    int kind = EPI_STORE;
+    const float* bias = nullptr; int64_t bias_bstride = 0;
+    const float* aux = nullptr;  int64_t ldaux = 0; int64_t aux_bstride = 0;
+    float* C2 = nullptr;         int64_t ldc2 = 0;  int64_t c2_bstride = 0;
+    float alpha = 1.f, beta = 0.f;
+    uint32_t key0 = 0, key1 = 0, step = 0, layer = 0, phase = 0;   // Philox stream of the sampling epilogue
+};
+
+// C[b](m,n) = epilogue( sum_k A[b](m,k) * B[b](k,n) ),  b in [0,batch).
+//   a_kc: A(m,k) = A[m*lda + k]  (contraction index contiguous) else A[k*lda + m]
+//   b_kc: B(k,n) = B[n*ldb + k]  else B[k*ldb + n]
+//   C(m,n) = C[m*ldc + n]
+struct GemmDesc {
+    const float* A = nullptr; int64_t lda = 0; int64_t a_bstride = 0; bool a_kc = true;
+    const float* B = nullptr; int64_t ldb = 0; int64_t b_bstride = 0; bool b_kc = true;
+    float* C = nullptr;       int64_t ldc = 0; int64_t c_bstride = 0;
+    int M = 0, N = 0, K = 0, batch = 1;
+    Epilogue epi;
+    int force_cfg = -1;     // -1: choose; otherwise tile configuration index
+    int force_splits = 0;   // 0: choose; otherwise number of contraction splits
+};
+
+struct GemmPlan { int cfg; int splits; int bm, bn; };
+
+GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits);
+// float32 elements of scratch the plan for this problem needs (0 when it is not split)
+int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg = -1, int force_splits = 0);
+// enqueue; returns hipError_t as int (0 = ok).  ws must hold gemm_ws_floats() floats when that is > 0.
+int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t stream);
+
+}  // namespace mavg

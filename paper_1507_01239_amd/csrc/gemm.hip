@@ -1,0 +1,403 @@
+// fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32), LDS-staged and double-buffered, with
+// the fused epilogues the training path needs and a deterministic split of the contraction for
+// problems with too few output tiles to fill 256 compute units.
+//
+// One workgroup = 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN output tile; each
+// wavefront owns (BM/2) x (BN/2) as a grid of 32x32 MFMA accumulators.  Operand tiles are staged
+// in LDS k-major ([k][m] and [k][n]), so a lane's MFMA operand is one ds_read_b32 whose 32 lanes
+// read 32 consecutive floats.
+#include "gemm.h"
+#include "../../include/mavg.h"
+#include "device_math.h"
+#include <utility>
+#include <type_traits>
+
+namespace mavg {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N-1>{}).
+// Used wherever the accumulator arrays are indexed, so that every index is a constant from the start
+// and the accumulators stay in registers.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+struct GemmKParams {
+    const float* A; int64_t lda, a_bstride;
+    const float* B; int64_t ldb, b_bstride;
+    float* C; int64_t ldc, c_bstride;
+    int M, N, K, batch, splits, kper;   // kper: contraction elements per split (multiple of the k tile)
+    int tiles_m, tiles_n;
+    int vecA, vecB;                     // operands may be read with 16-byte loads
+    float* ws;                          // partial sums [batch][split][M][N] when splits > 1
+    Epilogue epi;
+};
+
+// ---- epilogue ------------------------------------------------------------------------------------
+
+struct EpiCtx {       // per-batch resolved pointers
+    const float* bias; const float* aux; float* C; float* C2;
+};
+
+__device__ __forceinline__ EpiCtx epi_ctx(const Epilogue& e, float* C, int64_t c_bstride, int b) {
+    EpiCtx c;
+    c.bias = e.bias ? e.bias + (int64_t)b * e.bias_bstride : nullptr;
+    c.aux = e.aux ? e.aux + (int64_t)b * e.aux_bstride : nullptr;
+    c.C = C ? C + (int64_t)b * c_bstride : nullptr;
+    c.C2 = e.C2 ? e.C2 + (int64_t)b * e.c2_bstride : nullptr;
+    return c;
+}
+
+template <int KIND>
+__device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, int64_t ldc, int N, int m, int n, float v) {
+    if (KIND == EPI_STORE) {
+        c.C[(int64_t)m * ldc + n] = v;
+    } else if (KIND == EPI_BIAS) {
+        c.C[(int64_t)m * ldc + n] = v + c.bias[n];
+    } else if (KIND == EPI_BIAS_SIGMOID) {
+        c.C[(int64_t)m * ldc + n] = sigmoidf_dev(v + c.bias[n]);
+    } else if (KIND == EPI_MUL_DSIGMOID) {
+        const float a = c.aux[(int64_t)m * e.ldaux + n];
+        c.C[(int64_t)m * ldc + n] = v * a * (1.f - a);
+    } else if (KIND == EPI_AXPBY) {
+        const int64_t i = (int64_t)m * ldc + n;
+        float r = e.alpha * v;
+        if (e.beta != 0.f) r += e.beta * c.C[i];
+        c.C[i] = r;
+        if (c.C2) { const int64_t j = (int64_t)m * e.ldc2 + n; c.C2[j] += r; }
+    } else if (KIND == EPI_BIAS_SIGMOID_SAMPLE) {
+        const float p = sigmoidf_dev(v + c.bias[n]);
+        if (c.C) c.C[(int64_t)m * ldc + n] = p;
+        const float u = philox_uniform((uint64_t)m * (uint64_t)N + (uint64_t)n, e.key0, e.key1, e.step, e.layer, e.phase);
+        c.C2[(int64_t)m * e.ldc2 + n] = (u < p) ? 1.f : 0.f;
+    }
+}
+
+// Write a wavefront's accumulators through epilogue KIND.  Accumulator element v of a lane sits at
+// row 8*(v/4) + 4*(lane/32) + v%4, column lane%32 of its 32x32 block.
+template <int KIND, int TM, int TN>
+__device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const Epilogue& e, const EpiCtx& c,
+                                           int64_t ldc, int M, int N, int mbase, int nbase, int lrow, int lcol) {
+    static_for<TM * TN * 16>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        constexpr int i = t / (TN * 16), j = (t / 16) % TN, v = t % 16;
+        const int n = nbase + j * 32 + lcol;
+        const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
+        if (m < M && n < N) epi_apply<KIND>(e, c, ldc, N, m, n, acc[i][j][v]);
+    });
+}
+
+// Apply epilogue `kind` to four consecutive elements of a row (the split-contraction reducer).
+template <int KIND>
+__device__ __forceinline__ void epi_apply4(const Epilogue& e, const EpiCtx& c, int64_t ldc, int N, int m, int n, float4 s) {
+    epi_apply<KIND>(e, c, ldc, N, m, n + 0, s.x);
+    epi_apply<KIND>(e, c, ldc, N, m, n + 1, s.y);
+    epi_apply<KIND>(e, c, ldc, N, m, n + 2, s.z);
+    epi_apply<KIND>(e, c, ldc, N, m, n + 3, s.w);
+}
+
+#define MAVG_EPI_DISPATCH(kind, CALL)                                              \
+    switch (kind) {                                                                \
+    case EPI_STORE: { constexpr int KIND = EPI_STORE; CALL; break; }               \
+    case EPI_BIAS: { constexpr int KIND = EPI_BIAS; CALL; break; }                 \
+    case EPI_BIAS_SIGMOID: { constexpr int KIND = EPI_BIAS_SIGMOID; CALL; break; } \
+    case EPI_MUL_DSIGMOID: { constexpr int KIND = EPI_MUL_DSIGMOID; CALL; break; } \
+    case EPI_AXPBY: { constexpr int KIND = EPI_AXPBY; CALL; break; }               \
+    case EPI_BIAS_SIGMOID_SAMPLE: { constexpr int KIND = EPI_BIAS_SIGMOID_SAMPLE; CALL; break; } \
+    default: break;                                                                \
+    }
+
+// ---- main kernel ---------------------------------------------------------------------------------
+
+constexpr int kPad = 4;
+
+// Global -> register load of one operand tile (BR rows of the non-contracted index by BK contraction
+// steps), zero-filled outside [0,R) x [k0,kend).  KC: the contraction index is the contiguous one.
+template <bool KC, int NLD, int BR, int BK>
+__device__ __forceinline__ void load_operand(const float* __restrict__ P, int64_t ld, int vec, int r0, int R,
+                                             int k0, int kend, int tid, float4 (&reg)[NLD]) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int f = tid + i * 256;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (KC) {
+            const int r = f / (BK / 4), kq = f % (BK / 4);
+            const int gr = r0 + r, gk = k0 + kq * 4;
+            if (gr < R && gk < kend) {
+                const float* src = P + (int64_t)gr * ld + gk;
+                if (vec && gk + 3 < kend) v = *reinterpret_cast<const float4*>(src);
+                else {
+                    v.x = src[0];
+                    if (gk + 1 < kend) v.y = src[1];
+                    if (gk + 2 < kend) v.z = src[2];
+                    if (gk + 3 < kend) v.w = src[3];
+                }
+            }
+        } else {
+            const int k = f / (BR / 4), rq = f % (BR / 4);
+            const int gk = k0 + k, gr = r0 + rq * 4;
+            if (gk < kend && gr < R) {
+                const float* src = P + (int64_t)gk * ld + gr;
+                if (vec && gr + 3 < R) v = *reinterpret_cast<const float4*>(src);
+                else {
+                    v.x = src[0];
+                    if (gr + 1 < R) v.y = src[1];
+                    if (gr + 2 < R) v.z = src[2];
+                    if (gr + 3 < R) v.w = src[3];
+                }
+            }
+        }
+        reg[i] = v;
+    }
+}
+
+// Register -> LDS store of the tile, k-major: S[k][r].
+template <bool KC, int NLD, int BR, int BK, int LDS_LD>
+__device__ __forceinline__ void store_operand(float* S, int tid, const float4 (&reg)[NLD]) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int f = tid + i * 256;
+        if (KC) {
+            const int r = f / (BK / 4), kq = f % (BK / 4);
+            S[(kq * 4 + 0) * LDS_LD + r] = reg[i].x;
+            S[(kq * 4 + 1) * LDS_LD + r] = reg[i].y;
+            S[(kq * 4 + 2) * LDS_LD + r] = reg[i].z;
+            S[(kq * 4 + 3) * LDS_LD + r] = reg[i].w;
+        } else {
+            const int k = f / (BR / 4), rq = f % (BR / 4);
+            *reinterpret_cast<float4*>(&S[k * LDS_LD + rq * 4]) = reg[i];
+        }
+    }
+}
+
+template <int BM, int BN, int BK, bool AKC, bool BKC>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmKParams p) {
+    constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 accumulators per wavefront, each way
+    constexpr int LDAS = BM + kPad, LDBS = BN + kPad;
+    constexpr int A_LD = BM * BK / 4 / 256, B_LD = BN * BK / 4 / 256;   // float4 loads per thread per tile
+    static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for 256 threads");
+    __shared__ __attribute__((aligned(16))) float As[2][BK][LDAS];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDBS];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
+    const int bz = blockIdx.z, b = bz / p.splits, split = bz - b * p.splits;
+    const int tile = blockIdx.x;
+    const int tn_i = tile % p.tiles_n, tm_i = tile / p.tiles_n;
+    const int m0 = tm_i * BM, n0 = tn_i * BN;
+    const int kbeg = split * p.kper;
+    const int kend = min(p.K, kbeg + p.kper);
+    const float* __restrict__ A = p.A + (int64_t)b * p.a_bstride;
+    const float* __restrict__ B = p.B + (int64_t)b * p.b_bstride;
+
+    float4 ra[A_LD], rb[B_LD];
+
+    floatx16 acc[TM][TN];
+    static_for<TM * TN>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        acc[t / TN][t % TN] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    });
+
+    const int nkt = (kend - kbeg + BK - 1) / BK;
+    if (nkt > 0) {
+        load_operand<AKC, A_LD, BM, BK>(A, p.lda, p.vecA, m0, p.M, kbeg, kend, tid, ra);
+        load_operand<BKC, B_LD, BN, BK>(B, p.ldb, p.vecB, n0, p.N, kbeg, kend, tid, rb);
+        store_operand<AKC, A_LD, BM, BK, LDAS>(&As[0][0][0], tid, ra);
+        store_operand<BKC, B_LD, BN, BK, LDBS>(&Bs[0][0][0], tid, rb);
+    }
+    __syncthreads();
+    const int lrow = lane >> 5, lcol = lane & 31;
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nkt) {
+            load_operand<AKC, A_LD, BM, BK>(A, p.lda, p.vecA, m0, p.M, kbeg + (kt + 1) * BK, kend, tid, ra);
+            load_operand<BKC, B_LD, BN, BK>(B, p.ldb, p.vecB, n0, p.N, kbeg + (kt + 1) * BK, kend, tid, rb);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            float a[TM], bb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = As[buf][kk + lrow][wm + i * 32 + lcol];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bb[j] = Bs[buf][kk + lrow][wn + j * 32 + lcol];
+            static_for<TM * TN>([&](auto tc) {
+                constexpr int t = decltype(tc)::value;
+                constexpr int i = t / TN, j = t % TN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], bb[j], acc[i][j], 0, 0, 0);
+            });
+        }
+        if (kt + 1 < nkt) {
+            store_operand<AKC, A_LD, BM, BK, LDAS>(&As[buf ^ 1][0][0], tid, ra);
+            store_operand<BKC, B_LD, BN, BK, LDBS>(&Bs[buf ^ 1][0][0], tid, rb);
+        }
+        __syncthreads();
+    }
+
+    if (p.splits > 1) {
+        Epilogue raw;
+        EpiCtx c;
+        c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr;
+        c.C = p.ws + ((int64_t)bz * p.M) * p.N;
+        write_tile<EPI_STORE, TM, TN>(acc, raw, c, p.N, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol);
+    } else {
+        const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
+        MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, TM, TN>(acc, p.epi, c, p.ldc, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol)))
+    }
+}
+
+// Sum the partial results of a split contraction in split order and apply the epilogue.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
+    const int b = blockIdx.y;
+    const int64_t MN = (int64_t)p.M * p.N;
+    const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
+    const float* __restrict__ W = p.ws + (int64_t)b * p.splits * MN;
+    if ((p.N & 3) == 0) {
+        const int64_t nq = MN >> 2;
+        for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256) {
+            float4 s = *reinterpret_cast<const float4*>(W + q * 4);
+            for (int sp = 1; sp < p.splits; ++sp) {
+                const float4 t = *reinterpret_cast<const float4*>(W + sp * MN + q * 4);
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+            const int64_t e = q * 4;
+            const int m = (int)(e / p.N), n = (int)(e - (int64_t)m * p.N);
+            MAVG_EPI_DISPATCH(p.epi.kind, (epi_apply4<KIND>(p.epi, c, p.ldc, p.N, m, n, s)))
+        }
+    } else {
+        for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < MN; e += (int64_t)gridDim.x * 256) {
+            float s = W[e];
+            for (int sp = 1; sp < p.splits; ++sp) s += W[sp * MN + e];
+            const int m = (int)(e / p.N), n = (int)(e - (int64_t)m * p.N);
+            MAVG_EPI_DISPATCH(p.epi.kind, (epi_apply<KIND>(p.epi, c, p.ldc, p.N, m, n, s)))
+        }
+    }
+}
+
+// ---- host side -----------------------------------------------------------------------------------
+
+struct TileCfg { int bm, bn, bk; };
+static const TileCfg kCfgs[] = {{128, 128, 16}, {64, 64, 16}};
+constexpr int kNumCfgs = 2;
+
+GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
+    GemmPlan pl;
+    int cfg = force_cfg;
+    if (cfg < 0 || cfg >= kNumCfgs) {
+        // big tiles when there are enough of them to occupy the chip, or the problem is large both ways
+        const int64_t big = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
+        cfg = (M > 64 && N > 64 && (big >= 24 || (M >= 512 && N >= 512))) ? 0 : 1;
+    }
+    pl.cfg = cfg;
+    pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
+    const int bk = kCfgs[cfg].bk;
+    const int64_t tiles = (int64_t)((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn) * batch;
+    int splits = force_splits;
+    if (splits <= 0) {
+        splits = 1;
+        if (tiles < kNumCU) {
+            splits = (int)((kNumCU + tiles - 1) / tiles);          // aim at one workgroup per compute unit
+            const int max_by_k = (K + 8 * bk - 1) / (8 * bk);       // keep >= 8 k-tiles per split
+            if (splits > max_by_k) splits = max_by_k;
+            if (splits > 16) splits = 16;
+            if (splits < 1) splits = 1;
+        }
+    }
+    // contraction elements per split, rounded up to the k tile; drop empty trailing splits
+    int kper = ((K + splits - 1) / splits + bk - 1) / bk * bk;
+    if (kper < bk) kper = bk;
+    splits = (K + kper - 1) / kper;
+    if (splits < 1) splits = 1;
+    pl.splits = splits;
+    return pl;
+}
+
+int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg, int force_splits) {
+    const GemmPlan pl = gemm_plan(M, N, K, batch, force_cfg, force_splits);
+    return pl.splits > 1 ? (int64_t)pl.splits * batch * M * N : 0;
+}
+
+template <int BM, int BN, int BK>
+static void launch_cfg(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
+    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, true, true>), grid, dim3(256), 0, s, p);
+    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, true, false>), grid, dim3(256), 0, s, p);
+    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, false, false>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, false, true>), grid, dim3(256), 0, s, p);
+}
+
+static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t stream) {
+    if (d.M <= 0 || d.N <= 0 || d.batch <= 0) return 0;
+    const GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, d.force_splits);
+    GemmKParams p;
+    p.A = d.A; p.lda = d.lda; p.a_bstride = d.a_bstride;
+    p.B = d.B; p.ldb = d.ldb; p.b_bstride = d.b_bstride;
+    p.C = d.C; p.ldc = d.ldc; p.c_bstride = d.c_bstride;
+    p.M = d.M; p.N = d.N; p.K = d.K; p.batch = d.batch;
+    p.splits = pl.splits;
+    const int bk = kCfgs[pl.cfg].bk;
+    int kper = ((d.K + pl.splits - 1) / pl.splits + bk - 1) / bk * bk;
+    if (kper < bk) kper = bk;
+    p.kper = kper;
+    p.tiles_m = (d.M + pl.bm - 1) / pl.bm;
+    p.tiles_n = (d.N + pl.bn - 1) / pl.bn;
+    p.vecA = aligned16(d.A) && (d.lda % 4 == 0) && (d.a_bstride % 4 == 0);
+    p.vecB = aligned16(d.B) && (d.ldb % 4 == 0) && (d.b_bstride % 4 == 0);
+    p.ws = ws;
+    p.epi = d.epi;
+    if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return (int)hipErrorInvalidValue;
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
+    if (pl.cfg == 0) launch_cfg<128, 128, 16>(p, d.a_kc, d.b_kc, grid, stream);
+    else launch_cfg<64, 64, 16>(p, d.a_kc, d.b_kc, grid, stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
+    if (pl.splits > 1) {
+        const int64_t work = ((int64_t)d.M * d.N + 3) / 4;
+        int64_t gx = (work + 255) / 256;
+        if (gx > 4096) gx = 4096;
+        if (gx < 1) gx = 1;
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3((unsigned)gx, (unsigned)d.batch), dim3(256), 0, stream, p);
+        e = hipGetLastError();
+    }
+    return (int)e;
+}
+
+}  // namespace mavg
+
+// ---- exported test/tuning entry points -----------------------------------------------------------
+using namespace mavg;
+
+extern "C" int64_t mavg_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t cfg, int32_t splits) {
+    if (m < 1 || n < 1 || k < 0) return MAVG_E_DIM;
+    if (cfg >= kNumCfgs || splits < 0) return MAVG_E_FLAG;
+    return gemm_ws_floats(m, n, k, 1, cfg, splits) * 4 + 256;
+}
+
+extern "C" int32_t mavg_gemm(const float* a, int64_t lda, int32_t a_kc, const float* b, int64_t ldb, int32_t b_kc,
+                             float* c, int64_t ldc, int32_t m, int32_t n, int32_t k, int32_t epi, const float* bias,
+                             const float* aux, int64_t ldaux, float alpha, float beta, int32_t cfg, int32_t splits,
+                             void* workspace, int64_t workspace_bytes, void* stream) {
+    if (!a || !b || !c) return MAVG_E_NULL;
+    if (m < 1 || n < 1 || k < 0) return MAVG_E_DIM;
+    if (cfg >= kNumCfgs || splits < 0 || epi < EPI_STORE || epi > EPI_AXPBY) return MAVG_E_FLAG;
+    if ((epi == EPI_BIAS || epi == EPI_BIAS_SIGMOID) && !bias) return MAVG_E_NULL;
+    if (epi == EPI_MUL_DSIGMOID && !aux) return MAVG_E_NULL;
+    if (lda < (a_kc ? k : m) || ldb < (b_kc ? k : n) || ldc < n || (epi == EPI_MUL_DSIGMOID && ldaux < n)) return MAVG_E_ALIGN;
+    const int64_t need = gemm_ws_floats(m, n, k, 1, cfg, splits);
+    if (need > 0 && (!workspace || workspace_bytes < need * 4 + 256)) return MAVG_E_WORKSPACE;
+    GemmDesc g;
+    g.A = a; g.lda = lda; g.a_kc = a_kc != 0;
+    g.B = b; g.ldb = ldb; g.b_kc = b_kc != 0;
+    g.C = c; g.ldc = ldc;
+    g.M = m; g.N = n; g.K = k;
+    g.epi.kind = epi; g.epi.bias = bias; g.epi.aux = aux; g.epi.ldaux = ldaux; g.epi.alpha = alpha; g.epi.beta = beta;
+    g.force_cfg = cfg; g.force_splits = splits;
+    float* ws = workspace ? reinterpret_cast<float*>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~uintptr_t(255)) : nullptr;
+    return gemm_launch(g, ws, need, static_cast<hipStream_t>(stream)) == 0 ? MAVG_OK : MAVG_E_LAUNCH;
+}

@@ -1,0 +1,32 @@
+// Internal launchers of the non-GEMM kernels (softmax, cross-entropy error, column sums, reductions).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mavg {
+
+// rows x cols matrix z (row stride ld), batch b at z + b*bstride: z <- softmax of each row (max-subtracted).
+int softmax_rows_launch(float* z, int64_t ld, int64_t bstride, int rows, int cols, int batch, hipStream_t s);
+
+// delta[b](n,j) = scale * (p[b](n,j) - [j == labels[b][n]]);  rowloss[b][n] = -log p[b](n, labels[b][n]).
+int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride,
+                    const int32_t* labels, int64_t label_bstride,
+                    float* delta, int64_t ldd, int64_t d_bstride,
+                    float* rowloss, int rows, int cols, int batch, float scale, hipStream_t s);
+
+// out[b] = sum_{i<n} v[b*n + i], summed in a fixed order (one workgroup per b).
+int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s);
+
+// dst[b][j] = beta*dst[b][j] + alpha * sum_{n<rows} (X[b](n,j) - Y[b](n,j))   (Y may be null);
+// if dst2: dst2[b][j] += dst[b][j].
+int colsum_axpby_launch(const float* X, int64_t ldx, int64_t x_bstride,
+                        const float* Y, int64_t ldy, int64_t y_bstride,
+                        float* dst, int64_t dst_bstride, float* dst2, int64_t dst2_bstride,
+                        int rows, int cols, int batch, float alpha, float beta, hipStream_t s);
+
+// out[0] = sum over rows x cols of (X - Y)^2, fixed order; partial: scratch of >= sqdiff_partials() floats.
+int sqdiff_partials();
+int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, int rows, int cols,
+                      float* partial, float* out, hipStream_t s);
+
+}  // namespace mavg

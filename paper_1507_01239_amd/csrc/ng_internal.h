@@ -1,0 +1,25 @@
+// Internal interface between the DNN update and the NG-SGD preconditioner.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mavg {
+
+// One layer's preconditioned weight/bias update for k replicas (replica = batch index).
+struct NgLayerArgs {
+    int k, n, d_in, d_out;
+    const float* A_in; int64_t a_ld, a_bstride;        // n x d_in input activations
+    const float* delta; int64_t ldd, d_bstride;        // n x d_out output derivatives
+    float* W; float* b; int64_t theta_stride;          // d_out x d_in weights, d_out biases
+    char* state_in; char* state_out; int64_t state_rstride;   // replica r's states at + r*state_rstride bytes
+    int rank; float alpha, eta, lr;
+    float* ws; int64_t ws_floats;
+    float* gemm_ws; int64_t gemm_ws_floats;
+};
+
+// float32 elements of scratch ng_layer_update needs for the widest layer of the network
+int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank);
+// returns 0 or a hipError_t
+int ng_layer_update(const NgLayerArgs& a, hipStream_t s);
+
+}  // namespace mavg

@@ -1,0 +1,161 @@
+// rbm_cd1_step: one CD-1 minibatch update of an RBM.  Three affine GEMMs (hidden probabilities with
+// the Bernoulli sampling fused into the epilogue, reconstruction, hidden probabilities of the
+// reconstruction), two statistics GEMMs fused with the momentum update, two column-sum kernels for the
+// biases, and a fixed-order reduction for the reconstruction error.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/mavg.h"
+#include "gemm.h"
+#include "kernels.h"
+
+using namespace mavg;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct RbmWs {
+    int64_t ldh, ldv;
+    int64_t off_ph0, off_h0, off_v1, off_ph1, off_part, off_gemm, gemm_floats, total;
+};
+
+RbmWs rbm_ws(int V, int H, int n) {
+    RbmWs w;
+    w.ldh = round_up(H, 4);
+    w.ldv = round_up(V, 4);
+    int64_t g = gemm_ws_floats(n, H, V, 1), f;
+    f = gemm_ws_floats(n, V, H, 1); if (f > g) g = f;
+    f = gemm_ws_floats(H, V, n, 1); if (f > g) g = f;
+    w.gemm_floats = round_up(g, 64);
+    int64_t off = 0;
+    w.off_ph0 = off; off += round_up((int64_t)n * w.ldh, 64);
+    w.off_h0 = off;  off += round_up((int64_t)n * w.ldh, 64);
+    w.off_ph1 = off; off += round_up((int64_t)n * w.ldh, 64);
+    w.off_v1 = off;  off += round_up((int64_t)n * w.ldv, 64);
+    w.off_part = off; off += round_up(sqdiff_partials(), 64);
+    w.off_gemm = off; off += w.gemm_floats;
+    w.total = off;
+    return w;
+}
+
+float* ws_base(void* workspace) {
+    return reinterpret_cast<float*>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~uintptr_t(255));
+}
+
+}  // namespace
+
+extern "C" int64_t rbm_workspace_bytes(int32_t n_vis, int32_t n_hid, int32_t n) {
+    if (n_vis < 1 || n_hid < 1 || n < 1) return MAVG_E_DIM;
+    return rbm_ws(n_vis, n_hid, n).total * 4 + 256;
+}
+
+extern "C" int32_t rbm_hidden_prob(int32_t n_vis, int32_t n_hid, const float* w, const float* c, const float* v,
+                                   int32_t n, float* out, void* workspace, int64_t workspace_bytes, void* stream) {
+    if (!w || !c || !v || !out) return MAVG_E_NULL;
+    if (n_vis < 1 || n_hid < 1 || n < 1) return MAVG_E_DIM;
+    if (!aligned16(w) || !aligned16(c) || !aligned16(v) || !aligned16(out)) return MAVG_E_ALIGN;
+    const RbmWs lay = rbm_ws(n_vis, n_hid, n);
+    if (!workspace || workspace_bytes < lay.total * 4 + 256) return MAVG_E_WORKSPACE;
+    float* ws = ws_base(workspace);
+    GemmDesc g;
+    g.M = n; g.N = n_hid; g.K = n_vis;
+    g.A = v; g.lda = n_vis; g.a_kc = true;
+    g.B = w; g.ldb = n_vis; g.b_kc = true;
+    g.C = out; g.ldc = n_hid;
+    g.epi.kind = EPI_BIAS_SIGMOID; g.epi.bias = c;
+    if (gemm_launch(g, ws + lay.off_gemm, lay.gemm_floats, static_cast<hipStream_t>(stream)) != 0) return MAVG_E_LAUNCH;
+    return MAVG_OK;
+}
+
+extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w, float* a, float* c, float* mw,
+                                float* ma, float* mc, const float* v0, int32_t n, float lr, float momentum,
+                                uint64_t seed, uint32_t step, uint32_t layer, uint32_t flags, float* recon_err,
+                                float* dbg_ph0, float* dbg_h0, float* dbg_v1, void* workspace, int64_t workspace_bytes,
+                                void* stream) {
+    if (!w || !a || !c || !mw || !ma || !mc || !v0) return MAVG_E_NULL;
+    if (V < 1 || H < 1 || n < 1) return MAVG_E_DIM;
+    if (vis_type != MAVG_VIS_BERNOULLI && vis_type != MAVG_VIS_GAUSSIAN) return MAVG_E_FLAG;
+    if (flags & ~MAVG_SAMPLE_V1) return MAVG_E_FLAG;
+    if ((flags & MAVG_SAMPLE_V1) && vis_type == MAVG_VIS_GAUSSIAN) return MAVG_E_FLAG;
+    if (!aligned16(w) || !aligned16(a) || !aligned16(c) || !aligned16(mw) || !aligned16(ma) || !aligned16(mc) ||
+        !aligned16(v0))
+        return MAVG_E_ALIGN;
+    const RbmWs lay = rbm_ws(V, H, n);
+    if (!workspace || workspace_bytes < lay.total * 4 + 256) return MAVG_E_WORKSPACE;
+    float* ws = ws_base(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* ph0 = ws + lay.off_ph0;
+    float* h0 = ws + lay.off_h0;
+    float* ph1 = ws + lay.off_ph1;
+    float* v1 = ws + lay.off_v1;
+    float* gws = ws + lay.off_gemm;
+    const uint32_t k0 = (uint32_t)(seed & 0xFFFFFFFFu), k1 = (uint32_t)(seed >> 32);
+    const float invn = 1.0f / (float)n;
+
+    {   // P_h0 = sigmoid(V0 W^T + c), H0 = [u < P_h0]
+        GemmDesc g;
+        g.M = n; g.N = H; g.K = V;
+        g.A = v0; g.lda = V; g.a_kc = true;
+        g.B = w; g.ldb = V; g.b_kc = true;
+        g.C = ph0; g.ldc = lay.ldh;
+        g.epi.kind = EPI_BIAS_SIGMOID_SAMPLE; g.epi.bias = c;
+        g.epi.C2 = h0; g.epi.ldc2 = lay.ldh;
+        g.epi.key0 = k0; g.epi.key1 = k1; g.epi.step = step; g.epi.layer = layer; g.epi.phase = 0;
+        if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    }
+    {   // V1 from H0 W + a
+        GemmDesc g;
+        g.M = n; g.N = V; g.K = H;
+        g.A = h0; g.lda = lay.ldh; g.a_kc = true;
+        g.B = w; g.ldb = V; g.b_kc = false;
+        g.C = v1; g.ldc = lay.ldv;
+        g.epi.bias = a;
+        if (vis_type == MAVG_VIS_GAUSSIAN) g.epi.kind = EPI_BIAS;
+        else if (!(flags & MAVG_SAMPLE_V1)) g.epi.kind = EPI_BIAS_SIGMOID;
+        else {
+            g.epi.kind = EPI_BIAS_SIGMOID_SAMPLE;
+            g.C = nullptr;
+            g.epi.C2 = v1; g.epi.ldc2 = lay.ldv;
+            g.epi.key0 = k0; g.epi.key1 = k1; g.epi.step = step; g.epi.layer = layer; g.epi.phase = 1;
+        }
+        if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    }
+    {   // P_h1 = sigmoid(V1 W^T + c)
+        GemmDesc g;
+        g.M = n; g.N = H; g.K = V;
+        g.A = v1; g.lda = lay.ldv; g.a_kc = true;
+        g.B = w; g.ldb = V; g.b_kc = true;
+        g.C = ph1; g.ldc = lay.ldh;
+        g.epi.kind = EPI_BIAS_SIGMOID; g.epi.bias = c;
+        if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    }
+    if (dbg_ph0 && hipMemcpy2DAsync(dbg_ph0, (size_t)H * 4, ph0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s) != hipSuccess) return MAVG_E_LAUNCH;
+    if (dbg_h0 && hipMemcpy2DAsync(dbg_h0, (size_t)H * 4, h0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s) != hipSuccess) return MAVG_E_LAUNCH;
+    if (dbg_v1 && hipMemcpy2DAsync(dbg_v1, (size_t)V * 4, v1, (size_t)lay.ldv * 4, (size_t)V * 4, n, hipMemcpyDeviceToDevice, s) != hipSuccess) return MAVG_E_LAUNCH;
+    if (recon_err && sqdiff_sum_launch(v0, V, v1, lay.ldv, n, V, ws + lay.off_part, recon_err, s) != 0) return MAVG_E_LAUNCH;
+    {   // MW <- momentum MW + (lr/n) P_h0^T V0
+        GemmDesc g;
+        g.M = H; g.N = V; g.K = n;
+        g.A = ph0; g.lda = lay.ldh; g.a_kc = false;
+        g.B = v0; g.ldb = V; g.b_kc = false;
+        g.C = mw; g.ldc = V;
+        g.epi.kind = EPI_AXPBY; g.epi.alpha = lr * invn; g.epi.beta = momentum;
+        if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    }
+    {   // MW <- MW - (lr/n) P_h1^T V1 ;  W <- W + MW
+        GemmDesc g;
+        g.M = H; g.N = V; g.K = n;
+        g.A = ph1; g.lda = lay.ldh; g.a_kc = false;
+        g.B = v1; g.ldb = lay.ldv; g.b_kc = false;
+        g.C = mw; g.ldc = V;
+        g.epi.kind = EPI_AXPBY; g.epi.alpha = -lr * invn; g.epi.beta = 1.f;
+        g.epi.C2 = w; g.epi.ldc2 = V;
+        if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    }
+    // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma      (and the same for c with P_h0 - P_h1)
+    if (colsum_axpby_launch(v0, V, 0, v1, lay.ldv, 0, ma, 0, a, 0, n, V, 1, lr * invn, momentum, s) != 0) return MAVG_E_LAUNCH;
+    if (colsum_axpby_launch(ph0, lay.ldh, 0, ph1, lay.ldh, 0, mc, 0, c, 0, n, H, 1, lr * invn, momentum, s) != 0) return MAVG_E_LAUNCH;
+    return MAVG_OK;
+}

@@ -1,0 +1,222 @@
+"""GPU parity of dnn_forward / dnn_backward_update (+ replicas_average) against the float64 oracle.
+
+Tolerances are those fixed for this build: per-step activations and gradients 1e-4 relative
+(norm-wise per tensor), parameters after 50 steps 1e-3 relative, averaged parameters 1e-6 relative."""
+import numpy as np
+import pytest
+
+import gen
+from oracle import averaging, dnn
+from tests.util import dev, host, rel_err, workspace
+
+pytestmark = pytest.mark.gpu
+
+ACT_TOL, GRAD_TOL, PARAM_TOL = 1e-4, 1e-4, 1e-3
+
+
+class Gpu:
+    """k replicas of one network on the device, driven through the C ABI."""
+
+    def __init__(self, dims, k, n, theta0, flags=None):
+        import torch
+        from paper_1507_01239_amd import binding as B
+        self.B, self.torch = B, torch
+        self.dims, self.k, self.n = dims, k, n
+        self.shape = B.Shape(dims)
+        self.P = B.mavg_param_count(self.shape)
+        self.stride = (self.P + 63) // 64 * 64
+        self.act_stride = (B.mavg_act_count(self.shape, n) + 63) // 64 * 64
+        self.flags = B.MEAN_GRAD if flags is None else flags
+        self.theta = torch.zeros(k, self.stride, device="cuda")
+        self.theta[:, :self.P] = dev(theta0)[None, :]
+        self.acts = torch.empty(k, self.act_stride, device="cuda")
+        self.ws = workspace(B.mavg_workspace_bytes(self.shape, n, k, self.flags))
+        self.loss = torch.zeros(k, device="cuda")
+
+    def forward(self, X):
+        """X: k x n x d0 numpy."""
+        self.x = dev(X.reshape(self.k, -1))
+        self.B.dnn_forward(self.shape, self.k, self.theta, self.stride, self.x, self.x.shape[1], self.n, self.acts,
+                           self.act_stride, self.ws)
+
+    def backward(self, Y, lr):
+        self.y = dev(Y.reshape(self.k, -1).astype(np.int32))
+        self.B.dnn_backward_update(self.shape, self.k, self.theta, self.stride, self.x, self.x.shape[1], self.y,
+                                   self.y.shape[1], self.n, self.acts, self.act_stride, lr, self.flags, self.loss, self.ws)
+
+    def step(self, X, Y, lr):
+        self.forward(X)
+        self.backward(Y, lr)
+
+    def average(self):
+        self.B.replicas_average(self.theta, self.stride, self.P, self.k)
+
+    def params(self):
+        self.torch.cuda.synchronize()
+        return host(self.theta[:, :self.P])
+
+    def activations(self, r=0):
+        self.torch.cuda.synchronize()
+        a = host(self.acts[r])
+        out, off = [], 0
+        for d in self.dims[1:]:
+            out.append(a[off:off + self.n * d].reshape(self.n, d))
+            off += self.n * d
+        return out
+
+
+def _tiny_shards(seed, K, T, n, dims):
+    return [[(gen.features_iid(n, dims[0], seed, k, t), gen.labels_uniform(n, dims[-1], seed, k, t))
+             for t in range(T)] for k in range(K)]
+
+
+def test_config1_tiny_four_replicas_averaged_every_two():
+    # 40-64-64-32, minibatch 32, lr 0.1, 4 replicas, averaging every 2 minibatches, 8 minibatches per replica
+    dims, K, T, n, lr, n_avg, seed = gen.CONFIG_TINY_DIMS, 4, 8, 32, 0.1, 2, 7
+    theta0 = gen.init_theta(dims, seed, 0.1)
+    shards = _tiny_shards(seed, K, T, n, dims)
+    trace = []
+    ref_thetas, ref_losses = averaging.train_with_averaging(theta0, dims, shards, lr, n_avg, trace=trace)
+    g = Gpu(dims, K, n, theta0)
+    for t in range(T):
+        X = np.stack([shards[k][t][0] for k in range(K)])
+        Y = np.stack([shards[k][t][1] for k in range(K)])
+        g.forward(X)
+        if t == 0:
+            acts_ref = dnn.forward(theta0, dims, X[2])
+            for a_gpu, a_ref in zip(g.activations(2), acts_ref):
+                assert rel_err(a_gpu, a_ref) < ACT_TOL
+        g.backward(Y, lr)
+        losses = host(g.loss)
+        assert np.allclose(losses, ref_losses[:, t], rtol=1e-4)
+        if (t + 1) % n_avg == 0:
+            g.average()
+        assert rel_err(g.params(), trace[t]) < PARAM_TOL
+    th = g.params()
+    assert rel_err(th, ref_thetas) < PARAM_TOL
+    assert all(np.array_equal(th[0], th[r]) for r in range(K))     # every replica holds the average
+
+
+def test_averaging_every_update_equals_gradient_averaging_on_gpu():
+    # Sec. 3: K replicas, one step each on its own shard, then averaging == one step on the concatenated batch
+    dims, K, n, lr, seed = gen.CONFIG_TINY_DIMS, 4, 32, 0.1, 9
+    theta0 = gen.init_theta(dims, seed, 0.1)
+    shards = _tiny_shards(seed, K, 1, n, dims)
+    X = np.stack([shards[k][0][0] for k in range(K)])
+    Y = np.stack([shards[k][0][1] for k in range(K)])
+    g = Gpu(dims, K, n, theta0)
+    g.step(X, Y, lr)
+    g.average()
+    one = Gpu(dims, 1, K * n, theta0)
+    one.step(X.reshape(1, K * n, -1), Y.reshape(1, -1), lr)
+    assert rel_err(g.params()[0], one.params()[0]) < 1e-6
+
+
+@pytest.mark.parametrize("mean", [True, False])
+def test_per_step_gradient_and_activations_tiny_ragged(mean):
+    # widths and minibatch that are not multiples of any tile, incl. an odd output layer
+    dims, n = (44, 72, 36, 52), 37
+    rng = np.random.default_rng(3)
+    theta0 = (rng.standard_normal(gen.param_count(dims)) * 0.3).astype(np.float32)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    from paper_1507_01239_amd import binding as B
+    g = Gpu(dims, 1, n, theta0, flags=B.MEAN_GRAD if mean else 0)
+    lr = 4.0 if mean else 0.125
+    g.step(X[None], y[None], lr)
+    acts_ref = dnn.forward(theta0, dims, X)
+    for a_gpu, a_ref in zip(g.activations(0), acts_ref):
+        assert rel_err(a_gpu, a_ref) < ACT_TOL
+    grad_ref, loss_ref = dnn.gradient(theta0, dims, X, y, mean_grad=mean)
+    grad_gpu = (theta0.astype(np.float64) - g.params()[0].astype(np.float64)) / lr
+    for (Wg, bg), (Wr, br) in zip(dnn.unpack(grad_gpu, dims), dnn.unpack(grad_ref, dims)):
+        assert rel_err(Wg, Wr) < GRAD_TOL
+        assert rel_err(bg, br) < GRAD_TOL
+    assert abs(host(g.loss)[0] - loss_ref) < 1e-4 * abs(loss_ref)
+
+
+def test_unaligned_widths_paper_like_output():
+    # widths that are not multiples of 4 anywhere (the paper's own output layer has 8806 units)
+    dims, n = (10, 13, 7, 9), 5
+    rng = np.random.default_rng(4)
+    theta0 = (rng.standard_normal(gen.param_count(dims)) * 0.4).astype(np.float32)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    g = Gpu(dims, 1, n, theta0)
+    g.step(X[None], y[None], 2.0)
+    ref, _, acts_ref = dnn.sgd_step(theta0, dims, X, y, 2.0)
+    for a_gpu, a_ref in zip(g.activations(0), acts_ref):
+        assert rel_err(a_gpu, a_ref) < ACT_TOL
+    assert rel_err(g.params()[0], ref) < 1e-5
+
+
+def test_zero_learning_rate_leaves_parameters_bit_identical():
+    dims, n = gen.CONFIG_TINY_DIMS, 32
+    theta0 = gen.init_theta(dims, 1, 0.1)
+    g = Gpu(dims, 2, n, theta0)
+    X = np.stack([gen.features_iid(n, 40, 1, k, 0) for k in range(2)])
+    Y = np.stack([gen.labels_uniform(n, 32, 1, k, 0) for k in range(2)])
+    g.step(X, Y, 0.0)
+    assert np.array_equal(g.params()[0], theta0) and np.array_equal(g.params()[1], theta0)
+
+
+def _full_batch(seed, replica, t, n):
+    dims = gen.CONFIG_FULL_DIMS
+    return (gen.features_speech_like(n, dims[0], seed, replica, t), gen.labels_zipf(n, dims[-1], seed, replica, t))
+
+
+def test_config2_full_size_fifty_steps():
+    # 440-6x2048-8000, minibatch 256, lr 0.008, mean gradient: activations and gradient of the first step,
+    # parameters after 50 steps
+    dims, n, lr, seed, T = gen.CONFIG_FULL_DIMS, 256, 0.008, 21, 50
+    theta0 = gen.init_theta(dims, seed, 0.05)
+    g = Gpu(dims, 1, n, theta0)
+    ref = theta0.astype(np.float64)
+    for t in range(T):
+        X, y = _full_batch(seed, 0, t, n)
+        g.forward(X[None])
+        if t in (0, T - 1):
+            acts_ref = dnn.forward(ref, dims, X)
+            for a_gpu, a_ref in zip(g.activations(0), acts_ref):
+                assert rel_err(a_gpu, a_ref) < (ACT_TOL if t == 0 else PARAM_TOL)
+        g.backward(y[None], lr)
+        ref, loss_ref, _ = dnn.sgd_step(ref, dims, X, y, lr)
+        if t in (0, T - 1):
+            assert abs(host(g.loss)[0] - loss_ref) < 1e-3 * abs(loss_ref)
+    th = g.params()[0]
+    assert rel_err(th, ref) < PARAM_TOL
+    for (Wg, bg), (Wr, br) in zip(dnn.unpack(th.astype(np.float64), dims), dnn.unpack(ref, dims)):
+        assert rel_err(Wg, Wr) < PARAM_TOL and rel_err(bg - 0.0, br) < 5e-3
+
+
+def test_full_size_first_step_gradient():
+    dims, n, seed = gen.CONFIG_FULL_DIMS, 256, 22
+    theta0 = gen.init_theta(dims, seed, 0.05)
+    X, y = _full_batch(seed, 0, 0, n)
+    lr = 16.0       # a power of two large enough that (theta - theta')/lr resolves the gradient in float32
+    g = Gpu(dims, 1, n, theta0)
+    g.step(X[None], y[None], lr)
+    grad_ref, _ = dnn.gradient(theta0, dims, X, y, mean_grad=True)
+    grad_gpu = (theta0.astype(np.float64) - g.params()[0].astype(np.float64)) / lr
+    for (Wg, bg), (Wr, br) in zip(dnn.unpack(grad_gpu, dims), dnn.unpack(grad_ref, dims)):
+        assert rel_err(Wg, Wr) < GRAD_TOL
+        assert rel_err(bg, br) < GRAD_TOL
+
+
+def test_config3_eight_full_size_replicas_two_averaging_periods():
+    # 8 replicas resident on the device, each on its own shard, averaged every 2 minibatches (minibatch 128)
+    dims, K, n, lr, n_avg, seed, T = gen.CONFIG_FULL_DIMS, 8, 128, 0.008, 2, 23, 4
+    theta0 = gen.init_theta(dims, seed, 0.05)
+    shards = [[_full_batch(seed, k, t, n) for t in range(T)] for k in range(K)]
+    ref, ref_losses = averaging.train_with_averaging(theta0, dims, shards, lr, n_avg)
+    g = Gpu(dims, K, n, theta0)
+    for t in range(T):
+        X = np.stack([shards[k][t][0] for k in range(K)])
+        Y = np.stack([shards[k][t][1] for k in range(K)])
+        g.step(X, Y, lr)
+        assert np.allclose(host(g.loss), ref_losses[:, t], rtol=1e-3)
+        if (t + 1) % n_avg == 0:
+            g.average()
+    th = g.params()
+    assert rel_err(th[0], ref[0]) < PARAM_TOL
+    assert all(np.array_equal(th[0], th[r]) for r in range(1, K))

@@ -1,0 +1,94 @@
+"""GPU parity of the MFMA GEMM (all three operand layouts, both tile shapes, split contraction, every
+epilogue, ragged sizes) against float64 NumPy products of the same float32 inputs."""
+import numpy as np
+import pytest
+
+from tests.util import dev, host, rel_err, workspace
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(m, n, k, a_kc, b_kc, epi=0, cfg=-1, splits=0, seed=0, pad=0, alpha=1.0, beta=0.0):
+    import torch
+    from paper_1507_01239_amd import binding as B
+    rng = np.random.default_rng(seed)
+    A = rng.standard_normal((m, k)).astype(np.float32)
+    Bm = rng.standard_normal((k, n)).astype(np.float32)
+    lda = (k if a_kc else m) + pad
+    ldb = (k if b_kc else n) + pad
+    ldc = n + pad
+    a_st = np.zeros((m if a_kc else k, lda), np.float32)
+    b_st = np.zeros((n if b_kc else k, ldb), np.float32)
+    if a_kc: a_st[:, :k] = A
+    else: a_st[:, :m] = A.T
+    if b_kc: b_st[:, :k] = Bm.T
+    else: b_st[:, :n] = Bm
+    bias = rng.standard_normal(n).astype(np.float32)
+    aux = rng.random((m, n)).astype(np.float32)
+    c0 = rng.standard_normal((m, ldc)).astype(np.float32)
+    c = dev(c0)
+    ws = workspace(B.mavg_gemm_workspace_bytes(m, n, k, cfg, splits))
+    B.mavg_gemm(dev(a_st), lda, a_kc, dev(b_st), ldb, b_kc, c, ldc, m, n, k, epi, dev(bias), dev(aux), n, alpha, beta,
+                cfg, splits, ws)
+    torch.cuda.synchronize()
+    got = host(c)
+    v = A.astype(np.float64) @ Bm.astype(np.float64)
+    if epi == 1: ref = v + bias
+    elif epi == 2: ref = 1 / (1 + np.exp(-(v + bias)))
+    elif epi == 3: ref = v * aux * (1.0 - aux)
+    elif epi == 4: ref = beta * c0[:, :n].astype(np.float64) + alpha * v
+    else: ref = v
+    if pad:
+        assert np.array_equal(got[:, n:], c0[:, n:])     # nothing written outside the n columns
+    return rel_err(got[:, :n], ref)
+
+
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_layouts_and_tiles(a_kc, b_kc, cfg):
+    # several tiles each way plus ragged tails in m, n and k
+    assert _run(200, 328, 148, a_kc, b_kc, cfg=cfg, seed=1) < 2e-6
+    assert _run(129, 65, 33, a_kc, b_kc, cfg=cfg, seed=2, pad=4) < 2e-6
+
+
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("splits", [1, 3])
+def test_epilogues_with_and_without_split(epi, splits):
+    assert _run(96, 160, 200, 1, 1, epi=epi, splits=splits, seed=3, alpha=-0.5, beta=1.0) < 3e-6
+    assert _run(70, 132, 260, 0, 0, epi=epi, cfg=1, splits=splits, seed=4, alpha=0.25, beta=0.5) < 3e-6
+
+
+def test_unaligned_operands_use_the_scalar_path():
+    # leading dimensions that are not multiples of 4 (e.g. the paper's 8806-wide output layer)
+    assert _run(37, 45, 51, 1, 1, seed=5, pad=1) < 2e-6
+    assert _run(37, 46, 50, 1, 0, seed=6, pad=2) < 2e-6
+    assert _run(38, 45, 53, 0, 0, seed=7, pad=3) < 2e-6
+
+
+def test_degenerate_sizes():
+    assert _run(1, 1, 1, 1, 1, seed=8) < 1e-6
+    assert _run(3, 2, 5, 0, 0, seed=9, splits=4) < 1e-6      # more splits asked for than k tiles exist
+    assert _run(64, 64, 16, 1, 0, seed=10) < 1e-6
+
+
+def test_training_shapes_auto_plan():
+    # the full-size layer shapes at minibatch 256 (forward, back-propagation, weight gradient)
+    assert _run(256, 2048, 440, 1, 1, epi=2, seed=11) < 3e-6
+    assert _run(256, 2048, 2048, 1, 0, epi=3, seed=12) < 3e-6
+    assert _run(2048, 440, 256, 0, 0, epi=4, alpha=-0.008, beta=1.0, seed=13) < 3e-6
+    assert _run(256, 8000, 2048, 1, 1, epi=1, seed=14) < 3e-6
+
+
+def test_runs_are_bitwise_reproducible():
+    import torch
+    from paper_1507_01239_amd import binding as B
+    rng = np.random.default_rng(0)
+    a, b = dev(rng.standard_normal((256, 2048)).astype(np.float32)), dev(rng.standard_normal((512, 2048)).astype(np.float32))
+    outs = []
+    for _ in range(2):
+        c = torch.empty(256, 512, device="cuda")
+        ws = workspace(B.mavg_gemm_workspace_bytes(256, 512, 2048, -1, 0))
+        B.mavg_gemm(a, 2048, 1, b, 2048, 1, c, 512, 256, 512, 2048, 0, None, None, 0, 1.0, 0.0, -1, 0, ws)
+        torch.cuda.synchronize()
+        outs.append(host(c))
+    assert np.array_equal(outs[0], outs[1])
