@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the training hot path on one MI355X.
+
+A step = dnn_forward + dnn_backward_update (fused SGD update) on one 256-frame minibatch of the
+440-6x2048-8000 sigmoid/softmax DNN, fp32, synthetic speech-shaped inputs already resident in HBM.
+Prints ONE JSON line: whole-job train frames/s, the roofline record of the dominant kernel (timed live
+with HIP events on the launch stream) and the CPU oracle timed beside it on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps 200] [--warmup 10] [--no-cpu] [--no-extras]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # 256 CU x 4 SIMD x 64 FLOP/cycle x 2.4 GHz
+PEAK_HBM_GBPS = 8000.0
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--minibatch", type=int, default=256)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-extras", action="store_true", help="skip the averaging / CD-1 side measurements")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no inter-GPU collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import gen
+    from paper_1507_01239_amd import binding as B       # raises if the HIP library is not built
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    dims, n, lr, seed = gen.CONFIG_FULL_DIMS, args.minibatch, 0.008, 1234
+    steps, warmup = args.steps, args.warmup
+    shape = B.Shape(dims)
+    P = B.mavg_param_count(shape)
+    flop_per_frame = 2 * (3 * sum(dims[l] * dims[l - 1] for l in range(1, len(dims))) - dims[1] * dims[0])
+
+    # ---- inputs resident in HBM before the timed region ------------------------------------------
+    total = steps + warmup
+    distinct = min(total, 64)            # 64 distinct minibatches cycled; all resident
+    log(f"generating {distinct} minibatches of {n} frames ...")
+    xs = torch.stack([torch.from_numpy(gen.features_speech_like(n, dims[0], seed, 0, t)) for t in range(distinct)]).cuda()
+    ys = torch.stack([torch.from_numpy(gen.labels_zipf(n, dims[-1], seed, 0, t)) for t in range(distinct)]).cuda()
+    theta0 = gen.init_theta(dims, seed, 0.05)
+    theta = torch.from_numpy(theta0).cuda()
+    acts = torch.empty(B.mavg_act_count(shape, n), device="cuda")
+    ws = torch.empty(B.mavg_workspace_bytes(shape, n, 1, B.MEAN_GRAD) + 256, dtype=torch.uint8, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+
+    def step(t):
+        x, y = xs[t % distinct], ys[t % distinct]
+        B.dnn_forward(shape, 1, theta, P, x, 0, n, acts, 0, ws)
+        B.dnn_backward_update(shape, 1, theta, P, x, 0, y, 0, n, acts, 0, lr, B.MEAN_GRAD, loss, ws)
+
+    for t in range(warmup):
+        step(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(warmup, total):
+        step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / steps * 1e3
+    frames_per_s = n * steps / elapsed
+    final_loss = float(loss.item()) / n
+    log(f"train: {ms_per_step:.3f} ms/step, {frames_per_s:,.0f} frames/s, mean loss {final_loss:.4f}")
+
+    # ---- roofline of the dominant kernel: the output-layer GEMM (n x 8000 x 2048), forward form --
+    # timed with HIP events on the stream the kernel is launched on (torch's current stream)
+    M, N, K = n, dims[-1], dims[-2]
+    a = torch.randn(M, K, device="cuda")
+    w = torch.randn(N, K, device="cuda") * 0.05
+    c = torch.empty(M, N, device="cuda")
+    bias = torch.zeros(N, device="cuda")
+    gws = torch.empty(B.mavg_gemm_workspace_bytes(M, N, K, -1, 0) + 256, dtype=torch.uint8, device="cuda")
+    reps = 50
+    for _ in range(5):
+        B.mavg_gemm(a, K, 1, w, K, 1, c, N, M, N, K, 1, bias, None, 0, 1.0, 0.0, -1, 0, gws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        B.mavg_gemm(a, K, 1, w, K, 1, c, N, M, N, K, 1, bias, None, 0, 1.0, 0.0, -1, 0, gws)
+    e1.record()
+    torch.cuda.synchronize()
+    gemm_ms = e0.elapsed_time(e1) / reps
+    gemm_tflops = 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": f"gemm_kernel fp32 {M}x{N}x{K} (output layer, forward)",
+                "achieved": round(gemm_tflops, 3), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(gemm_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": round(gemm_ms * 1e3, 2)}
+    log(f"roofline: {roofline}")
+
+    extras = {"step_mfma_tflops": round(frames_per_s * flop_per_frame / 1e12, 3),
+              "step_mfma_frac": round(frames_per_s * flop_per_frame / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
+              "flop_per_frame": flop_per_frame, "final_mean_loss": round(final_loss, 4)}
+
+    if not args.no_extras:
+        # replica averaging: 8 replicas of the same network resident in HBM (2*K*P*4 bytes per call)
+        Kr = 8
+        reps_t = torch.randn(Kr, P, device="cuda") * 0.05
+        for _ in range(3):
+            B.replicas_average(reps_t, P, P, Kr)
+        e0.record()
+        for _ in range(20):
+            B.replicas_average(reps_t, P, P, Kr)
+        e1.record()
+        torch.cuda.synchronize()
+        avg_ms = e0.elapsed_time(e1) / 20
+        gbps = 2.0 * Kr * P * 4 / (avg_ms * 1e-3) / 1e9
+        extras["averaging"] = {"replicas": Kr, "params": P, "ms": round(avg_ms, 4), "GB/s": round(gbps, 1),
+                               "frac_of_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4)}
+        log(f"averaging: {extras['averaging']}")
+        del reps_t
+
+    cpu_baseline = None
+    if not args.no_cpu:
+        from oracle import dnn as odnn
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        th = theta0.astype(np.float64)
+        xs_h, ys_h = xs.cpu().numpy(), ys.cpu().numpy()
+        done, t0 = 0, time.perf_counter()
+        while done < 50 and (time.perf_counter() - t0) < args.cpu_seconds:
+            th, _, _ = odnn.sgd_step(th, dims, xs_h[done % distinct], ys_h[done % distinct], lr)
+            done += 1
+        cpu_el = time.perf_counter() - t0
+        cpu_baseline = {"value": round(n * done / cpu_el, 1), "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+                        "sample": f"{done} minibatches of {n} frames of the same workload (fp64 NumPy oracle)"}
+        log(f"cpu_baseline: {cpu_baseline}")
+
+    out = {"metric": "train frames/s, 6x2048 DNN mb256", "value": round(frames_per_s, 1), "unit": "frames/s",
+           "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"440-6x2048-8000 sigmoid/softmax DNN, minibatch {n}, SGD lr 0.008, 1 replica "
+                                  "(forward + cross-entropy backward + fused update)",
+                      "minibatch": n, "params": P},
+           "roofline": roofline, "cpu_baseline": cpu_baseline, "extras": extras}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

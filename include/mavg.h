@@ -61,6 +61,8 @@ typedef struct {
 
 /* Version / build identification: returns a static host string. */
 const char* mavg_version(void);
+/* Text of the last HIP error behind a MAVG_E_LAUNCH on this host thread (static host string). */
+const char* mavg_last_error(void);
 
 /* ---- sizes (host only; negative MAVG_E_* on invalid shape) ----------------------------------- */
 
@@ -120,7 +122,9 @@ int32_t dnn_backward_update(const mavg_shape* shape, int32_t k,
 /* ---- model averaging  (Sec. 3, eqs. 1-2; every replica receives the mean, as after an all-reduce) */
 /*
  * theta_r[i] <- (1/k) * sum_{j=0..k-1} theta_j[i]   for r in [0,k), i in [0,count).
- * The sum runs j = 0,1,...,k-1 in float32 and is multiplied once by the float32 value 1/k.
+ * The sum is a balanced pairwise tree in float32, ((t0+t1)+(t2+t3))+((t4+t5)+(t6+t7)) for k = 8 (for k > 8:
+ * blocks of 8 replicas, then a tree over the block sums), multiplied once by the float32 value 1/k;
+ * for k a power of two, identical replicas are therefore returned bit for bit.
  *   theta  device, replica r at theta + r*theta_stride;  theta_stride >= count, multiple of 4
  *   count  >= 0 (0 is a no-op);  1 <= k <= 64.  Needs no workspace.
  */

@@ -9,6 +9,11 @@ from __future__ import annotations
 import ctypes as C
 import os
 
+# PyTorch provides the device memory and streams this library works on, and it ships its own copy of the
+# HIP runtime.  It must be loaded BEFORE libmavg.so so that both use the same runtime instance: loading the
+# library first pulls in the system runtime and torch's kernels then fault.
+import torch  # noqa: F401  (import order matters)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmavg.so")
 
@@ -24,7 +29,8 @@ _ERR = {E_NULL: "null pointer", E_DIM: "bad dimension or count", E_ALIGN: "bad a
 
 class MavgError(RuntimeError):
     def __init__(self, code: int, where: str):
-        super().__init__(f"{where}: error {code} ({_ERR.get(code, 'unknown')})")
+        detail = f": {lib.mavg_last_error().decode()}" if code == E_LAUNCH else ""
+        super().__init__(f"{where}: error {code} ({_ERR.get(code, 'unknown')}{detail})")
         self.code = code
 
 
@@ -54,6 +60,7 @@ class Shape:
 _p, _i32, _i64, _u32, _u64, _f = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64, C.c_float
 _SIG = {
     "mavg_version": (C.c_char_p, []),
+    "mavg_last_error": (C.c_char_p, []),
     "mavg_param_count": (_i64, [_p]),
     "mavg_act_count": (_i64, [_p, _i32]),
     "mavg_workspace_bytes": (_i64, [_p, _i32, _i32, _u32, _i32]),
@@ -103,7 +110,6 @@ def _nbytes(t):
 def _stream(stream):
     if stream is not None:
         return stream
-    import torch
     return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
 
 

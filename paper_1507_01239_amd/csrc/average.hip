@@ -1,16 +1,28 @@
 // replicas_average: theta_r <- (1/k) sum_j theta_j for k parameter vectors resident in HBM.
 // Pure streaming (k reads + k writes per element): each thread owns 16-byte columns, issues the k
-// independent loads back to back, adds them in replica order, scales once and stores k copies.
+// independent loads back to back, adds them as a balanced pairwise tree (a fixed order), scales once and stores k copies.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "../../include/mavg.h"
+#include "gemm.h"
 
 namespace mavg {
 
 constexpr int kAvgThreads = 256;
 
 typedef float float4v __attribute__((ext_vector_type(4)));
+
+// Pairwise (balanced tree) sum of v[0..K) into v[0]: ((v0+v1)+(v2+v3))+((v4+v5)+(v6+v7)) for K = 8.
+// For K a power of two, identical inputs x give exactly K*x, so identical replicas are returned
+// bit for bit after the final multiply by 1/K.
+template <int K>
+__device__ __forceinline__ void tree_sum(float4v (&v)[K]) {
+#pragma unroll
+    for (int w = 1; w < K; w *= 2)
+#pragma unroll
+        for (int j = 0; j + w < K; j += 2 * w) v[j] += v[j + w];
+}
 
 template <int K>
 __global__ __launch_bounds__(kAvgThreads) void average_kernel(float* __restrict__ theta, int64_t stride, int64_t n4, float inv) {
@@ -20,23 +32,40 @@ __global__ __launch_bounds__(kAvgThreads) void average_kernel(float* __restrict_
 #pragma unroll
         for (int j = 0; j < K; ++j)
             v[j] = __builtin_nontemporal_load(reinterpret_cast<const float4v*>(theta + j * stride) + q);
-        float4v s = v[0];
-#pragma unroll
-        for (int j = 1; j < K; ++j) s += v[j];
-        s *= inv;
+        tree_sum<K>(v);
+        const float4v s = v[0] * inv;
 #pragma unroll
         for (int j = 0; j < K; ++j)
             __builtin_nontemporal_store(s, reinterpret_cast<float4v*>(theta + j * stride) + q);
     }
 }
 
-// any k: two passes over the replicas per column
+// 8 < k <= 64: blocks of 8 replicas are tree-summed, then the (up to 8) block sums are combined as a
+// balanced tree too: ((b0+b1)+(b2+b3))+((b4+b5)+(b6+b7)), built with a binary counter of partial sums so
+// that only one block of loads is in flight at a time.
 __global__ __launch_bounds__(kAvgThreads) void average_any_kernel(float* __restrict__ theta, int64_t stride, int64_t n4, int k, float inv) {
     const int64_t step = (int64_t)gridDim.x * kAvgThreads;
+    const float4v zero = {0.f, 0.f, 0.f, 0.f};
     for (int64_t q = (int64_t)blockIdx.x * kAvgThreads + threadIdx.x; q < n4; q += step) {
-        float4v s = reinterpret_cast<const float4v*>(theta)[q];
-        for (int j = 1; j < k; ++j) s += (reinterpret_cast<const float4v*>(theta + j * stride))[q];
-        s *= inv;
+        float4v l0 = zero, l1 = zero, l2 = zero, total = zero;
+#pragma unroll 1
+        for (int g = 0; g < 8; ++g) {
+            float4v v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int r = g * 8 + j;
+                v[j] = r < k ? (reinterpret_cast<const float4v*>(theta + r * stride))[q] : zero;
+            }
+            tree_sum<8>(v);
+            float4v b = v[0];
+            if ((g & 1) == 0) { l0 = b; continue; }
+            b = l0 + b;
+            if ((g & 2) == 0) { l1 = b; continue; }
+            b = l1 + b;
+            if ((g & 4) == 0) { l2 = b; continue; }
+            total = l2 + b;
+        }
+        const float4v s = total * inv;
         for (int j = 0; j < k; ++j) (reinterpret_cast<float4v*>(theta + j * stride))[q] = s;
     }
 }
@@ -45,8 +74,13 @@ __global__ __launch_bounds__(kAvgThreads) void average_any_kernel(float* __restr
 __global__ void average_tail_kernel(float* __restrict__ theta, int64_t stride, int64_t begin, int64_t count, int k, float inv) {
     const int64_t i = begin + threadIdx.x;
     if (i < count) {
-        float s = theta[i];
-        for (int j = 1; j < k; ++j) s += theta[j * stride + i];
+        float blk[8];
+        for (int g = 0; g < 8; ++g) {
+            float v[8];
+            for (int j = 0; j < 8; ++j) v[j] = (g * 8 + j < k) ? theta[(int64_t)(g * 8 + j) * stride + i] : 0.f;
+            blk[g] = ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
+        }
+        float s = ((blk[0] + blk[1]) + (blk[2] + blk[3])) + ((blk[4] + blk[5]) + (blk[6] + blk[7]));
         s *= inv;
         for (int j = 0; j < k; ++j) theta[j * stride + i] = s;
     }
@@ -81,11 +115,11 @@ extern "C" int32_t replicas_average(float* theta, int64_t theta_stride, int64_t 
         case 8: hipLaunchKernelGGL(average_kernel<8>, grid, block, 0, s, theta, theta_stride, n4, inv); break;
         default: hipLaunchKernelGGL(average_any_kernel, grid, block, 0, s, theta, theta_stride, n4, (int)k, inv); break;
         }
-        if (hipGetLastError() != hipSuccess) return MAVG_E_LAUNCH;
+        if (note_hip_error(hipGetLastError()) != 0) return MAVG_E_LAUNCH;
     }
     if ((count & 3) != 0) {
         hipLaunchKernelGGL(average_tail_kernel, dim3(1), dim3(4), 0, s, theta, theta_stride, n4 << 2, count, (int)k, inv);
-        if (hipGetLastError() != hipSuccess) return MAVG_E_LAUNCH;
+        if (note_hip_error(hipGetLastError()) != 0) return MAVG_E_LAUNCH;
     }
     return MAVG_OK;
 }

@@ -2,6 +2,7 @@
 // column sums with a fused axpby update, and fixed-order reductions.  No atomics anywhere: every sum
 // has one owner and a fixed order, so results are reproducible bit for bit.
 #include "kernels.h"
+#include "gemm.h"
 #include "device_math.h"
 
 namespace mavg {
@@ -77,7 +78,7 @@ int softmax_rows_launch(float* z, int64_t ld, int64_t bstride, int rows, int col
     else if (cols <= kThreads * 16) hipLaunchKernelGGL(softmax_rows_kernel<16>, grid, dim3(kThreads), 0, s, z, ld, bstride, cols);
     else if (cols <= kThreads * 36) hipLaunchKernelGGL(softmax_rows_kernel<36>, grid, dim3(kThreads), 0, s, z, ld, bstride, cols);
     else hipLaunchKernelGGL(softmax_rows_long_kernel, grid, dim3(kThreads), 0, s, z, ld, bstride, cols);
-    return (int)hipGetLastError();
+    return note_hip_error(hipGetLastError());
 }
 
 // ---- cross-entropy output error ------------------------------------------------------------------
@@ -110,7 +111,7 @@ int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride, const int32_
     dim3 grid((unsigned)gx, (unsigned)rows, (unsigned)batch);
     hipLaunchKernelGGL(ce_delta_kernel, grid, dim3(kThreads), 0, s, p, ldp, p_bstride, labels, label_bstride, delta, ldd,
                        d_bstride, rowloss, rows, cols, scale);
-    return (int)hipGetLastError();
+    return note_hip_error(hipGetLastError());
 }
 
 // ---- fixed-order segment sums --------------------------------------------------------------------
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void sum_segments_kernel(const float* __r
 int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s) {
     if (batch <= 0) return 0;
     hipLaunchKernelGGL(sum_segments_kernel, dim3((unsigned)batch), dim3(kThreads), 0, s, v, n, out);
-    return (int)hipGetLastError();
+    return note_hip_error(hipGetLastError());
 }
 
 // ---- column sums with fused update ---------------------------------------------------------------
@@ -171,7 +172,7 @@ int colsum_axpby_launch(const float* X, int64_t ldx, int64_t x_bstride, const fl
     dim3 grid((unsigned)((cols + 63) / 64), (unsigned)batch);
     hipLaunchKernelGGL(colsum_axpby_kernel, grid, dim3(kThreads), 0, s, X, ldx, x_bstride, Y, ldy, y_bstride, dst, dst_bstride,
                        dst2, dst2_bstride, rows, cols, alpha, beta);
-    return (int)hipGetLastError();
+    return note_hip_error(hipGetLastError());
 }
 
 // ---- sum of squared differences ------------------------------------------------------------------
@@ -197,7 +198,7 @@ int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, 
                       float* out, hipStream_t s) {
     hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(kThreads), 0, s, X, ldx, Y, ldy, rows, cols, partial);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
+    if (e != hipSuccess) return note_hip_error(e);
     return sum_segments_launch(partial, kSqBlocks, 1, out, s);
 }
 

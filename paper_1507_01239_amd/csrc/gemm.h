@@ -6,6 +6,9 @@
 
 namespace mavg {
 
+// Remember / report the last HIP error a launch of this library saw (per host thread).
+int note_hip_error(hipError_t e);   // returns (int)e
+
 // The library is written for MI355X only: 256 compute units in 8 XCDs.
 constexpr int kNumCU = 256;
 constexpr int kNumXCD = 8;

@@ -356,7 +356,7 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     if (pl.cfg == 0) launch_cfg<128, 128, 16>(p, d.a_kc, d.b_kc, grid, stream);
     else launch_cfg<64, 64, 16>(p, d.a_kc, d.b_kc, grid, stream);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return (int)e;
+    if (e != hipSuccess) return note_hip_error(e);
     if (pl.splits > 1) {
         const int64_t work = ((int64_t)d.M * d.N + 3) / 4;
         int64_t gx = (work + 255) / 256;
@@ -365,10 +365,20 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
         hipLaunchKernelGGL(gemm_reduce_kernel, dim3((unsigned)gx, (unsigned)d.batch), dim3(256), 0, stream, p);
         e = hipGetLastError();
     }
-    return (int)e;
+    return note_hip_error(e);
 }
 
 }  // namespace mavg
+
+static thread_local hipError_t g_last_error = hipSuccess;
+namespace mavg {
+int note_hip_error(hipError_t e) {
+    if (e != hipSuccess) g_last_error = e;
+    return (int)e;
+}
+}  // namespace mavg
+
+extern "C" const char* mavg_last_error(void) { return hipGetErrorString(g_last_error); }
 
 // ---- exported test/tuning entry points -----------------------------------------------------------
 using namespace mavg;

@@ -131,9 +131,9 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
         g.epi.kind = EPI_BIAS_SIGMOID; g.epi.bias = c;
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
-    if (dbg_ph0 && hipMemcpy2DAsync(dbg_ph0, (size_t)H * 4, ph0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s) != hipSuccess) return MAVG_E_LAUNCH;
-    if (dbg_h0 && hipMemcpy2DAsync(dbg_h0, (size_t)H * 4, h0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s) != hipSuccess) return MAVG_E_LAUNCH;
-    if (dbg_v1 && hipMemcpy2DAsync(dbg_v1, (size_t)V * 4, v1, (size_t)lay.ldv * 4, (size_t)V * 4, n, hipMemcpyDeviceToDevice, s) != hipSuccess) return MAVG_E_LAUNCH;
+    if (dbg_ph0 && note_hip_error(hipMemcpy2DAsync(dbg_ph0, (size_t)H * 4, ph0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
+    if (dbg_h0 && note_hip_error(hipMemcpy2DAsync(dbg_h0, (size_t)H * 4, h0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
+    if (dbg_v1 && note_hip_error(hipMemcpy2DAsync(dbg_v1, (size_t)V * 4, v1, (size_t)lay.ldv * 4, (size_t)V * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (recon_err && sqdiff_sum_launch(v0, V, v1, lay.ldv, n, V, ws + lay.off_part, recon_err, s) != 0) return MAVG_E_LAUNCH;
     {   // MW <- momentum MW + (lr/n) P_h0^T V0
         GemmDesc g;

@@ -9,7 +9,7 @@ from tests.util import dev, host, rel_err
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 11])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 8, 11, 64])
 @pytest.mark.parametrize("count,stride", [(8864, 8864), (8864, 9000), (1003, 1004), (3, 4), (4096 * 33 + 2, 4096 * 33 + 4)])
 def test_matches_oracle(K, count, stride):
     import torch
@@ -26,7 +26,7 @@ def test_matches_oracle(K, count, stride):
     assert all(np.array_equal(out[0, :count], out[r, :count]) for r in range(K))
 
 
-@pytest.mark.parametrize("K", [1, 2, 4, 8])
+@pytest.mark.parametrize("K", [1, 2, 4, 8, 16, 64])
 def test_identical_replicas_are_returned_bit_exact_and_averaging_is_idempotent(K):
     import torch
     from paper_1507_01239_amd import binding as B
