@@ -47,6 +47,13 @@ extern "C" {
 /* dnn_backward_update flags */
 #define MAVG_MEAN_GRAD    1u    /* scale the output error by 1/n (gradient of the mean loss)     */
 #define MAVG_USE_NGSGD    2u    /* precondition each layer's gradient factors (needs ng_state)   */
+#define MAVG_NG_FIRST     4u    /* with MAVG_USE_NGSGD: first minibatch on freshly initialised
+                                   states (each state is folded three times before it is applied) */
+
+/* ngsgd_precondition `update` modes */
+#define MAVG_NG_APPLY        0  /* precondition only                                             */
+#define MAVG_NG_UPDATE       1  /* precondition, then fold the minibatch into the state          */
+#define MAVG_NG_INIT_UPDATE  2  /* first minibatch on a fresh state: fold three times, then as 1 */
 
 /* rbm_cd1_step */
 #define MAVG_VIS_BERNOULLI 0
@@ -166,10 +173,11 @@ int32_t rbm_hidden_prob(int32_t n_vis, int32_t n_hid, const float* w, const floa
  * ngsgd_state_init writes R = [I 0], d = rho = 1e-10, t = 0.
  *
  * ngsgd_precondition, on x (device, n x dim, row stride ldx >= dim), in place:
- *   if update and t == 0: fold x into the state three times first
+ *   update = MAVG_NG_INIT_UPDATE (the caller's first minibatch on a fresh state; the library never reads the
+ *   state back to the host, so the caller says so): fold x into the state three times first (t stays 0)
  *   beta = rho (1 + alpha) + alpha sum(d)/dim;  e_i = d_i/(d_i + beta)
  *   H = x R^T;  xh = x - H diag(e) R;  x <- xh * ||x||_F / ||xh||_F
- *   if update: fold x in:  J = H^T x;  Y = (eta/n) J + (1-eta)(diag(d) + rho I) R;  Z = Y Y^T = U diag(c) U^T;
+ *   update >= MAVG_NG_UPDATE: fold x in:  J = H^T x;  Y = (eta/n) J + (1-eta)(diag(d) + rho I) R;  Z = Y Y^T = U diag(c) U^T;
  *              R <- diag(c)^-1/2 U^T Y;  rho <- [eta ||x||^2/n + (1-eta)(dim rho + sum d) - sum sqrt c]/(dim - rank);
  *              d <- sqrt(c) - rho;  floors rho >= 1e-10, d_i >= max(1e-10, 5e-4 max d);  t <- t + 1
  * The rank x rank work (Z, its eigen-decomposition, d, rho) is done in float64; the n x dim and

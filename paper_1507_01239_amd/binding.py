@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmavg.so")
 
 OK, E_NULL, E_DIM, E_ALIGN, E_FLAG, E_LAUNCH, E_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
-MEAN_GRAD, USE_NGSGD = 1, 2
+MEAN_GRAD, USE_NGSGD, NG_FIRST = 1, 2, 4
 VIS_BERNOULLI, VIS_GAUSSIAN = 0, 1
 SAMPLE_V1 = 1
 NG_APPLY, NG_UPDATE, NG_INIT_UPDATE = 0, 1, 2

@@ -131,34 +131,39 @@ int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_
 }
 
 // ---- column sums with fused update ---------------------------------------------------------------
-// One thread per column, rows summed top to bottom (coalesced across the columns of a wavefront);
-// rows are split over the 4 wavefront-rows of a 64x4 workgroup and combined in a fixed order.
+// A workgroup owns 32 columns: 256 threads = 32 columns x 8 row groups; row group g sums rows g, g+8, ...
+// top to bottom (a wavefront reads two 128-byte row segments per step), then the 8 partial sums of a
+// column are combined in a fixed order through LDS.
 __global__ __launch_bounds__(kThreads) void colsum_axpby_kernel(const float* __restrict__ X, int64_t ldx, int64_t x_bstride,
                                                                 const float* __restrict__ Y, int64_t ldy, int64_t y_bstride,
                                                                 float* __restrict__ dst, int64_t dst_bstride,
                                                                 float* __restrict__ dst2, int64_t dst2_bstride,
-                                                                int rows, int cols, float alpha, float beta) {
-    __shared__ float sh[4][64];
+                                                                int rows, int cols, float alpha, float beta, ColsumExtras ex) {
+    __shared__ float sh[8][33];
     const int b = blockIdx.y;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    const int j = blockIdx.x * 64 + tx;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int j = blockIdx.x * 32 + tx;
     float s = 0.f;
     if (j < cols) {
         const float* __restrict__ x = X + (int64_t)b * x_bstride + j;
-        const int r0 = (int)(((int64_t)rows * ty) / 4), r1 = (int)(((int64_t)rows * (ty + 1)) / 4);
-        if (Y) {
-            const float* __restrict__ y = Y + (int64_t)b * y_bstride + j;
-            for (int n = r0; n < r1; ++n) s += x[(int64_t)n * ldx] - y[(int64_t)n * ldy];
-        } else {
-            for (int n = r0; n < r1; ++n) s += x[(int64_t)n * ldx];
+        const float* __restrict__ y = Y ? Y + (int64_t)b * y_bstride + j : nullptr;
+        const float* __restrict__ w = ex.roww ? ex.roww + (int64_t)b * ex.roww_bstride : nullptr;
+        for (int n = ty; n < rows; n += 8) {
+            float v = x[(int64_t)n * ldx];
+            if (y) v -= y[(int64_t)n * ldy];
+            if (w) v *= w[(int64_t)n * ex.roww_ld];
+            s += v;
         }
     }
     sh[ty][tx] = s;
     __syncthreads();
     if (ty == 0 && j < cols) {
-        const float tot = (sh[0][tx] + sh[1][tx]) + (sh[2][tx] + sh[3][tx]);
+        const float tot = ((sh[0][tx] + sh[1][tx]) + (sh[2][tx] + sh[3][tx])) + ((sh[4][tx] + sh[5][tx]) + (sh[6][tx] + sh[7][tx]));
+        float a = alpha;
+        if (ex.alpha_dev0) a *= ex.alpha_dev0[b];
+        if (ex.alpha_dev1) a *= ex.alpha_dev1[b];
         float* d = dst + (int64_t)b * dst_bstride + j;
-        float r = alpha * tot;
+        float r = a * tot;
         if (beta != 0.f) r += beta * *d;
         *d = r;
         if (dst2) dst2[(int64_t)b * dst2_bstride + j] += r;
@@ -167,11 +172,13 @@ __global__ __launch_bounds__(kThreads) void colsum_axpby_kernel(const float* __r
 
 int colsum_axpby_launch(const float* X, int64_t ldx, int64_t x_bstride, const float* Y, int64_t ldy, int64_t y_bstride,
                         float* dst, int64_t dst_bstride, float* dst2, int64_t dst2_bstride, int rows, int cols, int batch,
-                        float alpha, float beta, hipStream_t s) {
+                        float alpha, float beta, hipStream_t s, const ColsumExtras* extras) {
     if (cols <= 0 || batch <= 0) return 0;
-    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)batch);
+    dim3 grid((unsigned)((cols + 31) / 32), (unsigned)batch);
+    ColsumExtras ex;
+    if (extras) ex = *extras;
     hipLaunchKernelGGL(colsum_axpby_kernel, grid, dim3(kThreads), 0, s, X, ldx, x_bstride, Y, ldy, y_bstride, dst, dst_bstride,
-                       dst2, dst2_bstride, rows, cols, alpha, beta);
+                       dst2, dst2_bstride, rows, cols, alpha, beta, ex);
     return note_hip_error(hipGetLastError());
 }
 

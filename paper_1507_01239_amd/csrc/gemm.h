@@ -20,6 +20,7 @@ enum EpiKind : int {
     EPI_MUL_DSIGMOID = 3,     // C = v * a * (1 - a),  a = aux[m, n]
     EPI_AXPBY = 4,            // C = beta*C + alpha*v ;  if C2: C2 += C
     EPI_BIAS_SIGMOID_SAMPLE = 5,  // p = sigmoid(v + bias[n]); if C: C = p;  C2 = [u(m*N+n) < p]
+    EPI_ROWSCALE_ADD = 6,     // C = alpha*v + rowvec[m] * aux[m, n]
 };
 
 struct Epilogue {
@@ -28,6 +29,9 @@ struct Epilogue {
     const float* aux = nullptr;  int64_t ldaux = 0; int64_t aux_bstride = 0;
     float* C2 = nullptr;         int64_t ldc2 = 0;  int64_t c2_bstride = 0;
     float alpha = 1.f, beta = 0.f;
+    // optional device-side factors of alpha (EPI_AXPBY): alpha_eff = alpha * alpha_dev0[b] * alpha_dev1[b]
+    const float* alpha_dev0 = nullptr; const float* alpha_dev1 = nullptr;
+    const float* rowvec = nullptr; int64_t rowvec_bstride = 0;     // EPI_ROWSCALE_ADD
     uint32_t key0 = 0, key1 = 0, step = 0, layer = 0, phase = 0;   // Philox stream of the sampling epilogue
 };
 

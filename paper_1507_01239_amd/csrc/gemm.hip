@@ -41,8 +41,8 @@ struct GemmKParams {
 
 // ---- epilogue ------------------------------------------------------------------------------------
 
-struct EpiCtx {       // per-batch resolved pointers
-    const float* bias; const float* aux; float* C; float* C2;
+struct EpiCtx {       // per-batch resolved pointers and scalars
+    const float* bias; const float* aux; float* C; float* C2; const float* rowvec; float alpha;
 };
 
 __device__ __forceinline__ EpiCtx epi_ctx(const Epilogue& e, float* C, int64_t c_bstride, int b) {
@@ -51,6 +51,10 @@ __device__ __forceinline__ EpiCtx epi_ctx(const Epilogue& e, float* C, int64_t c
     c.aux = e.aux ? e.aux + (int64_t)b * e.aux_bstride : nullptr;
     c.C = C ? C + (int64_t)b * c_bstride : nullptr;
     c.C2 = e.C2 ? e.C2 + (int64_t)b * e.c2_bstride : nullptr;
+    c.rowvec = e.rowvec ? e.rowvec + (int64_t)b * e.rowvec_bstride : nullptr;
+    c.alpha = e.alpha;
+    if (e.alpha_dev0) c.alpha *= e.alpha_dev0[b];
+    if (e.alpha_dev1) c.alpha *= e.alpha_dev1[b];
     return c;
 }
 
@@ -67,7 +71,7 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
         c.C[(int64_t)m * ldc + n] = v * a * (1.f - a);
     } else if (KIND == EPI_AXPBY) {
         const int64_t i = (int64_t)m * ldc + n;
-        float r = e.alpha * v;
+        float r = c.alpha * v;
         if (e.beta != 0.f) r += e.beta * c.C[i];
         c.C[i] = r;
         if (c.C2) { const int64_t j = (int64_t)m * e.ldc2 + n; c.C2[j] += r; }
@@ -76,6 +80,8 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
         if (c.C) c.C[(int64_t)m * ldc + n] = p;
         const float u = philox_uniform((uint64_t)m * (uint64_t)N + (uint64_t)n, e.key0, e.key1, e.step, e.layer, e.phase);
         c.C2[(int64_t)m * e.ldc2 + n] = (u < p) ? 1.f : 0.f;
+    } else if (KIND == EPI_ROWSCALE_ADD) {
+        c.C[(int64_t)m * ldc + n] = c.alpha * v + c.rowvec[m] * c.aux[(int64_t)m * e.ldaux + n];
     }
 }
 
@@ -110,6 +116,7 @@ __device__ __forceinline__ void epi_apply4(const Epilogue& e, const EpiCtx& c, i
     case EPI_MUL_DSIGMOID: { constexpr int KIND = EPI_MUL_DSIGMOID; CALL; break; } \
     case EPI_AXPBY: { constexpr int KIND = EPI_AXPBY; CALL; break; }               \
     case EPI_BIAS_SIGMOID_SAMPLE: { constexpr int KIND = EPI_BIAS_SIGMOID_SAMPLE; CALL; break; } \
+    case EPI_ROWSCALE_ADD: { constexpr int KIND = EPI_ROWSCALE_ADD; CALL; break; } \
     default: break;                                                                \
     }
 
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmKParams p) {
     if (p.splits > 1) {
         Epilogue raw;
         EpiCtx c;
-        c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr;
+        c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr; c.rowvec = nullptr; c.alpha = 1.f;
         c.C = p.ws + ((int64_t)bz * p.M) * p.N;
         write_tile<EPI_STORE, TM, TN>(acc, raw, c, p.N, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol);
     } else {

@@ -17,12 +17,19 @@ int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride,
 // out[b] = sum_{i<n} v[b*n + i], summed in a fixed order (one workgroup per b).
 int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s);
 
-// dst[b][j] = beta*dst[b][j] + alpha * sum_{n<rows} (X[b](n,j) - Y[b](n,j))   (Y may be null);
+// dst[b][j] = beta*dst[b][j] + alpha * sum_{n<rows} w[b][n] * (X[b](n,j) - Y[b](n,j))   (Y may be null);
 // if dst2: dst2[b][j] += dst[b][j].
+// Optional extras (null = absent): row weights w[b][n] = roww[b*roww_bstride + n*roww_ld]; device-side factors
+// of alpha, alpha_eff = alpha * alpha_dev0[b] * alpha_dev1[b].
+struct ColsumExtras {
+    const float* roww = nullptr; int64_t roww_ld = 0, roww_bstride = 0;
+    const float* alpha_dev0 = nullptr; const float* alpha_dev1 = nullptr;
+};
 int colsum_axpby_launch(const float* X, int64_t ldx, int64_t x_bstride,
                         const float* Y, int64_t ldy, int64_t y_bstride,
                         float* dst, int64_t dst_bstride, float* dst2, int64_t dst2_bstride,
-                        int rows, int cols, int batch, float alpha, float beta, hipStream_t s);
+                        int rows, int cols, int batch, float alpha, float beta, hipStream_t s,
+                        const ColsumExtras* extras = nullptr);
 
 // out[0] = sum over rows x cols of (X - Y)^2, fixed order; partial: scratch of >= sqdiff_partials() floats.
 int sqdiff_partials();

@@ -9,10 +9,11 @@ namespace mavg {
 struct NgLayerArgs {
     int k, n, d_in, d_out;
     const float* A_in; int64_t a_ld, a_bstride;        // n x d_in input activations
-    const float* delta; int64_t ldd, d_bstride;        // n x d_out output derivatives
+    float* delta; int64_t ldd, d_bstride;              // n x d_out output derivatives (overwritten)
     float* W; float* b; int64_t theta_stride;          // d_out x d_in weights, d_out biases
     char* state_in; char* state_out; int64_t state_rstride;   // replica r's states at + r*state_rstride bytes
     int rank; float alpha, eta, lr;
+    int mode;                                           // 1 apply + fold, 2 first minibatch (three folds first)
     float* ws; int64_t ws_floats;
     float* gemm_ws; int64_t gemm_ws_floats;
 };

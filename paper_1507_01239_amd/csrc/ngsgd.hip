@@ -1,20 +1,687 @@
-// NG-SGD preconditioner -- placeholder translation unit while the DNN path is brought up.
+// NG-SGD: online low-rank natural-gradient preconditioner (Sec. 4, eq. 4: theta <- theta + alpha E g with
+// E symmetric positive definite, standing for the inverse Fisher matrix of eq. 5, approximated directly).
+//
+// State per preconditioned matrix (dimension D, rank R): R_t (R x D, orthonormal rows, float32), d_t (R),
+// rho_t, t (float64 / int64); Fisher estimate F_t = R_t^T diag(d_t) R_t + rho_t I.
+//   apply:  beta = rho(1+alpha) + alpha sum(d)/D;  e_i = d_i/(d_i+beta);  H = X R^T;  Xh = X - H diag(e) R;
+//           out = Xh ||X||_F/||Xh||_F
+//   fold:   Y = (eta/N) H^T X + (1-eta)(diag(d)+rho I) R;  Z = Y Y^T = U diag(c) U^T;  R' = diag(c)^-1/2 U^T Y;
+//           rho' = [eta ||X||^2/N + (1-eta)(D rho + sum d) - sum sqrt c]/(D-R);  d' = sqrt(c) - rho';  floors.
+// Xh is evaluated as  X1 = X - H R;  H2 = X1 R^T;  Xh = X1 + (H (I - E) - H2) R : the projection on the tracked
+// subspace is taken out twice, because X often lies almost entirely inside it and a single float32 pass
+// leaves the small remainder with a large relative error.
+// The N x D and R x D work runs in float32 on the MFMA GEMM; the R x R work (Z, its Jacobi eigen-decomposition,
+// d, rho) runs in float64 in one workgroup.  Every kernel takes a batch index (one state per replica).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "../../include/mavg.h"
+#include "device_math.h"
+#include "gemm.h"
+#include "kernels.h"
 #include "ng_internal.h"
 
 namespace mavg {
-int64_t ng_dnn_ws_floats(const int*, int, int, int, int) { return 0; }
-int ng_layer_update(const NgLayerArgs&, hipStream_t) { return (int)hipErrorNotSupported; }
+
+namespace {
+
+constexpr double kEps = 1e-10, kDelta = 5e-4, kCFloor = 1e-24;
+constexpr int kInitFolds = 3;
+constexpr int kMaxRank = 64;
+constexpr int kJacobiSweeps = 14;
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+struct StateView { float* R; double* d; double* rho; int64_t* t; };
+__host__ __device__ inline StateView state_view(char* st, int dim, int rank) {
+    const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
+    StateView v;
+    v.R = reinterpret_cast<float*>(st);
+    v.d = reinterpret_cast<double*>(st + (int64_t)rank * ld * 4);
+    v.rho = v.d + rank;
+    v.t = reinterpret_cast<int64_t*>(v.rho + 1);
+    return v;
+}
+
+// scratch carve-up (offsets in floats from a 256-byte aligned base)
+struct NgWs {
+    int64_t ldr, ld;
+    int64_t off_H, off_H2, H_b, off_Y, RY_b, off_coef, coef_b, off_gamma;
+    int64_t off_scal, off_part, off_Z, off_Wt;       // float64 regions (offsets still in floats)
+    int64_t off_H64, H64_b, off_Y64, Y64_b;          // float64 copies used by the initial folds
+    int64_t off_gemm, gemm_floats, total;
+};
+
+NgWs ng_ws(int dim, int rank, int n, int batch) {
+    NgWs w;
+    w.ldr = round_up(rank, 4);
+    w.ld = round_up(dim, 4);
+    w.H_b = round_up((int64_t)n * w.ldr, 64);
+    w.RY_b = round_up((int64_t)rank * w.ld, 64);
+    w.coef_b = 3 * kMaxRank;
+    int64_t g = gemm_ws_floats(n, rank, dim, batch), f;
+    f = gemm_ws_floats(rank, dim, n, batch); if (f > g) g = f;
+    f = gemm_ws_floats(n, dim, rank, batch, -1, 1); if (f > g) g = f;
+    w.gemm_floats = round_up(g, 64);
+    int64_t off = 0;
+    w.off_H = off;     off += w.H_b * batch;
+    w.off_H2 = off;    off += w.H_b * batch;
+    w.off_Y = off;     off += w.RY_b * batch;
+    w.off_coef = off;  off += w.coef_b * batch;
+    w.off_gamma = off; off += round_up(2 * (int64_t)batch, 64);
+    w.off_scal = off;  off += round_up(2 * 2 * (int64_t)batch, 64);
+    w.off_part = off;  off += 2 * 256 * (int64_t)batch;
+    w.off_Z = off;     off += 2 * (int64_t)kMaxRank * kMaxRank * batch;
+    w.off_Wt = off;    off += 2 * (int64_t)kMaxRank * kMaxRank * batch;
+    w.H64_b = 2 * (int64_t)n * kMaxRank;
+    w.Y64_b = 2 * round_up((int64_t)rank * w.ld, 64);
+    w.off_H64 = off;   off += w.H64_b * batch;
+    w.off_Y64 = off;   off += w.Y64_b * batch;
+    w.off_gemm = off;  off += w.gemm_floats;
+    w.total = off;
+    return w;
+}
+
+__device__ __forceinline__ double block_sum_d(double v, double* sh) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const double r = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+    __syncthreads();
+    return r;
+}
+
+// ---- kernels -------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(256) void ng_init_kernel(char* state, int dim, int rank) {
+    const StateView v = state_view(state, dim, rank);
+    const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < (int64_t)rank * ld; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / ld, c = i - r * ld;
+        v.R[i] = (r == c) ? 1.f : 0.f;
+    }
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < rank) v.d[threadIdx.x] = kEps;
+        if (threadIdx.x == 0) { *v.rho = kEps; *v.t = 0; }
+    }
+}
+
+// coef[b] = [ e_i | (1-eta)(d_i+rho) | 1 - e_i ]
+__global__ __launch_bounds__(64) void ng_coeff_kernel(char* state, int64_t st_b, int dim, int rank, float alpha, float eta,
+                                                      float* coef, int64_t coef_b) {
+    const int b = blockIdx.x;
+    const StateView v = state_view(state + (int64_t)b * st_b, dim, rank);
+    double sumd = 0.0;
+    for (int j = 0; j < rank; ++j) sumd += v.d[j];
+    const double rho = *v.rho;
+    const double beta = rho * (1.0 + (double)alpha) + (double)alpha * sumd / (double)dim;
+    if (threadIdx.x < rank) {
+        const double di = v.d[threadIdx.x];
+        coef[(int64_t)b * coef_b + threadIdx.x] = (float)(di / (di + beta));
+        coef[(int64_t)b * coef_b + kMaxRank + threadIdx.x] = (float)((1.0 - (double)eta) * (di + rho));
+        coef[(int64_t)b * coef_b + 2 * kMaxRank + threadIdx.x] = (float)(beta / (di + beta));
+    }
+}
+
+// H2 <- H (I - E) - H2   (n x rank, row stride ldr)
+__global__ __launch_bounds__(256) void ng_combine_kernel(const float* __restrict__ H, float* __restrict__ H2, int64_t h_b, int64_t ldr,
+                                                         int n, int rank, const float* __restrict__ coef, int64_t coef_b) {
+    const int b = blockIdx.y;
+    const float* __restrict__ ome = coef + (int64_t)b * coef_b + 2 * kMaxRank;
+    const int64_t total = (int64_t)n * ldr;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int i = (int)(e % ldr);
+        if (i < rank) H2[(int64_t)b * h_b + e] = H[(int64_t)b * h_b + e] * ome[i] - H2[(int64_t)b * h_b + e];
+    }
+}
+
+// partial sums of squares of an n x dim matrix: part[b][blockIdx.x]
+__global__ __launch_bounds__(256) void ng_sumsq_partial_kernel(const float* __restrict__ x, int64_t ldx, int64_t x_b, int n, int dim,
+                                                               double* __restrict__ part) {
+    __shared__ double sh[4];
+    const int b = blockIdx.y;
+    const float* __restrict__ xb = x + (int64_t)b * x_b;
+    double s = 0.0;
+    for (int r = blockIdx.x; r < n; r += gridDim.x) {
+        const float* __restrict__ row = xb + (int64_t)r * ldx;
+        float a = 0.f;
+        for (int c = threadIdx.x; c < dim; c += 256) { const float q = row[c]; a += q * q; }
+        s += (double)a;
+    }
+    s = block_sum_d(s, sh);
+    if (threadIdx.x == 0) part[(int64_t)b * 256 + blockIdx.x] = s;
+}
+
+// scal[b][which] = sum of the 256 partials; which == 1 also sets gamma[b] = sqrt(scal[0]/scal[1]) (1 if either is 0)
+__global__ __launch_bounds__(256) void ng_sumsq_final_kernel(const double* __restrict__ part, double* __restrict__ scal, int which,
+                                                             float* __restrict__ gamma) {
+    __shared__ double sh[4];
+    const int b = blockIdx.x;
+    double s = part[(int64_t)b * 256 + threadIdx.x];
+    s = block_sum_d(s, sh);
+    if (threadIdx.x == 0) {
+        scal[b * 2 + which] = s;
+        if (which == 1) {
+            const double nx = scal[b * 2 + 0];
+            gamma[b] = (nx > 0.0 && s > 0.0) ? (float)sqrt(nx / s) : 1.f;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void ng_scale_kernel(float* __restrict__ x, int64_t ldx, int64_t x_b, int n, int dim,
+                                                       const float* __restrict__ gamma) {
+    const int b = blockIdx.y;
+    const float g = gamma[b];
+    const int64_t total = (int64_t)n * dim;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int64_t r = e / dim, c = e - r * dim;
+        x[(int64_t)b * x_b + r * ldx + c] *= g;
+    }
+}
+
+// Z = Y Y^T in float64; one workgroup per (i <= j)
+template <typename YT>
+__global__ __launch_bounds__(256) void ng_z_kernel(const YT* __restrict__ Y, int64_t ry_b, int64_t ld, int dim, int rank,
+                                                   double* __restrict__ Z) {
+    __shared__ double sh[4];
+    const int b = blockIdx.y;
+    const int i = blockIdx.x / rank, j = blockIdx.x - i * rank;
+    if (i > j) return;
+    const YT* __restrict__ yi = Y + (int64_t)b * ry_b + (int64_t)i * ld;
+    const YT* __restrict__ yj = Y + (int64_t)b * ry_b + (int64_t)j * ld;
+    double s = 0.0;
+    for (int c = threadIdx.x; c < dim; c += 256) s += (double)yi[c] * (double)yj[c];
+    s = block_sum_d(s, sh);
+    if (threadIdx.x == 0) {
+        double* Zb = Z + (int64_t)b * kMaxRank * kMaxRank;
+        Zb[i * rank + j] = s;
+        Zb[j * rank + i] = s;
+    }
+}
+
+// Symmetric eigen-decomposition of the rank x rank matrix Z by cyclic Jacobi rotations in a round-robin
+// (tournament) order, so that the rank/2 disjoint rotations of a round are applied in parallel; then the
+// new d, rho, t and the matrix Wt = diag(c)^-1/2 U^T (rows in descending order of c).
+__global__ __launch_bounds__(256) void ng_eig_kernel(char* state, int64_t st_b, int dim, int rank, int n, float eta,
+                                                     const double* __restrict__ Zg, const double* __restrict__ scal,
+                                                     double* __restrict__ Wt, int bump_t) {
+    extern __shared__ double smem[];
+    const int r = rank;
+    double* Zs = smem;               // r x r
+    double* Us = Zs + r * r;         // r x r
+    double* cs = Us + r * r;         // 32 cos
+    double* sn = cs + 32;            // 32 sin
+    double* red = sn + 32;           // 8
+    int* pp = reinterpret_cast<int*>(red + 8);   // 32 + 32 pair indices
+    int* qq = pp + 32;
+    int* order = qq + 32;            // 64
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const double* __restrict__ Zb = Zg + (int64_t)b * kMaxRank * kMaxRank;
+    for (int i = tid; i < r * r; i += 256) {
+        Zs[i] = Zb[i];
+        Us[i] = (i / r == i % r) ? 1.0 : 0.0;
+    }
+    __syncthreads();
+    const int m = (r + 1) & ~1;      // even number of players
+    const int half = m / 2;
+    for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
+        // stop when the off-diagonal mass is negligible against the diagonal
+        double off = 0.0, dg = 0.0;
+        for (int i = tid; i < r * r; i += 256) {
+            const double v = Zs[i];
+            if (i / r == i % r) dg += v * v; else off += v * v;
+        }
+        off = block_sum_d(off, red);
+        dg = block_sum_d(dg, red);
+        if (off <= 1e-30 * dg) break;
+        for (int round = 0; round < m - 1; ++round) {
+            if (tid < half) {
+                int p, q;
+                if (tid == 0) { p = m - 1; q = round; }
+                else { p = (round + tid) % (m - 1); q = (round - tid + (m - 1)) % (m - 1); }
+                if (p > q) { const int t = p; p = q; q = t; }
+                double c = 1.0, s = 0.0;
+                if (q < r) {
+                    const double apq = Zs[p * r + q];
+                    if (apq != 0.0) {
+                        const double tau = (Zs[q * r + q] - Zs[p * r + p]) / (2.0 * apq);
+                        const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+                        c = 1.0 / sqrt(1.0 + t * t);
+                        s = t * c;
+                    }
+                } else { q = -1; }
+                pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
+            }
+            __syncthreads();
+            // rows:  row_p <- c row_p - s row_q ;  row_q <- s row_p + c row_q
+            for (int w = tid; w < half * r; w += 256) {
+                const int k = w / r, j = w - k * r;
+                const int p = pp[k], q = qq[k];
+                if (q >= 0) {
+                    const double c = cs[k], s = sn[k];
+                    const double zp = Zs[p * r + j], zq = Zs[q * r + j];
+                    Zs[p * r + j] = c * zp - s * zq;
+                    Zs[q * r + j] = s * zp + c * zq;
+                }
+            }
+            __syncthreads();
+            // columns of Z and of U
+            for (int w = tid; w < half * r; w += 256) {
+                const int k = w / r, i = w - k * r;
+                const int p = pp[k], q = qq[k];
+                if (q >= 0) {
+                    const double c = cs[k], s = sn[k];
+                    const double zp = Zs[i * r + p], zq = Zs[i * r + q];
+                    Zs[i * r + p] = c * zp - s * zq;
+                    Zs[i * r + q] = s * zp + c * zq;
+                    const double up = Us[i * r + p], uq = Us[i * r + q];
+                    Us[i * r + p] = c * up - s * uq;
+                    Us[i * r + q] = s * up + c * uq;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    // descending order of the eigenvalues (ties by index)
+    if (tid < r) {
+        const double ci = Zs[tid * r + tid];
+        int pos = 0;
+        for (int j = 0; j < r; ++j) {
+            const double cj = Zs[j * r + j];
+            if (cj > ci || (cj == ci && j < tid)) ++pos;
+        }
+        order[pos] = tid;
+    }
+    __syncthreads();
+    const StateView v = state_view(state + (int64_t)b * st_b, dim, rank);
+    if (tid == 0) {
+        const double cmax = Zs[order[0] * r + order[0]];
+        double sumd = 0.0, sumsq = 0.0;
+        for (int j = 0; j < r; ++j) sumd += v.d[j];
+        const double rho = *v.rho;
+        for (int i = 0; i < r; ++i) {
+            double c = Zs[order[i] * r + order[i]];
+            c = fmax(c, kCFloor * cmax);
+            const double sq = sqrt(c);
+            Zs[order[i] * r + order[i]] = sq;          // keep sqrt(c_i) on the diagonal for the other threads
+            sumsq += sq;
+        }
+        const double trT = (double)eta * scal[b * 2 + 0] / (double)n + (1.0 - (double)eta) * ((double)dim * rho + sumd);
+        double rho_new = (trT - sumsq) / (double)(dim - rank);
+        double dmax = -1e300;
+        for (int i = 0; i < r; ++i) {
+            const double di = Zs[order[i] * r + order[i]] - rho_new;
+            v.d[i] = di;
+            dmax = fmax(dmax, di);
+        }
+        rho_new = fmax(rho_new, kEps);
+        const double floor_d = fmax(kEps, kDelta * dmax);
+        for (int i = 0; i < r; ++i) v.d[i] = fmax(v.d[i], floor_d);
+        *v.rho = rho_new;
+        if (bump_t) *v.t = *v.t + 1;
+    }
+    __syncthreads();
+    double* __restrict__ Wb = Wt + (int64_t)b * kMaxRank * kMaxRank;
+    for (int w = tid; w < r * r; w += 256) {
+        const int i = w / r, k = w - i * r;
+        const int col = order[i];
+        Wb[w] = Us[k * r + col] / Zs[col * r + col];
+    }
+}
+
+// R' = Wt Y (float64 accumulation), one thread per column
+template <typename YT>
+__global__ __launch_bounds__(256) void ng_newr_kernel(char* state, int64_t st_b, int dim, int rank, const YT* __restrict__ Y,
+                                                      int64_t ry_b, const double* __restrict__ Wt) {
+    __shared__ double Ws[kMaxRank * kMaxRank];
+    const int b = blockIdx.y;
+    const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
+    const double* __restrict__ Wb = Wt + (int64_t)b * kMaxRank * kMaxRank;
+    for (int i = threadIdx.x; i < rank * rank; i += 256) Ws[i] = Wb[i];
+    __syncthreads();
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= ld) return;
+    float* __restrict__ R = state_view(state + (int64_t)b * st_b, dim, rank).R;
+    if (c >= dim) {
+        for (int i = 0; i < rank; ++i) R[(int64_t)i * ld + c] = 0.f;
+        return;
+    }
+    YT y[kMaxRank];
+    const YT* __restrict__ Yb = Y + (int64_t)b * ry_b;
+#pragma unroll
+    for (int k = 0; k < kMaxRank; ++k) y[k] = (k < rank) ? Yb[(int64_t)k * ld + c] : (YT)0;
+    for (int i = 0; i < rank; ++i) {
+        double acc = 0.0;
+#pragma unroll
+        for (int k = 0; k < kMaxRank; ++k)
+            if (k < rank) acc += Ws[i * rank + k] * (double)y[k];
+        R[(int64_t)i * ld + c] = (float)acc;
+    }
+}
+
+// Float64 versions of H = X R^T and Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for the folds that start from the
+// initial state: there the rows of Y are all dominated by the leading direction of the data and the weaker
+// directions sit below float32 resolution.
+__global__ __launch_bounds__(256) void ng_h64_kernel(char* state, int64_t st_b, int dim, int rank, const float* __restrict__ x,
+                                                     int64_t ldx, int64_t x_b, double* __restrict__ H64, int64_t h_b) {
+    __shared__ double sh[4];
+    const int b = blockIdx.y, r = blockIdx.x;
+    const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
+    const float* __restrict__ R = state_view(state + (int64_t)b * st_b, dim, rank).R;
+    const float* __restrict__ row = x + (int64_t)b * x_b + (int64_t)r * ldx;
+    double acc[kMaxRank];
+#pragma unroll
+    for (int i = 0; i < kMaxRank; ++i) acc[i] = 0.0;
+    for (int c = threadIdx.x; c < dim; c += 256) {
+        const double xv = (double)row[c];
+#pragma unroll
+        for (int i = 0; i < kMaxRank; ++i)
+            if (i < rank) acc[i] += xv * (double)R[(int64_t)i * ld + c];
+    }
+    double* __restrict__ out = H64 + ((int64_t)b * h_b) / 2 + (int64_t)r * kMaxRank;
+#pragma unroll
+    for (int i = 0; i < kMaxRank; ++i) {
+        if (i < rank) {                       // uniform across the workgroup
+            const double v = block_sum_d(acc[i], sh);
+            if (threadIdx.x == 0) out[i] = v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void ng_y64_kernel(char* state, int64_t st_b, int dim, int rank, int n, float eta,
+                                                     const float* __restrict__ x, int64_t ldx, int64_t x_b,
+                                                     const double* __restrict__ H64, int64_t h_b, double* __restrict__ Y64, int64_t y_b) {
+    __shared__ double hs[16][kMaxRank];
+    const int b = blockIdx.y;
+    const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
+    const StateView v = state_view(state + (int64_t)b * st_b, dim, rank);
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const float* __restrict__ xb = x + (int64_t)b * x_b;
+    const double* __restrict__ Hb = H64 + ((int64_t)b * h_b) / 2;
+    double acc[kMaxRank];
+#pragma unroll
+    for (int i = 0; i < kMaxRank; ++i) acc[i] = 0.0;
+    for (int n0 = 0; n0 < n; n0 += 16) {
+        __syncthreads();
+        for (int w = threadIdx.x; w < 16 * kMaxRank; w += 256) {
+            const int rr = w / kMaxRank, i = w - rr * kMaxRank;
+            hs[rr][i] = (n0 + rr < n && i < rank) ? Hb[(int64_t)(n0 + rr) * kMaxRank + i] : 0.0;
+        }
+        __syncthreads();
+        if (c < dim) {
+            for (int rr = 0; rr < 16 && n0 + rr < n; ++rr) {
+                const double xv = (double)xb[(int64_t)(n0 + rr) * ldx + c];
+#pragma unroll
+                for (int i = 0; i < kMaxRank; ++i)
+                    if (i < rank) acc[i] += hs[rr][i] * xv;
+            }
+        }
+    }
+    if (c < dim) {
+        const double rho = *v.rho, s = (double)eta / (double)n;
+        double* __restrict__ Yb = Y64 + ((int64_t)b * y_b) / 2;
+#pragma unroll
+        for (int i = 0; i < kMaxRank; ++i)
+            if (i < rank) Yb[(int64_t)i * ld + c] = s * acc[i] + (1.0 - (double)eta) * (v.d[i] + rho) * (double)v.R[(int64_t)i * ld + c];
+    }
+}
+
+// Xaug[b](r, 0..d) = A[b](r, :), Xaug[b](r, d) = 1, padding columns 0
+__global__ __launch_bounds__(256) void ng_augment_kernel(const float* __restrict__ A, int64_t lda, int64_t a_b, int n, int d,
+                                                         float* __restrict__ X, int64_t ldx, int64_t x_b) {
+    const int b = blockIdx.y;
+    const int64_t total = (int64_t)n * ldx;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int64_t r = e / ldx, c = e - r * ldx;
+        float v = 0.f;
+        if (c < d) v = A[(int64_t)b * a_b + r * lda + c];
+        else if (c == d) v = 1.f;
+        X[(int64_t)b * x_b + e] = v;
+    }
+}
+
+// ---- host orchestration --------------------------------------------------------------------------
+
+struct NgCall {
+    char* state; int64_t st_b;          // bytes between the states of consecutive batch elements
+    int dim, rank;
+    float* x; int64_t ldx, x_b;         // preconditioned in place
+    int n, batch;
+    float alpha, eta;
+    int mode;                           // 0 apply, 1 apply + fold, 2 three folds first, then apply + fold
+    bool scale;                         // multiply by gamma in place (else only report gamma)
+    float* gamma;                       // [batch] device floats receiving ||X||/||Xh||
+    float* ws;                          // 256-byte aligned scratch of ng_ws(dim, rank, n, batch).total floats
+};
+
+#define NG_CHECK(expr)                       \
+    do {                                     \
+        const int rc__ = (expr);             \
+        if (rc__ != 0) return rc__;          \
+    } while (0)
+#define NG_LAUNCHED() NG_CHECK(note_hip_error(hipGetLastError()))
+
+int ng_eig_smem_bytes(int rank) { return (2 * rank * rank + 32 + 32 + 8) * 8 + (32 + 32 + 64) * 4; }
+
+int ng_run(const NgCall& c, hipStream_t s) {
+    const NgWs w = ng_ws(c.dim, c.rank, c.n, c.batch);
+    float* H = c.ws + w.off_H;
+    float* H2 = c.ws + w.off_H2;
+    float* Y = c.ws + w.off_Y;
+    float* coef = c.ws + w.off_coef;
+    float* gamma = c.gamma;
+    double* scal = reinterpret_cast<double*>(c.ws + w.off_scal);
+    double* part = reinterpret_cast<double*>(c.ws + w.off_part);
+    double* Z = reinterpret_cast<double*>(c.ws + w.off_Z);
+    double* Wt = reinterpret_cast<double*>(c.ws + w.off_Wt);
+    double* H64 = reinterpret_cast<double*>(c.ws + w.off_H64);
+    double* Y64 = reinterpret_cast<double*>(c.ws + w.off_Y64);
+    float* gws = c.ws + w.off_gemm;
+    const float* Rm = reinterpret_cast<const float*>(c.state);
+    const int64_t st_bf = c.st_b / 4;
+    const int smem = ng_eig_smem_bytes(c.rank);
+    if (smem > 64 * 1024) {
+        static bool raised = false;     // idempotent; benign if two threads race to set the same value
+        if (!raised) {
+            NG_CHECK(note_hip_error(hipFuncSetAttribute(reinterpret_cast<const void*>(ng_eig_kernel),
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem)));
+            raised = true;
+        }
+    }
+
+    auto sumsq = [&](int which) -> int {
+        hipLaunchKernelGGL(ng_sumsq_partial_kernel, dim3(256, c.batch), dim3(256), 0, s, c.x, c.ldx, c.x_b, c.n, c.dim, part);
+        NG_LAUNCHED();
+        hipLaunchKernelGGL(ng_sumsq_final_kernel, dim3(c.batch), dim3(256), 0, s, part, scal, which, gamma);
+        NG_LAUNCHED();
+        return 0;
+    };
+    auto coeff = [&]() -> int {
+        hipLaunchKernelGGL(ng_coeff_kernel, dim3(c.batch), dim3(64), 0, s, c.state, c.st_b, c.dim, c.rank, c.alpha, c.eta, coef,
+                           w.coef_b);
+        NG_LAUNCHED();
+        return 0;
+    };
+    auto gemm_H = [&](float* Hout) -> int {         // Hout = X R^T
+        GemmDesc g;
+        g.M = c.n; g.N = c.rank; g.K = c.dim; g.batch = c.batch;
+        g.A = c.x; g.lda = c.ldx; g.a_bstride = c.x_b; g.a_kc = true;
+        g.B = Rm; g.ldb = w.ld; g.b_bstride = st_bf; g.b_kc = true;
+        g.C = Hout; g.ldc = w.ldr; g.c_bstride = w.H_b;
+        return gemm_launch(g, gws, w.gemm_floats, s);
+    };
+    auto gemm_Y = [&]() -> int {         // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R
+        GemmDesc g;
+        g.M = c.rank; g.N = c.dim; g.K = c.n; g.batch = c.batch;
+        g.A = H; g.lda = w.ldr; g.a_bstride = w.H_b; g.a_kc = false;
+        g.B = c.x; g.ldb = c.ldx; g.b_bstride = c.x_b; g.b_kc = false;
+        g.C = Y; g.ldc = w.ld; g.c_bstride = w.RY_b;
+        g.epi.kind = EPI_ROWSCALE_ADD; g.epi.alpha = c.eta / (float)c.n;
+        g.epi.rowvec = coef + kMaxRank; g.epi.rowvec_bstride = w.coef_b;
+        g.epi.aux = Rm; g.epi.ldaux = w.ld; g.epi.aux_bstride = st_bf;
+        return gemm_launch(g, gws, w.gemm_floats, s);
+    };
+    auto gemm_XR = [&](const float* coefmat, float sign) -> int {     // X <- X + sign * coefmat R
+        GemmDesc g;
+        g.M = c.n; g.N = c.dim; g.K = c.rank; g.batch = c.batch;
+        g.A = coefmat; g.lda = w.ldr; g.a_bstride = w.H_b; g.a_kc = true;
+        g.B = Rm; g.ldb = w.ld; g.b_bstride = st_bf; g.b_kc = false;
+        g.C = c.x; g.ldc = c.ldx; g.c_bstride = c.x_b;
+        g.epi.kind = EPI_AXPBY; g.epi.alpha = sign; g.epi.beta = 1.f;
+        g.force_splits = 1;
+        return gemm_launch(g, gws, w.gemm_floats, s);
+    };
+    auto finish_fold = [&](int bump, bool y64) -> int {     // from Y: Z, eigen-decomposition, new state
+        if (y64) hipLaunchKernelGGL(ng_z_kernel<double>, dim3(c.rank * c.rank, c.batch), dim3(256), 0, s, Y64, w.Y64_b / 2, w.ld, c.dim, c.rank, Z);
+        else hipLaunchKernelGGL(ng_z_kernel<float>, dim3(c.rank * c.rank, c.batch), dim3(256), 0, s, Y, w.RY_b, w.ld, c.dim, c.rank, Z);
+        NG_LAUNCHED();
+        hipLaunchKernelGGL(ng_eig_kernel, dim3(c.batch), dim3(256), smem, s, c.state, c.st_b, c.dim, c.rank, c.n, c.eta, Z, scal, Wt, bump);
+        NG_LAUNCHED();
+        const dim3 gr((unsigned)((w.ld + 255) / 256), c.batch);
+        if (y64) hipLaunchKernelGGL(ng_newr_kernel<double>, gr, dim3(256), 0, s, c.state, c.st_b, c.dim, c.rank, Y64, w.Y64_b / 2, Wt);
+        else hipLaunchKernelGGL(ng_newr_kernel<float>, gr, dim3(256), 0, s, c.state, c.st_b, c.dim, c.rank, Y, w.RY_b, Wt);
+        NG_LAUNCHED();
+        return 0;
+    };
+
+    NG_CHECK(sumsq(0));
+    if (c.mode == 2) {
+        for (int f = 0; f < kInitFolds; ++f) {      // in float64: see ng_h64_kernel
+            hipLaunchKernelGGL(ng_h64_kernel, dim3(c.n, c.batch), dim3(256), 0, s, c.state, c.st_b, c.dim, c.rank, c.x, c.ldx, c.x_b,
+                               H64, w.H64_b);
+            NG_LAUNCHED();
+            hipLaunchKernelGGL(ng_y64_kernel, dim3((unsigned)((c.dim + 255) / 256), c.batch), dim3(256), 0, s, c.state, c.st_b, c.dim,
+                               c.rank, c.n, c.eta, c.x, c.ldx, c.x_b, H64, w.H64_b, Y64, w.Y64_b);
+            NG_LAUNCHED();
+            NG_CHECK(finish_fold(0, true));
+        }
+    }
+    NG_CHECK(coeff());
+    NG_CHECK(gemm_H(H));
+    if (c.mode >= 1) NG_CHECK(gemm_Y());
+    NG_CHECK(gemm_XR(H, -1.f));                 // X1 = X - H R
+    NG_CHECK(gemm_H(H2));                       // H2 = X1 R^T  (what the first pass left inside the subspace)
+    {
+        int64_t gx = ((int64_t)c.n * w.ldr + 255) / 256;
+        if (gx > 1024) gx = 1024;
+        hipLaunchKernelGGL(ng_combine_kernel, dim3((unsigned)gx, c.batch), dim3(256), 0, s, H, H2, w.H_b, w.ldr, c.n, c.rank, coef,
+                           w.coef_b);
+        NG_LAUNCHED();
+    }
+    NG_CHECK(gemm_XR(H2, 1.f));                 // Xh = X1 + (H (I - E) - H2) R
+    NG_CHECK(sumsq(1));
+    if (c.scale) {
+        int64_t gx = ((int64_t)c.n * c.dim + 255) / 256;
+        if (gx > 2048) gx = 2048;
+        hipLaunchKernelGGL(ng_scale_kernel, dim3((unsigned)gx, c.batch), dim3(256), 0, s, c.x, c.ldx, c.x_b, c.n, c.dim, gamma);
+        NG_LAUNCHED();
+    }
+    if (c.mode >= 1) NG_CHECK(finish_fold(1, false));
+    return 0;
+}
+
+}  // namespace
+
+namespace {
+// scratch of one layer's update: [augmented input copy | gamma_in | gamma_out | preconditioner scratch]
+int64_t ng_layer_ws_floats(int d_in, int d_out, int n, int k, int rank) {
+    const int64_t ld_in = round_up(d_in + 1, 4);
+    const int64_t a = ng_ws(d_in + 1, rank, n, k).total, b = ng_ws(d_out, rank, n, k).total;
+    return round_up((int64_t)k * n * ld_in, 64) + 2 * round_up(k, 64) + (a > b ? a : b);
+}
+}  // namespace
+
+int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank) {
+    int64_t m = 0;
+    for (int l = 1; l <= L; ++l) {
+        const int64_t f = ng_layer_ws_floats(d[l - 1], d[l], n, k, rank);
+        if (f > m) m = f;
+    }
+    return m;
+}
+
+int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
+    if (a.ws_floats < ng_layer_ws_floats(a.d_in, a.d_out, a.n, a.k, a.rank)) return (int)hipErrorInvalidValue;
+    const int dim_in = a.d_in + 1;
+    const int64_t ld_in = round_up(dim_in, 4);
+    const int64_t aug_b = (int64_t)a.n * ld_in;
+    float* Xaug = a.ws;
+    float* gamma_in = Xaug + round_up((int64_t)a.k * aug_b, 64);
+    float* gamma_out = gamma_in + round_up(a.k, 64);
+    float* ngws = gamma_out + round_up(a.k, 64);
+    {
+        int64_t gx = (aug_b + 255) / 256;
+        if (gx > 2048) gx = 2048;
+        hipLaunchKernelGGL(ng_augment_kernel, dim3((unsigned)gx, a.k), dim3(256), 0, s, a.A_in, a.a_ld, a.a_bstride, a.n, a.d_in,
+                           Xaug, ld_in, aug_b);
+        NG_LAUNCHED();
+    }
+    NgCall c;
+    c.rank = a.rank; c.n = a.n; c.batch = a.k; c.alpha = a.alpha; c.eta = a.eta; c.mode = a.mode; c.scale = false;
+    c.ws = ngws;
+    c.state = a.state_in; c.st_b = a.state_rstride; c.dim = dim_in; c.x = Xaug; c.ldx = ld_in; c.x_b = aug_b; c.gamma = gamma_in;
+    NG_CHECK(ng_run(c, s));
+    c.state = a.state_out; c.dim = a.d_out; c.x = a.delta; c.ldx = a.ldd; c.x_b = a.d_bstride; c.gamma = gamma_out;
+    NG_CHECK(ng_run(c, s));
+    {   // W <- W - lr g_out g_in  Xh_out^T Xh_in[:, :d_in]
+        GemmDesc g;
+        g.M = a.d_out; g.N = a.d_in; g.K = a.n; g.batch = a.k;
+        g.A = a.delta; g.lda = a.ldd; g.a_bstride = a.d_bstride; g.a_kc = false;
+        g.B = Xaug; g.ldb = ld_in; g.b_bstride = aug_b; g.b_kc = false;
+        g.C = a.W; g.ldc = a.d_in; g.c_bstride = a.theta_stride;
+        g.epi.kind = EPI_AXPBY; g.epi.alpha = -a.lr; g.epi.beta = 1.f;
+        g.epi.alpha_dev0 = gamma_in; g.epi.alpha_dev1 = gamma_out;
+        NG_CHECK(gemm_launch(g, a.gemm_ws, a.gemm_ws_floats, s));
+    }
+    {   // b <- b - lr g_out g_in  Xh_out^T Xh_in[:, d_in]
+        ColsumExtras ex;
+        ex.roww = Xaug + a.d_in; ex.roww_ld = ld_in; ex.roww_bstride = aug_b;
+        ex.alpha_dev0 = gamma_in; ex.alpha_dev1 = gamma_out;
+        NG_CHECK(colsum_axpby_launch(a.delta, a.ldd, a.d_bstride, nullptr, 0, 0, a.b, a.theta_stride, nullptr, 0, a.n, a.d_out,
+                                     a.k, -a.lr, 1.f, s, &ex));
+    }
+    return 0;
+}
+
 }  // namespace mavg
 
+using namespace mavg;
+
 extern "C" int64_t ngsgd_state_bytes(int32_t dim, int32_t rank) {
-    if (dim < 2 || rank < 1 || rank > 64 || rank >= dim) return MAVG_E_DIM;
-    const int64_t ld = (dim + 3) / 4 * 4;
-    return (int64_t)rank * ld * 4 + (int64_t)rank * 8 + 16;
+    if (dim < 2 || rank < 1 || rank > kMaxRank || rank >= dim) return MAVG_E_DIM;
+    const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
+    return round_up((int64_t)rank * ld * 4 + (int64_t)rank * 8 + 16, 16);
 }
-extern "C" int64_t ngsgd_workspace_bytes(int32_t, int32_t, int32_t) { return MAVG_E_FLAG; }
-extern "C" int32_t ngsgd_state_init(void*, int32_t, int32_t, void*) { return MAVG_E_FLAG; }
-extern "C" int32_t ngsgd_precondition(void*, int32_t, int32_t, float*, int64_t, int32_t, float, float, int32_t, void*, int64_t, void*) { return MAVG_E_FLAG; }
+
+extern "C" int64_t ngsgd_workspace_bytes(int32_t dim, int32_t rank, int32_t n) {
+    if (dim < 2 || rank < 1 || rank > kMaxRank || rank >= dim || n < 1) return MAVG_E_DIM;
+    return ng_ws(dim, rank, n, 1).total * 4 + 256;
+}
+
+extern "C" int32_t ngsgd_state_init(void* state, int32_t dim, int32_t rank, void* stream) {
+    if (!state) return MAVG_E_NULL;
+    if (dim < 2 || rank < 1 || rank > kMaxRank || rank >= dim) return MAVG_E_DIM;
+    if (reinterpret_cast<uintptr_t>(state) & 15u) return MAVG_E_ALIGN;
+    const int64_t work = (int64_t)rank * (((int64_t)dim + 3) / 4 * 4);
+    int64_t gx = (work + 255) / 256;
+    if (gx > 1024) gx = 1024;
+    hipLaunchKernelGGL(ng_init_kernel, dim3((unsigned)gx), dim3(256), 0, static_cast<hipStream_t>(stream), static_cast<char*>(state), dim, rank);
+    return note_hip_error(hipGetLastError()) == 0 ? MAVG_OK : MAVG_E_LAUNCH;
+}
+
+extern "C" int32_t ngsgd_precondition(void* state, int32_t dim, int32_t rank, float* x, int64_t ldx, int32_t n, float alpha,
+                                      float eta, int32_t update, void* workspace, int64_t workspace_bytes, void* stream) {
+    if (!state || !x) return MAVG_E_NULL;
+    if (dim < 2 || rank < 1 || rank > kMaxRank || rank >= dim || n < 1) return MAVG_E_DIM;
+    if (update < 0 || update > 2) return MAVG_E_FLAG;
+    if (!(alpha > 0.f) || !(eta > 0.f && eta < 1.f)) return MAVG_E_DIM;
+    if ((reinterpret_cast<uintptr_t>(state) & 15u) || (reinterpret_cast<uintptr_t>(x) & 15u) || ldx < dim) return MAVG_E_ALIGN;
+    const NgWs w = ng_ws(dim, rank, n, 1);
+    if (!workspace || workspace_bytes < w.total * 4 + 256) return MAVG_E_WORKSPACE;
+    NgCall c;
+    c.state = static_cast<char*>(state); c.st_b = 0; c.dim = dim; c.rank = rank;
+    c.x = x; c.ldx = ldx; c.x_b = 0; c.n = n; c.batch = 1; c.alpha = alpha; c.eta = eta; c.mode = update; c.scale = true;
+    c.ws = reinterpret_cast<float*>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~uintptr_t(255));
+    c.gamma = c.ws + w.off_gamma;
+    return ng_run(c, static_cast<hipStream_t>(stream)) == 0 ? MAVG_OK : MAVG_E_LAUNCH;
+}
