@@ -55,29 +55,30 @@ Layout make_layout(const mavg_shape* sh, int n) {
 
 // Workspace carve-up shared by forward and backward.
 struct Workspace {
-    int64_t ld_delta;       // row stride of the two delta buffers
-    int64_t delta_floats;   // per buffer (all replicas)
-    int64_t off_delta[2], off_rowloss, off_gemm, gemm_floats;
-    int64_t off_ng, ng_floats;       // NG-SGD: preconditioned copies + its own scratch
+    int64_t ld_delta[MAVG_MAX_LAYERS + 1];    // row stride of delta_l (d_l rounded up to a multiple of 4)
+    int64_t off_delta[MAVG_MAX_LAYERS + 1];   // delta_l for every layer: all are alive until the grouped weight update
+    int64_t off_rowloss, off_gemm, gemm_floats;
+    int64_t off_ng, ng_floats;                // NG-SGD: preconditioned copies + its own scratch
     int64_t total_floats;
 };
 
 Workspace make_workspace(const Layout& y, int n, int k, uint32_t flags, int ng_rank) {
     Workspace w;
-    w.ld_delta = round_up(y.dmax, 4);
-    w.delta_floats = round_up((int64_t)k * n * w.ld_delta, 64);
     int64_t g = 0;
     for (int l = 1; l <= y.L; ++l) {
         int64_t f = gemm_ws_floats(n, y.d[l], y.d[l - 1], k);                  // forward
         if (f > g) g = f;
         if (l > 1) { f = gemm_ws_floats(n, y.d[l - 1], y.d[l], k); if (f > g) g = f; }   // back-propagation
-        f = gemm_ws_floats(y.d[l], y.d[l - 1], n, k);                          // weight gradient
+        f = gemm_ws_floats(y.d[l], y.d[l - 1], n, k);                          // weight gradient (NG-SGD path)
         if (f > g) g = f;
     }
     w.gemm_floats = round_up(g, 64);
     int64_t off = 0;
-    w.off_delta[0] = off; off += w.delta_floats;
-    w.off_delta[1] = off; off += w.delta_floats;
+    for (int l = 1; l <= y.L; ++l) {
+        w.ld_delta[l] = round_up(y.d[l], 4);
+        w.off_delta[l] = off;
+        off += round_up((int64_t)k * n * w.ld_delta[l], 64);
+    }
     w.off_rowloss = off;  off += round_up((int64_t)k * n, 64);
     w.off_gemm = off;     off += w.gemm_floats;
     w.off_ng = off;
@@ -190,49 +191,48 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* gws = ws + w.off_gemm;
     float* rowloss = ws + w.off_rowloss;
-    float* dbuf[2] = {ws + w.off_delta[0], ws + w.off_delta[1]};
-    const int64_t ldd = w.ld_delta;
-    const int64_t d_bstride = (int64_t)n * ldd;
     const float scale = (flags & MAVG_MEAN_GRAD) ? 1.0f / (float)n : 1.0f;
+    auto delta_of = [&](int l) { return ws + w.off_delta[l]; };
+    auto dstride_of = [&](int l) { return (int64_t)n * w.ld_delta[l]; };
 
-    int cur = 0;
-    if (ce_delta_launch(acts + y.a_off[y.L], y.d[y.L], act_stride, labels, label_stride, dbuf[cur], ldd, d_bstride,
-                        rowloss, n, y.d[y.L], k, scale, s) != 0) return MAVG_E_LAUNCH;
+    if (ce_delta_launch(acts + y.a_off[y.L], y.d[y.L], act_stride, labels, label_stride, delta_of(y.L), w.ld_delta[y.L],
+                        dstride_of(y.L), rowloss, n, y.d[y.L], k, scale, s) != 0) return MAVG_E_LAUNCH;
     if (loss_sum && sum_segments_launch(rowloss, n, k, loss_sum, s) != 0) return MAVG_E_LAUNCH;
 
-    for (int l = y.L; l >= 1; --l) {
-        const float* A_in = (l == 1) ? x : acts + y.a_off[l - 1];
-        const int64_t a_ld = y.d[l - 1];
-        const int64_t a_bs = (l == 1) ? x_stride : act_stride;
-        float* delta = dbuf[cur];
-        if (l > 1) {
-            // delta_{l-1} = (delta_l W_l) * A_{l-1} (1 - A_{l-1}), with W_l as it was in the forward pass
-            GemmDesc g;
-            g.M = n; g.N = y.d[l - 1]; g.K = y.d[l]; g.batch = k;
-            g.A = delta; g.lda = ldd; g.a_bstride = d_bstride; g.a_kc = true;
-            g.B = theta + y.w_off[l]; g.ldb = y.d[l - 1]; g.b_bstride = theta_stride; g.b_kc = false;
-            g.C = dbuf[cur ^ 1]; g.ldc = ldd; g.c_bstride = d_bstride;
-            g.epi.kind = EPI_MUL_DSIGMOID;
-            g.epi.aux = A_in; g.epi.ldaux = a_ld; g.epi.aux_bstride = a_bs;
-            if (gemm_launch(g, gws, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    // 1. the chain: delta_{l-1} = (delta_l W_l) * A_{l-1} (1 - A_{l-1}), l = L..2, with every W_l as it was in the
+    //    forward pass (no weight is touched before the chain is complete)
+    for (int l = y.L; l >= 2; --l) {
+        GemmDesc g;
+        g.M = n; g.N = y.d[l - 1]; g.K = y.d[l]; g.batch = k;
+        g.A = delta_of(l); g.lda = w.ld_delta[l]; g.a_bstride = dstride_of(l); g.a_kc = true;
+        g.B = theta + y.w_off[l]; g.ldb = y.d[l - 1]; g.b_bstride = theta_stride; g.b_kc = false;
+        g.C = delta_of(l - 1); g.ldc = w.ld_delta[l - 1]; g.c_bstride = dstride_of(l - 1);
+        g.epi.kind = EPI_MUL_DSIGMOID;
+        g.epi.aux = acts + y.a_off[l - 1]; g.epi.ldaux = y.d[l - 1]; g.epi.aux_bstride = act_stride;
+        if (gemm_launch(g, gws, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
+    }
+    // 2. the updates.  Plain SGD: W_l <- W_l - lr delta_l^T A_{l-1} for all layers in ONE grouped launch, with
+    //    b_l <- b_l - lr colsum(delta_l) fused as the row sums of each GEMM's A operand (delta_l^T).
+    if (!ng) {
+        GemmDesc g[MAVG_MAX_LAYERS];
+        for (int l = 1; l <= y.L; ++l) {
+            GemmDesc& q = g[l - 1];
+            q.M = y.d[l]; q.N = y.d[l - 1]; q.K = n; q.batch = k;
+            q.A = delta_of(l); q.lda = w.ld_delta[l]; q.a_bstride = dstride_of(l); q.a_kc = false;
+            q.B = (l == 1) ? x : acts + y.a_off[l - 1]; q.ldb = y.d[l - 1]; q.b_bstride = (l == 1) ? x_stride : act_stride;
+            q.b_kc = false;
+            q.C = theta + y.w_off[l]; q.ldc = y.d[l - 1]; q.c_bstride = theta_stride;
+            q.epi.kind = EPI_AXPBY; q.epi.alpha = -lr; q.epi.beta = 1.f;
+            q.epi.rowsum_dst = theta + y.b_off[l]; q.epi.rowsum_bstride = theta_stride;
+            q.epi.rowsum_alpha = -lr; q.epi.rowsum_beta = 1.f;
         }
-        if (!ng) {
-            // W_l <- W_l - lr delta_l^T A_{l-1}
-            GemmDesc g;
-            g.M = y.d[l]; g.N = y.d[l - 1]; g.K = n; g.batch = k;
-            g.A = delta; g.lda = ldd; g.a_bstride = d_bstride; g.a_kc = false;
-            g.B = A_in; g.ldb = a_ld; g.b_bstride = a_bs; g.b_kc = false;
-            g.C = theta + y.w_off[l]; g.ldc = y.d[l - 1]; g.c_bstride = theta_stride;
-            g.epi.kind = EPI_AXPBY; g.epi.alpha = -lr; g.epi.beta = 1.f;
-            if (gemm_launch(g, gws, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
-            // b_l <- b_l - lr colsum(delta_l)
-            if (colsum_axpby_launch(delta, ldd, d_bstride, nullptr, 0, 0, theta + y.b_off[l], theta_stride, nullptr, 0, n,
-                                    y.d[l], k, -lr, 1.f, s) != 0) return MAVG_E_LAUNCH;
-        } else {
+        if (gemm_launch_grouped(g, y.L, s) != 0) return MAVG_E_LAUNCH;
+    } else {
+        for (int l = y.L; l >= 1; --l) {
             NgLayerArgs a;
             a.k = k; a.n = n; a.d_in = y.d[l - 1]; a.d_out = y.d[l];
-            a.A_in = A_in; a.a_ld = a_ld; a.a_bstride = a_bs;
-            a.delta = delta; a.ldd = ldd; a.d_bstride = d_bstride;
+            a.A_in = (l == 1) ? x : acts + y.a_off[l - 1]; a.a_ld = y.d[l - 1]; a.a_bstride = (l == 1) ? x_stride : act_stride;
+            a.delta = delta_of(l); a.ldd = w.ld_delta[l]; a.d_bstride = dstride_of(l);
             a.W = theta + y.w_off[l]; a.b = theta + y.b_off[l]; a.theta_stride = theta_stride;
             a.state_in = static_cast<char*>(ng_state) + (int64_t)(2 * (l - 1)) * ng_state_stride;
             a.state_out = static_cast<char*>(ng_state) + (int64_t)(2 * (l - 1) + 1) * ng_state_stride;
@@ -243,7 +243,6 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
             a.gemm_ws = gws; a.gemm_ws_floats = w.gemm_floats;
             if (ng_layer_update(a, s) != 0) return MAVG_E_LAUNCH;
         }
-        cur ^= 1;
     }
     return MAVG_OK;
 }

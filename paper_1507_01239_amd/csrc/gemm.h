@@ -32,6 +32,9 @@ struct Epilogue {
     // optional device-side factors of alpha (EPI_AXPBY): alpha_eff = alpha * alpha_dev0[b] * alpha_dev1[b]
     const float* alpha_dev0 = nullptr; const float* alpha_dev1 = nullptr;
     const float* rowvec = nullptr; int64_t rowvec_bstride = 0;     // EPI_ROWSCALE_ADD
+    // optional, only for an m-contiguous A operand (forces an unsplit contraction):
+    //   rowsum_dst[b][m] = rowsum_beta * rowsum_dst[b][m] + rowsum_alpha * sum_k A(m,k)
+    float* rowsum_dst = nullptr; int64_t rowsum_bstride = 0; float rowsum_alpha = 1.f, rowsum_beta = 0.f;
     uint32_t key0 = 0, key1 = 0, step = 0, layer = 0, phase = 0;   // Philox stream of the sampling epilogue
 };
 
@@ -56,5 +59,9 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
 int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg = -1, int force_splits = 0);
 // enqueue; returns hipError_t as int (0 = ok).  ws must hold gemm_ws_floats() floats when that is > 0.
 int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t stream);
+
+// Several independent GEMMs of the same operand layouts and batch count in ONE launch (64x64 tiles, unsplit
+// contraction, no scratch).  Returns hipError_t as int.
+int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream);
 
 }  // namespace mavg

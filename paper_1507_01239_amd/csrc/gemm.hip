@@ -90,13 +90,50 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
 template <int KIND, int TM, int TN>
 __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const Epilogue& e, const EpiCtx& c,
                                            int64_t ldc, int M, int N, int mbase, int nbase, int lrow, int lcol) {
-    static_for<TM * TN * 16>([&](auto tc) {
-        constexpr int t = decltype(tc)::value;
-        constexpr int i = t / (TN * 16), j = (t / 16) % TN, v = t % 16;
-        const int n = nbase + j * 32 + lcol;
-        const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
-        if (m < M && n < N) epi_apply<KIND>(e, c, ldc, N, m, n, acc[i][j][v]);
-    });
+    constexpr bool kReadsC = KIND == EPI_AXPBY;
+    constexpr bool kReadsAux = KIND == EPI_MUL_DSIGMOID || KIND == EPI_ROWSCALE_ADD;
+    if constexpr (kReadsC || kReadsAux) {
+        // read-modify-write epilogues: issue the 16 loads of a 32x32 block back to back, then combine and
+        // store, so that their latencies overlap instead of adding up
+        const bool need_old = kReadsAux || e.beta != 0.f;
+        static_for<TM * TN>([&](auto bc) {
+            constexpr int t = decltype(bc)::value;
+            constexpr int i = t / TN, j = t % TN;
+            const int n = nbase + j * 32 + lcol;
+            float old[16];
+            static_for<16>([&](auto vc) {
+                constexpr int v = decltype(vc)::value;
+                const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
+                old[v] = 0.f;
+                if (need_old && m < M && n < N)
+                    old[v] = kReadsC ? c.C[(int64_t)m * ldc + n] : c.aux[(int64_t)m * e.ldaux + n];
+            });
+            static_for<16>([&](auto vc) {
+                constexpr int v = decltype(vc)::value;
+                const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
+                if (m < M && n < N) {
+                    const float a = acc[i][j][v];
+                    if constexpr (KIND == EPI_AXPBY) {
+                        const float r = c.alpha * a + e.beta * old[v];
+                        c.C[(int64_t)m * ldc + n] = r;
+                        if (c.C2) c.C2[(int64_t)m * e.ldc2 + n] += r;
+                    } else if constexpr (KIND == EPI_MUL_DSIGMOID) {
+                        c.C[(int64_t)m * ldc + n] = a * old[v] * (1.f - old[v]);
+                    } else {
+                        c.C[(int64_t)m * ldc + n] = c.alpha * a + c.rowvec[m] * old[v];
+                    }
+                }
+            });
+        });
+    } else {
+        static_for<TM * TN * 16>([&](auto tc) {
+            constexpr int t = decltype(tc)::value;
+            constexpr int i = t / (TN * 16), j = (t / 16) % TN, v = t % 16;
+            const int n = nbase + j * 32 + lcol;
+            const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
+            if (m < M && n < N) epi_apply<KIND>(e, c, ldc, N, m, n, acc[i][j][v]);
+        });
+    }
 }
 
 // Apply epilogue `kind` to four consecutive elements of a row (the split-contraction reducer).
@@ -126,14 +163,22 @@ constexpr int kPad = 4;
 
 // Global -> register load of one operand tile (BR rows of the non-contracted index by BK contraction
 // steps), zero-filled outside [0,R) x [k0,kend).  KC: the contraction index is the contiguous one.
-template <bool KC, int NLD, int BR, int BK>
+template <bool GUARD, bool KC, int NLD, int BR, int BK, int NT>
 __device__ __forceinline__ void load_operand(const float* __restrict__ P, int64_t ld, int vec, int r0, int R,
                                              int k0, int kend, int tid, float4 (&reg)[NLD]) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-        const int f = tid + i * 256;
+        const int f = tid + i * NT;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (KC) {
+        if (!GUARD) {      // tile fully inside the matrix, 16-byte aligned: one vector load, no checks
+            if (KC) {
+                const int r = f / (BK / 4), kq = f % (BK / 4);
+                v = *reinterpret_cast<const float4*>(P + (int64_t)(r0 + r) * ld + (k0 + kq * 4));
+            } else {
+                const int k = f / (BR / 4), rq = f % (BR / 4);
+                v = *reinterpret_cast<const float4*>(P + (int64_t)(k0 + k) * ld + (r0 + rq * 4));
+            }
+        } else if (KC) {
             const int r = f / (BK / 4), kq = f % (BK / 4);
             const int gr = r0 + r, gk = k0 + kq * 4;
             if (gr < R && gk < kend) {
@@ -165,11 +210,11 @@ __device__ __forceinline__ void load_operand(const float* __restrict__ P, int64_
 }
 
 // Register -> LDS store of the tile, k-major: S[k][r].
-template <bool KC, int NLD, int BR, int BK, int LDS_LD>
+template <bool KC, int NLD, int BR, int BK, int LDS_LD, int NT>
 __device__ __forceinline__ void store_operand(float* S, int tid, const float4 (&reg)[NLD]) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-        const int f = tid + i * 256;
+        const int f = tid + i * NT;
         if (KC) {
             const int r = f / (BK / 4), kq = f % (BK / 4);
             S[(kq * 4 + 0) * LDS_LD + r] = reg[i].x;
@@ -183,27 +228,30 @@ __device__ __forceinline__ void store_operand(float* S, int tid, const float4 (&
     }
 }
 
-template <int BM, int BN, int BK, bool AKC, bool BKC>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmKParams p) {
-    constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 accumulators per wavefront, each way
+// BM x BN output tile, BK contraction steps per LDS stage, WM x WN wavefronts (64*WM*WN threads); each
+// wavefront owns (BM/WM) x (BN/WN) as TM x TN accumulators of 32x32.
+template <int BM, int BN, int BK, int WM, int WN, int PF, bool AKC, bool BKC>
+__device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, const int bz) {
+    static_assert(PF >= 2 && PF % 2 == 0, "prefetch depth must be even");
+    constexpr int NT = 64 * WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int LDAS = BM + kPad, LDBS = BN + kPad;
-    constexpr int A_LD = BM * BK / 4 / 256, B_LD = BN * BK / 4 / 256;   // float4 loads per thread per tile
-    static_assert(A_LD >= 1 && B_LD >= 1, "tile too small for 256 threads");
+    constexpr int A_LD = BM * BK / 4 / NT, B_LD = BN * BK / 4 / NT;   // float4 loads per thread per tile
+    static_assert(TM >= 1 && TN >= 1 && BM % (WM * 32) == 0 && BN % (WN * 32) == 0, "bad wavefront grid");
+    static_assert(A_LD >= 1 && B_LD >= 1 && A_LD * NT * 4 == BM * BK && B_LD * NT * 4 == BN * BK, "tile does not divide over the threads");
+    static_assert(BM <= NT, "row sums need one thread per tile row");
     __shared__ __attribute__((aligned(16))) float As[2][BK][LDAS];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDBS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
-    const int bz = blockIdx.z, b = bz / p.splits, split = bz - b * p.splits;
-    const int tile = blockIdx.x;
+    const int wm = (wave / WN) * (BM / WM), wn = (wave % WN) * (BN / WN);
+    const int b = bz / p.splits, split = bz - b * p.splits;
     const int tn_i = tile % p.tiles_n, tm_i = tile / p.tiles_n;
     const int m0 = tm_i * BM, n0 = tn_i * BN;
     const int kbeg = split * p.kper;
     const int kend = min(p.K, kbeg + p.kper);
     const float* __restrict__ A = p.A + (int64_t)b * p.a_bstride;
     const float* __restrict__ B = p.B + (int64_t)b * p.b_bstride;
-
-    float4 ra[A_LD], rb[B_LD];
 
     floatx16 acc[TM][TN];
     static_for<TM * TN>([&](auto tc) {
@@ -212,41 +260,88 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmKParams p) {
     });
 
     const int nkt = (kend - kbeg + BK - 1) / BK;
-    if (nkt > 0) {
-        load_operand<AKC, A_LD, BM, BK>(A, p.lda, p.vecA, m0, p.M, kbeg, kend, tid, ra);
-        load_operand<BKC, B_LD, BN, BK>(B, p.ldb, p.vecB, n0, p.N, kbeg, kend, tid, rb);
-        store_operand<AKC, A_LD, BM, BK, LDAS>(&As[0][0][0], tid, ra);
-        store_operand<BKC, B_LD, BN, BK, LDBS>(&Bs[0][0][0], tid, rb);
-    }
-    __syncthreads();
     const int lrow = lane >> 5, lcol = lane & 31;
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nkt) {
-            load_operand<AKC, A_LD, BM, BK>(A, p.lda, p.vecA, m0, p.M, kbeg + (kt + 1) * BK, kend, tid, ra);
-            load_operand<BKC, B_LD, BN, BK>(B, p.ldb, p.vecB, n0, p.N, kbeg + (kt + 1) * BK, kend, tid, rb);
-        }
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float a[TM], bb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = As[buf][kk + lrow][wm + i * 32 + lcol];
-#pragma unroll
-            for (int j = 0; j < TN; ++j) bb[j] = Bs[buf][kk + lrow][wn + j * 32 + lcol];
-            static_for<TM * TN>([&](auto tc) {
-                constexpr int t = decltype(tc)::value;
-                constexpr int i = t / TN, j = t % TN;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], bb[j], acc[i][j], 0, 0, 0);
-            });
-        }
-        if (kt + 1 < nkt) {
-            store_operand<AKC, A_LD, BM, BK, LDAS>(&As[buf ^ 1][0][0], tid, ra);
-            store_operand<BKC, B_LD, BN, BK, LDBS>(&Bs[buf ^ 1][0][0], tid, rb);
+    // optional fused row sums of the A operand (sum over the contraction index), e.g. the bias gradient
+    // delta^T 1 next to the weight gradient delta^T A: taken from the LDS tiles by the first tile column only
+    const bool do_rowsum = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0 && tid < BM;
+    float rowsum = 0.f;
+
+    // The loop over k-tiles.  Global loads run PF tiles ahead of the multiply: tile kt+PF is requested while
+    // tile kt is multiplied out of LDS, and lives in registers until it is copied to the other LDS buffer
+    // one iteration before its turn.  A workgroup that is alone on its compute unit (the skinny
+    // minibatch-256 shapes) needs that many bytes in flight to cover HBM latency.  Inside a tile the MFMA
+    // operands of step kk+2 are read from LDS while step kk is issued.
+    auto mainloop = [&](auto guard_c) {
+        constexpr bool GUARD = decltype(guard_c)::value;
+        float4 ra[PF][A_LD], rb[PF][B_LD];
+        static_for<PF>([&](auto sc) {
+            constexpr int st = decltype(sc)::value;
+            if (st < nkt) {
+                load_operand<GUARD, AKC, A_LD, BM, BK, NT>(A, p.lda, p.vecA, m0, p.M, kbeg + st * BK, kend, tid, ra[st]);
+                load_operand<GUARD, BKC, B_LD, BN, BK, NT>(B, p.ldb, p.vecB, n0, p.N, kbeg + st * BK, kend, tid, rb[st]);
+            }
+        });
+        if (nkt > 0) {
+            store_operand<AKC, A_LD, BM, BK, LDAS, NT>(&As[0][0][0], tid, ra[0]);
+            store_operand<BKC, B_LD, BN, BK, LDBS, NT>(&Bs[0][0][0], tid, rb[0]);
         }
         __syncthreads();
-    }
+        for (int kt0 = 0; kt0 < nkt; kt0 += PF) {
+            static_for<PF>([&](auto sc) {
+                constexpr int st = decltype(sc)::value;      // register slot of tile kt (PF is even: LDS buffer = st & 1)
+                constexpr int buf = st & 1;
+                const int kt = kt0 + st;
+                if (kt < nkt) {
+                    if (kt + PF < nkt) {                      // slot st was copied to LDS an iteration ago: refill it
+                        load_operand<GUARD, AKC, A_LD, BM, BK, NT>(A, p.lda, p.vecA, m0, p.M, kbeg + (kt + PF) * BK, kend, tid, ra[st]);
+                        load_operand<GUARD, BKC, B_LD, BN, BK, NT>(B, p.ldb, p.vecB, n0, p.N, kbeg + (kt + PF) * BK, kend, tid, rb[st]);
+                    }
+                    float fa[2][TM], fb[2][TN];
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) fa[0][i] = As[buf][lrow][wm + i * 32 + lcol];
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) fb[0][j] = Bs[buf][lrow][wn + j * 32 + lcol];
+                    static_for<BK / 2>([&](auto kc) {
+                        constexpr int ks = decltype(kc)::value;
+                        constexpr int cur = ks & 1, nxt = cur ^ 1;
+                        if constexpr (ks + 1 < BK / 2) {
+#pragma unroll
+                            for (int i = 0; i < TM; ++i) fa[nxt][i] = As[buf][2 * (ks + 1) + lrow][wm + i * 32 + lcol];
+#pragma unroll
+                            for (int j = 0; j < TN; ++j) fb[nxt][j] = Bs[buf][2 * (ks + 1) + lrow][wn + j * 32 + lcol];
+                        }
+                        static_for<TM * TN>([&](auto tc) {
+                            constexpr int t = decltype(tc)::value;
+                            constexpr int i = t / TN, j = t % TN;
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+                        });
+                    });
+                    if (do_rowsum) {
+#pragma unroll
+                        for (int kk = 0; kk < BK; ++kk) rowsum += As[buf][kk][tid];
+                    }
+                    if (kt + 1 < nkt) {
+                        constexpr int nx = (st + 1) % PF;
+                        store_operand<AKC, A_LD, BM, BK, LDAS, NT>(&As[buf ^ 1][0][0], tid, ra[nx]);
+                        store_operand<BKC, B_LD, BN, BK, LDBS, NT>(&Bs[buf ^ 1][0][0], tid, rb[nx]);
+                    }
+                    __syncthreads();
+                }
+            });
+        }
+    };
+    const bool interior = p.vecA && p.vecB && m0 + BM <= p.M && n0 + BN <= p.N && ((kend - kbeg) % BK) == 0;
+    if (interior) mainloop(std::false_type{});
+    else mainloop(std::true_type{});
 
+    if (do_rowsum && m0 + tid < p.M) {
+        float* d = p.epi.rowsum_dst + (int64_t)b * p.epi.rowsum_bstride + m0 + tid;
+        float r = p.epi.rowsum_alpha * rowsum;
+        if (p.epi.rowsum_beta != 0.f) r += p.epi.rowsum_beta * *d;
+        *d = r;
+    }
     if (p.splits > 1) {
+        // split contraction: store the partial tile; gemm_reduce_kernel adds the partials in split order
         Epilogue raw;
         EpiCtx c;
         c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr; c.rowvec = nullptr; c.alpha = 1.f;
@@ -256,6 +351,28 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmKParams p) {
         const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
         MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, TM, TN>(acc, p.epi, c, p.ldc, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol)))
     }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int PF, bool AKC, bool BKC>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmKParams p) {
+    gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(p, blockIdx.x, blockIdx.z);
+}
+
+// Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
+// layers): workgroup x belongs to the group whose tile range contains it.  Contractions are not split here.
+constexpr int kMaxGroups = 8;
+struct GemmGroupParams {
+    GemmKParams g[kMaxGroups];
+    int tile_start[kMaxGroups + 1];
+    int ngroups;
+};
+
+template <int BM, int BN, int BK, int WM, int WN, int PF, bool AKC, bool BKC>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_grouped_kernel(GemmGroupParams gp) {
+    int gi = 0;
+    for (int i = 1; i < gp.ngroups; ++i)
+        if ((int)blockIdx.x >= gp.tile_start[i]) gi = i;
+    gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(gp.g[gi], (int)blockIdx.x - gp.tile_start[gi], blockIdx.z);
 }
 
 // Sum the partial results of a split contraction in split order and apply the epilogue.
@@ -288,18 +405,28 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
 
 // ---- host side -----------------------------------------------------------------------------------
 
-struct TileCfg { int bm, bn, bk; };
-static const TileCfg kCfgs[] = {{128, 128, 16}, {64, 64, 16}};
-constexpr int kNumCfgs = 2;
+struct TileCfg { int bm, bn, bk, threads; };
+// index = the `cfg` argument of the exported test entry point
+static const TileCfg kCfgs[] = {
+    {128, 128, 16, 256},   // 0: 2x2 wavefronts of 64x64
+    {64, 64, 16, 256},     // 1: 2x2 wavefronts of 32x32
+    {128, 128, 16, 512},   // 2: 2x4 wavefronts of 64x32
+    {128, 64, 16, 256},    // 3: 2x2 wavefronts of 64x32
+    {64, 128, 16, 256},    // 4: 2x2 wavefronts of 32x64
+    {256, 128, 16, 512},   // 5: 4x2 wavefronts of 64x64
+    {128, 64, 32, 256},    // 6: as 3 with 32 contraction steps per stage
+    {64, 64, 32, 256},     // 7: as 1 with 32 contraction steps per stage
+};
+constexpr int kNumCfgs = 8;
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
+    // Measured on MI355X (minibatch-256 layer shapes): 64x64 tiles win whenever a launch has fewer than about a
+    // thousand of them -- many small workgroups per compute unit run out of phase and hide each other's
+    // load, barrier and epilogue latencies -- and 128x128 tiles with 8 wavefronts win for the largest problems.
+    const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
     int cfg = force_cfg;
-    if (cfg < 0 || cfg >= kNumCfgs) {
-        // big tiles when there are enough of them to occupy the chip, or the problem is large both ways
-        const int64_t big = (int64_t)((M + 127) / 128) * ((N + 127) / 128) * batch;
-        cfg = (M > 64 && N > 64 && (big >= 24 || (M >= 512 && N >= 512))) ? 0 : 1;
-    }
+    if (cfg < 0 || cfg >= kNumCfgs) cfg = (t64 >= 3072 && M >= 512 && N >= 512) ? 2 : 1;
     pl.cfg = cfg;
     pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
     const int bk = kCfgs[cfg].bk;
@@ -308,7 +435,7 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
     if (splits <= 0) {
         splits = 1;
         if (tiles < kNumCU) {
-            splits = (int)((kNumCU + tiles - 1) / tiles);          // aim at one workgroup per compute unit
+            splits = (int)((2 * kNumCU + tiles - 1) / tiles);      // aim at two workgroups per compute unit
             const int max_by_k = (K + 8 * bk - 1) / (8 * bk);       // keep >= 8 k-tiles per split
             if (splits > max_by_k) splits = max_by_k;
             if (splits > 16) splits = 16;
@@ -329,19 +456,18 @@ int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg, int force_
     return pl.splits > 1 ? (int64_t)pl.splits * batch * M * N : 0;
 }
 
-template <int BM, int BN, int BK>
+template <int BM, int BN, int BK, int WM, int WN, int PF>
 static void launch_cfg(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
-    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, true, true>), grid, dim3(256), 0, s, p);
-    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, true, false>), grid, dim3(256), 0, s, p);
-    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, false, false>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, false, true>), grid, dim3(256), 0, s, p);
+    const dim3 block(64 * WM * WN);
+    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WM, WN, PF, true, true>), grid, block, 0, s, p);
+    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WM, WN, PF, true, false>), grid, block, 0, s, p);
+    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WM, WN, PF, false, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WM, WN, PF, false, true>), grid, block, 0, s, p);
 }
 
 static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
-int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t stream) {
-    if (d.M <= 0 || d.N <= 0 || d.batch <= 0) return 0;
-    const GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, d.force_splits);
+static GemmKParams fill_params(const GemmDesc& d, const GemmPlan& pl, float* ws) {
     GemmKParams p;
     p.A = d.A; p.lda = d.lda; p.a_bstride = d.a_bstride;
     p.B = d.B; p.ldb = d.ldb; p.b_bstride = d.b_bstride;
@@ -358,10 +484,27 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     p.vecB = aligned16(d.B) && (d.ldb % 4 == 0) && (d.b_bstride % 4 == 0);
     p.ws = ws;
     p.epi = d.epi;
-    if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return (int)hipErrorInvalidValue;
+    return p;
+}
+
+int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t stream) {
+    if (d.M <= 0 || d.N <= 0 || d.batch <= 0) return 0;
+    const bool rowsum = d.epi.rowsum_dst != nullptr;
+    if (rowsum && d.a_kc) return note_hip_error(hipErrorInvalidValue);
+    const GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
+    const GemmKParams p = fill_params(d, pl, ws);
+    if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return note_hip_error(hipErrorInvalidValue);
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
-    if (pl.cfg == 0) launch_cfg<128, 128, 16>(p, d.a_kc, d.b_kc, grid, stream);
-    else launch_cfg<64, 64, 16>(p, d.a_kc, d.b_kc, grid, stream);
+    switch (pl.cfg) {
+    case 0: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 1: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 2: launch_cfg<128, 128, 16, 2, 4, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 3: launch_cfg<128, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 4: launch_cfg<64, 128, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 5: launch_cfg<256, 128, 16, 4, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 6: launch_cfg<128, 64, 32, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
+    default: launch_cfg<64, 64, 32, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return note_hip_error(e);
     if (pl.splits > 1) {
@@ -373,6 +516,37 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
         e = hipGetLastError();
     }
     return note_hip_error(e);
+}
+
+int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
+    for (int c0 = 0; c0 < count; c0 += kMaxGroups) {
+        const int ng = count - c0 < kMaxGroups ? count - c0 : kMaxGroups;
+        GemmGroupParams gp;
+        gp.ngroups = 0;
+        int tiles = 0;
+        for (int i = 0; i < ng; ++i) {
+            const GemmDesc& di = d[c0 + i];
+            if (di.M <= 0 || di.N <= 0 || di.batch <= 0) continue;
+            if (di.a_kc != d[c0].a_kc || di.b_kc != d[c0].b_kc || di.batch != d[c0].batch) return note_hip_error(hipErrorInvalidValue);
+            if (di.epi.rowsum_dst != nullptr && di.a_kc) return note_hip_error(hipErrorInvalidValue);
+            const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, 1, 1);      // 64x64 tiles, unsplit
+            gp.g[gp.ngroups] = fill_params(di, pl, nullptr);
+            gp.tile_start[gp.ngroups] = tiles;
+            tiles += gp.g[gp.ngroups].tiles_m * gp.g[gp.ngroups].tiles_n;
+            ++gp.ngroups;
+        }
+        if (gp.ngroups == 0) continue;
+        gp.tile_start[gp.ngroups] = tiles;
+        const dim3 grid((unsigned)tiles, 1, (unsigned)d[c0].batch), block(256);
+        const bool a_kc = d[c0].a_kc, b_kc = d[c0].b_kc;
+        if (a_kc && b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, true>), grid, block, 0, stream, gp);
+        else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, false>), grid, block, 0, stream, gp);
+        else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, false>), grid, block, 0, stream, gp);
+        else hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, true>), grid, block, 0, stream, gp);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return note_hip_error(e);
+    }
+    return 0;
 }
 
 }  // namespace mavg
