@@ -22,6 +22,10 @@ if ROOT not in sys.path:
 
 PEAK_FP32_MFMA_TFLOPS = 157.3     # 256 CU x 4 SIMD x 64 FLOP/cycle x 2.4 GHz
 PEAK_HBM_GBPS = 8000.0
+# HBM-side traffic of one launch of the roofline kernel (256 x 8000 x 2048 forward GEMM), from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size) summarised in
+# profiles/gemm_output_layer_forward_hbm_counters.md: 85.2 MB fetched + 8.2 MB written.
+ROOFLINE_TRAFFIC_BYTES = {256: 93.4e6}
 
 
 def log(msg):
@@ -37,6 +41,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the averaging / CD-1 side measurements")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (a kernel of known traffic, to scale HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no inter-GPU collectives); use --gpus 1", file=sys.stderr)
@@ -109,9 +115,17 @@ def main():
     gemm_tflops = 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": f"gemm_kernel fp32 {M}x{N}x{K} (output layer, forward)",
                 "achieved": round(gemm_tflops, 3), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(gemm_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
+                "frac": round(gemm_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": ROOFLINE_TRAFFIC_BYTES.get(n),
                 "avg_launch_us": round(gemm_ms * 1e3, 2)}
     log(f"roofline: {roofline}")
+
+    if args.calibrate_copy:
+        src = torch.empty(64 * 1024 * 1024, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     extras = {"step_mfma_tflops": round(frames_per_s * flop_per_frame / 1e12, 3),
               "step_mfma_frac": round(frames_per_s * flop_per_frame / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
@@ -134,6 +148,95 @@ def main():
                                "frac_of_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4)}
         log(f"averaging: {extras['averaging']}")
         del reps_t
+
+        # RBM CD-1 steps (10*n*V*H FLOP each): Gaussian 440 -> 2048, then Bernoulli 2048 -> 2048 with sampled visibles
+        def cd1(V, H, vis, flags, lr_r, v0):
+            w_, a_, c_ = [torch.from_numpy(t).cuda() for t in gen.rbm_params(V, H, seed, 0)]
+            mw, ma, mc = torch.zeros_like(w_), torch.zeros_like(a_), torch.zeros_like(c_)
+            rws = torch.empty(B.rbm_workspace_bytes(V, H, n) + 256, dtype=torch.uint8, device="cuda")
+            err = torch.zeros(1, device="cuda")
+            for st in range(3):
+                B.rbm_cd1_step(V, H, vis, w_, a_, c_, mw, ma, mc, v0, n, lr_r, 0.9, seed, st, 0, flags, err, rws)
+            e0.record()
+            for st in range(20):
+                B.rbm_cd1_step(V, H, vis, w_, a_, c_, mw, ma, mc, v0, n, lr_r, 0.9, seed, 3 + st, 0, flags, err, rws)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 20
+            return {"ms": round(ms, 4), "frames/s": round(n / ms * 1e3, 1),
+                    "TFLOP/s": round(10.0 * n * V * H / (ms * 1e-3) / 1e12, 2),
+                    "frac_of_mfma_peak": round(10.0 * n * V * H / (ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4)}
+        extras["cd1_gaussian_440x2048"] = cd1(440, 2048, B.VIS_GAUSSIAN, 0, 0.01, xs[0])
+        extras["cd1_bernoulli_2048x2048"] = cd1(2048, 2048, B.VIS_BERNOULLI, B.SAMPLE_V1, 0.4, torch.rand(n, 2048, device="cuda"))
+        log(f"cd1: {extras['cd1_gaussian_440x2048']} {extras['cd1_bernoulli_2048x2048']}")
+
+        # NG-SGD step against the plain SGD step at minibatch 512, rank 30 (one replica)
+        def train_ms(nb, use_ng):
+            xb = torch.from_numpy(gen.features_speech_like(nb, dims[0], seed, 1, 0)).cuda()
+            yb = torch.from_numpy(gen.labels_zipf(nb, dims[-1], seed, 1, 0)).cuda()
+            th = torch.from_numpy(theta0).cuda()
+            ac = torch.empty(B.mavg_act_count(shape, nb), device="cuda")
+            fl = B.MEAN_GRAD | (B.USE_NGSGD if use_ng else 0)
+            w2 = torch.empty(B.mavg_workspace_bytes(shape, nb, 1, fl, 30) + 256, dtype=torch.uint8, device="cuda")
+            kw = {}
+            if use_ng:
+                L = len(dims) - 1
+                sb = B.ngsgd_state_bytes(max(dims) + 1, 30)
+                st_ = torch.zeros(2 * L, sb, dtype=torch.uint8, device="cuda")
+                for l in range(1, L + 1):
+                    B.ngsgd_state_init(st_[2 * (l - 1)], dims[l - 1] + 1, 30)
+                    B.ngsgd_state_init(st_[2 * (l - 1) + 1], dims[l], 30)
+                kw = dict(ng_state=st_, ng_state_stride=sb, ng_rank=30, ng_alpha=4.0, ng_eta=1.0 - float(np.exp(-nb / 2000.0)))
+            def one(first):
+                B.dnn_forward(shape, 1, th, P, xb, 0, nb, ac, 0, w2)
+                B.dnn_backward_update(shape, 1, th, P, xb, 0, yb, 0, nb, ac, 0, lr, fl | (B.NG_FIRST if (use_ng and first) else 0),
+                                      None, w2, **kw)
+            one(True)
+            for _ in range(3):
+                one(False)
+            e0.record()
+            for _ in range(20):
+                one(False)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / 20
+        # model-averaging sweep: 8 replicas resident in HBM, one grouped launch per GEMM for all replicas,
+        # parameters averaged every n_avg minibatches
+        def sweep():
+            Kr, out = 8, {}
+            th8 = torch.from_numpy(theta0).cuda().repeat(Kr, 1).contiguous()
+            for nb in (128, 256, 512, 1024):
+                xb = torch.stack([torch.from_numpy(gen.features_speech_like(nb, dims[0], seed, r, 0)) for r in range(Kr)]).cuda()
+                yb = torch.stack([torch.from_numpy(gen.labels_zipf(nb, dims[-1], seed, r, 0)) for r in range(Kr)]).cuda()
+                astride = (B.mavg_act_count(shape, nb) + 63) // 64 * 64
+                ac = torch.empty(Kr, astride, device="cuda")
+                w8 = torch.empty(B.mavg_workspace_bytes(shape, nb, Kr, B.MEAN_GRAD) + 256, dtype=torch.uint8, device="cuda")
+                for n_avg in (1, 2, 5, 10):
+                    def run(steps_):
+                        for t in range(steps_):
+                            B.dnn_forward(shape, Kr, th8, P, xb, nb * dims[0], nb, ac, astride, w8)
+                            B.dnn_backward_update(shape, Kr, th8, P, xb, nb * dims[0], yb, nb, nb, ac, astride, lr, B.MEAN_GRAD, None, w8)
+                            if (t + 1) % n_avg == 0:
+                                B.replicas_average(th8, P, P, Kr)
+                    run(n_avg if n_avg > 2 else 2)
+                    e0.record()
+                    run(20)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms = e0.elapsed_time(e1) / 20
+                    out[f"mb{nb}_n{n_avg}"] = {"ms_per_minibatch_of_all_replicas": round(ms, 3),
+                                               "frames/s": round(Kr * nb / ms * 1e3, 1),
+                                               "mfma_frac": round(Kr * nb / ms * 1e3 * flop_per_frame / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4)}
+                del xb, yb, ac, w8
+            return out
+        extras["averaging_sweep_8_replicas"] = sweep()
+        log(f"sweep: {extras['averaging_sweep_8_replicas']}")
+
+        sgd_ms, ng_ms = train_ms(512, False), train_ms(512, True)
+        extras["ngsgd_mb512_rank30"] = {"sgd_ms": round(sgd_ms, 4), "ngsgd_ms": round(ng_ms, 4),
+                                        "overhead": round(ng_ms / sgd_ms - 1.0, 4),
+                                        "ngsgd_frames/s": round(512 / ng_ms * 1e3, 1)}
+        log(f"ngsgd: {extras['ngsgd_mb512_rank30']}")
 
     cpu_baseline = None
     if not args.no_cpu:

@@ -134,6 +134,7 @@ int32_t dnn_backward_update(const mavg_shape* shape, int32_t k,
  * for k a power of two, identical replicas are therefore returned bit for bit.
  *   theta  device, replica r at theta + r*theta_stride;  theta_stride >= count, multiple of 4
  *   count  >= 0 (0 is a no-op);  1 <= k <= 64.  Needs no workspace.
+ * For k >= 6 the mean is first written to replica 0 and then copied to the others (two streaming passes).
  */
 int32_t replicas_average(float* theta, int64_t theta_stride, int64_t count, int32_t k, void* stream);
 

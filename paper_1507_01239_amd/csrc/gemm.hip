@@ -246,7 +246,20 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave / WN) * (BM / WM), wn = (wave % WN) * (BN / WN);
     const int b = bz / p.splits, split = bz - b * p.splits;
-    const int tn_i = tile % p.tiles_n, tm_i = tile / p.tiles_n;
+    // XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so the
+    // workgroups with equal (id mod 8) share an L2.  Give each XCD one contiguous run of the column-major
+    // tile sequence: the tiles_m tiles that read the same B tile (the same rows of a weight matrix) then sit
+    // on one XCD in consecutive slots and the weight tile crosses the fabric once instead of once per XCD
+    // (measured on the 256 x 8000 x 2048 layer: L2 fetch traffic 284 MB -> 85 MB).
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int xcd = tile % kNumXCD, slot = tile / kNumXCD;
+    const int tq = ntiles / kNumXCD, tr = ntiles % kNumXCD;
+    const int seq = xcd * tq + min(xcd, tr) + slot;          // bijection of [0, ntiles)
+    // Walk fastest along the smaller operand: it is the one that is re-read for every tile of the run and has
+    // to stay in L2 (activations when M <= N, e.g. 256 x 8000; the other way round for a weight gradient).
+    int tm_i, tn_i;
+    if (p.M <= p.N) { tn_i = seq / p.tiles_m; tm_i = seq - tn_i * p.tiles_m; }
+    else { tm_i = seq / p.tiles_n; tn_i = seq - tm_i * p.tiles_n; }
     const int m0 = tm_i * BM, n0 = tn_i * BN;
     const int kbeg = split * p.kper;
     const int kend = min(p.K, kbeg + p.kper);
