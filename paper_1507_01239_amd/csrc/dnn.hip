@@ -230,6 +230,7 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
     } else {
         for (int l = y.L; l >= 1; --l) {
             NgLayerArgs a;
+            a.dims = y.d; a.L = y.L; a.l = l;
             a.k = k; a.n = n; a.d_in = y.d[l - 1]; a.d_out = y.d[l];
             a.A_in = (l == 1) ? x : acts + y.a_off[l - 1]; a.a_ld = y.d[l - 1]; a.a_bstride = (l == 1) ? x_stride : act_stride;
             a.delta = delta_of(l); a.ldd = w.ld_delta[l]; a.d_bstride = dstride_of(l);
@@ -243,6 +244,8 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
             a.gemm_ws = gws; a.gemm_ws_floats = w.gemm_floats;
             if (ng_layer_update(a, s) != 0) return MAVG_E_LAUNCH;
         }
+        if (ng_dnn_finish(y.d, y.L, n, k, ng_rank, ng_eta, static_cast<char*>(ng_state), ng_state_stride, ws + w.off_ng, s) != 0)
+            return MAVG_E_LAUNCH;
     }
     return MAVG_OK;
 }

@@ -7,6 +7,7 @@ namespace mavg {
 
 // One layer's preconditioned weight/bias update for k replicas (replica = batch index).
 struct NgLayerArgs {
+    const int* dims; int L, l;                         // the network's widths d_0..d_L and this layer's index (1-based)
     int k, n, d_in, d_out;
     const float* A_in; int64_t a_ld, a_bstride;        // n x d_in input activations
     float* delta; int64_t ldd, d_bstride;              // n x d_out output derivatives (overwritten)
@@ -20,7 +21,11 @@ struct NgLayerArgs {
 
 // float32 elements of scratch ng_layer_update needs for the widest layer of the network
 int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank);
-// returns 0 or a hipError_t
+// returns 0 or a hipError_t.  Preconditions the two factors and applies the update; the folds of the states are
+// left pending (their Y matrices stay in the scratch) until ng_dnn_finish.
 int ng_layer_update(const NgLayerArgs& a, hipStream_t s);
+// Fold this minibatch into all 2*L*k states (after ng_layer_update has run for every layer).
+int ng_dnn_finish(const int* d, int L, int n, int k, int rank, float eta, char* ng_state, int64_t state_stride, float* ws,
+                  hipStream_t s);
 
 }  // namespace mavg

@@ -91,6 +91,19 @@ __device__ __forceinline__ double block_sum_d(double v, double* sh) {
     return r;
 }
 
+// Table of independent folds finished by one launch of each of ng_z_kernel / ng_eig_kernel / ng_newr_kernel:
+// slot = one preconditioned matrix (a layer's input or output side), times `batch` replicas.
+constexpr int kNgSlots = 32;
+struct NgFoldTable {
+    char* state[kNgSlots];          // state of (slot, replica 0); replica b at + b * st_b bytes
+    const void* Y[kNgSlots];        // Y of (slot, replica 0), float or double; replica b at + b * y_b[slot] elements
+    int64_t y_b[kNgSlots];
+    const double* scal[kNgSlots];   // [batch][2]: ||X||^2, ||Xh||^2
+    int dim[kNgSlots];
+    int64_t st_b;
+    int nslots, batch, first;       // first: index of slot 0 in the Z / Wt scratch arrays
+};
+
 // ---- kernels -------------------------------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void ng_init_kernel(char* state, int dim, int rank) {
@@ -181,19 +194,21 @@ __global__ __launch_bounds__(256) void ng_scale_kernel(float* __restrict__ x, in
 
 // Z = Y Y^T in float64; one workgroup per (i <= j)
 template <typename YT>
-__global__ __launch_bounds__(256) void ng_z_kernel(const YT* __restrict__ Y, int64_t ry_b, int64_t ld, int dim, int rank,
-                                                   double* __restrict__ Z) {
+__global__ __launch_bounds__(256) void ng_z_kernel(NgFoldTable tb, int rank, double* __restrict__ Z) {
     __shared__ double sh[4];
-    const int b = blockIdx.y;
+    const int slot = blockIdx.y, b = blockIdx.z;
     const int i = blockIdx.x / rank, j = blockIdx.x - i * rank;
     if (i > j) return;
-    const YT* __restrict__ yi = Y + (int64_t)b * ry_b + (int64_t)i * ld;
-    const YT* __restrict__ yj = Y + (int64_t)b * ry_b + (int64_t)j * ld;
+    const int dim = tb.dim[slot];
+    const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
+    const YT* __restrict__ Y = static_cast<const YT*>(tb.Y[slot]) + (int64_t)b * tb.y_b[slot];
+    const YT* __restrict__ yi = Y + (int64_t)i * ld;
+    const YT* __restrict__ yj = Y + (int64_t)j * ld;
     double s = 0.0;
     for (int c = threadIdx.x; c < dim; c += 256) s += (double)yi[c] * (double)yj[c];
     s = block_sum_d(s, sh);
     if (threadIdx.x == 0) {
-        double* Zb = Z + (int64_t)b * kMaxRank * kMaxRank;
+        double* Zb = Z + ((int64_t)(tb.first + slot) * tb.batch + b) * kMaxRank * kMaxRank;
         Zb[i * rank + j] = s;
         Zb[j * rank + i] = s;
     }
@@ -202,8 +217,7 @@ __global__ __launch_bounds__(256) void ng_z_kernel(const YT* __restrict__ Y, int
 // Symmetric eigen-decomposition of the rank x rank matrix Z by cyclic Jacobi rotations in a round-robin
 // (tournament) order, so that the rank/2 disjoint rotations of a round are applied in parallel; then the
 // new d, rho, t and the matrix Wt = diag(c)^-1/2 U^T (rows in descending order of c).
-__global__ __launch_bounds__(256) void ng_eig_kernel(char* state, int64_t st_b, int dim, int rank, int n, float eta,
-                                                     const double* __restrict__ Zg, const double* __restrict__ scal,
+__global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, int n, float eta, const double* __restrict__ Zg,
                                                      double* __restrict__ Wt, int bump_t) {
     extern __shared__ double smem[];
     const int r = rank;
@@ -215,8 +229,10 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(char* state, int64_t st_b, 
     int* pp = reinterpret_cast<int*>(red + 8);   // 32 + 32 pair indices
     int* qq = pp + 32;
     int* order = qq + 32;            // 64
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const double* __restrict__ Zb = Zg + (int64_t)b * kMaxRank * kMaxRank;
+    const int slot = blockIdx.x / tb.batch, b = blockIdx.x - slot * tb.batch, tid = threadIdx.x;
+    const int dim = tb.dim[slot];
+    const int64_t zi = (int64_t)(tb.first + slot) * tb.batch + b;
+    const double* __restrict__ Zb = Zg + zi * kMaxRank * kMaxRank;
     for (int i = tid; i < r * r; i += 256) {
         Zs[i] = Zb[i];
         Us[i] = (i / r == i % r) ? 1.0 : 0.0;
@@ -293,7 +309,7 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(char* state, int64_t st_b, 
         order[pos] = tid;
     }
     __syncthreads();
-    const StateView v = state_view(state + (int64_t)b * st_b, dim, rank);
+    const StateView v = state_view(tb.state[slot] + (int64_t)b * tb.st_b, dim, rank);
     if (tid == 0) {
         const double cmax = Zs[order[0] * r + order[0]];
         double sumd = 0.0, sumsq = 0.0;
@@ -306,7 +322,7 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(char* state, int64_t st_b, 
             Zs[order[i] * r + order[i]] = sq;          // keep sqrt(c_i) on the diagonal for the other threads
             sumsq += sq;
         }
-        const double trT = (double)eta * scal[b * 2 + 0] / (double)n + (1.0 - (double)eta) * ((double)dim * rho + sumd);
+        const double trT = (double)eta * tb.scal[slot][b * 2 + 0] / (double)n + (1.0 - (double)eta) * ((double)dim * rho + sumd);
         double rho_new = (trT - sumsq) / (double)(dim - rank);
         double dmax = -1e300;
         for (int i = 0; i < r; ++i) {
@@ -321,7 +337,7 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(char* state, int64_t st_b, 
         if (bump_t) *v.t = *v.t + 1;
     }
     __syncthreads();
-    double* __restrict__ Wb = Wt + (int64_t)b * kMaxRank * kMaxRank;
+    double* __restrict__ Wb = Wt + zi * kMaxRank * kMaxRank;
     for (int w = tid; w < r * r; w += 256) {
         const int i = w / r, k = w - i * r;
         const int col = order[i];
@@ -331,21 +347,22 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(char* state, int64_t st_b, 
 
 // R' = Wt Y (float64 accumulation).  A workgroup owns 32 columns; its 8 thread rows each produce every 8th row of R'.
 template <typename YT>
-__global__ __launch_bounds__(256) void ng_newr_kernel(char* state, int64_t st_b, int dim, int rank, const YT* __restrict__ Y,
-                                                      int64_t ry_b, const double* __restrict__ Wt) {
+__global__ __launch_bounds__(256) void ng_newr_kernel(NgFoldTable tb, int rank, const double* __restrict__ Wt) {
     __shared__ double Ws[kMaxRank * kMaxRank];
     __shared__ YT ys[kMaxRank][33];
-    const int b = blockIdx.y;
+    const int slot = blockIdx.y, b = blockIdx.z;
+    const int dim = tb.dim[slot];
     const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
-    const double* __restrict__ Wb = Wt + (int64_t)b * kMaxRank * kMaxRank;
+    if ((int64_t)blockIdx.x * 32 >= ld) return;
+    const double* __restrict__ Wb = Wt + ((int64_t)(tb.first + slot) * tb.batch + b) * kMaxRank * kMaxRank;
     for (int i = threadIdx.x; i < rank * rank; i += 256) Ws[i] = Wb[i];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int c = blockIdx.x * 32 + tx;
-    const YT* __restrict__ Yb = Y + (int64_t)b * ry_b;
+    const YT* __restrict__ Yb = static_cast<const YT*>(tb.Y[slot]) + (int64_t)b * tb.y_b[slot];
     for (int k = ty; k < rank; k += 8) ys[k][tx] = (c < dim) ? Yb[(int64_t)k * ld + c] : (YT)0;
     __syncthreads();
     if (c >= ld) return;
-    float* __restrict__ R = state_view(state + (int64_t)b * st_b, dim, rank).R;
+    float* __restrict__ R = state_view(tb.state[slot] + (int64_t)b * tb.st_b, dim, rank).R;
     for (int i = ty; i < rank; i += 8) {
         double acc = 0.0;
         for (int k = 0; k < rank; ++k) acc += Ws[i * rank + k] * (double)ys[k][tx];
@@ -446,6 +463,10 @@ struct NgCall {
     bool scale;                         // multiply by gamma in place (else only report gamma)
     float* gamma;                       // [batch] device floats receiving ||X||/||Xh||
     float* ws;                          // 256-byte aligned scratch of ng_ws(dim, rank, n, batch).total floats
+    // Deferred fold (the DNN path finishes the folds of all layers in one batched launch): when defer_Y is set,
+    // Y and ||X||^2 of this call are left there and the state is NOT updated by ng_run.
+    float* defer_Y = nullptr;           // [batch][RY_b] floats
+    double* defer_scal = nullptr;       // [batch][2]
 };
 
 #define NG_CHECK(expr)                       \
@@ -457,23 +478,9 @@ struct NgCall {
 
 int ng_eig_smem_bytes(int rank) { return (2 * rank * rank + 32 + 32 + 8) * 8 + (32 + 32 + 64) * 4; }
 
-int ng_run(const NgCall& c, hipStream_t s) {
-    const NgWs w = ng_ws(c.dim, c.rank, c.n, c.batch);
-    float* H = c.ws + w.off_H;
-    float* H2 = c.ws + w.off_H2;
-    float* Y = c.ws + w.off_Y;
-    float* coef = c.ws + w.off_coef;
-    float* gamma = c.gamma;
-    double* scal = reinterpret_cast<double*>(c.ws + w.off_scal);
-    double* part = reinterpret_cast<double*>(c.ws + w.off_part);
-    double* Z = reinterpret_cast<double*>(c.ws + w.off_Z);
-    double* Wt = reinterpret_cast<double*>(c.ws + w.off_Wt);
-    double* H64 = reinterpret_cast<double*>(c.ws + w.off_H64);
-    double* Y64 = reinterpret_cast<double*>(c.ws + w.off_Y64);
-    float* gws = c.ws + w.off_gemm;
-    const float* Rm = reinterpret_cast<const float*>(c.state);
-    const int64_t st_bf = c.st_b / 4;
-    const int smem = ng_eig_smem_bytes(c.rank);
+// Z = Y Y^T, eigen-decomposition, new (R, d, rho, t) for every (slot, replica) of the table: three launches.
+int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, double* Wt, int bump, hipStream_t s) {
+    const int smem = ng_eig_smem_bytes(rank);
     if (smem > 64 * 1024) {
         static bool raised = false;     // idempotent; benign if two threads race to set the same value
         if (!raised) {
@@ -482,7 +489,37 @@ int ng_run(const NgCall& c, hipStream_t s) {
             raised = true;
         }
     }
+    int maxdim = 0;
+    for (int i = 0; i < tb.nslots; ++i) if (tb.dim[i] > maxdim) maxdim = tb.dim[i];
+    const dim3 gz(rank * rank, tb.nslots, tb.batch);
+    if (y64) hipLaunchKernelGGL(ng_z_kernel<double>, gz, dim3(256), 0, s, tb, rank, Z);
+    else hipLaunchKernelGGL(ng_z_kernel<float>, gz, dim3(256), 0, s, tb, rank, Z);
+    NG_LAUNCHED();
+    hipLaunchKernelGGL(ng_eig_kernel, dim3(tb.nslots * tb.batch), dim3(256), smem, s, tb, rank, n, eta, Z, Wt, bump);
+    NG_LAUNCHED();
+    const dim3 gr((unsigned)((maxdim + 3 + 31) / 32), tb.nslots, tb.batch);
+    if (y64) hipLaunchKernelGGL(ng_newr_kernel<double>, gr, dim3(256), 0, s, tb, rank, Wt);
+    else hipLaunchKernelGGL(ng_newr_kernel<float>, gr, dim3(256), 0, s, tb, rank, Wt);
+    NG_LAUNCHED();
+    return 0;
+}
 
+int ng_run(const NgCall& c, hipStream_t s) {
+    const NgWs w = ng_ws(c.dim, c.rank, c.n, c.batch);
+    float* H = c.ws + w.off_H;
+    float* H2 = c.ws + w.off_H2;
+    float* Y = c.defer_Y ? c.defer_Y : c.ws + w.off_Y;
+    float* coef = c.ws + w.off_coef;
+    float* gamma = c.gamma;
+    double* scal = c.defer_scal ? c.defer_scal : reinterpret_cast<double*>(c.ws + w.off_scal);
+    double* part = reinterpret_cast<double*>(c.ws + w.off_part);
+    double* Z = reinterpret_cast<double*>(c.ws + w.off_Z);
+    double* Wt = reinterpret_cast<double*>(c.ws + w.off_Wt);
+    double* H64 = reinterpret_cast<double*>(c.ws + w.off_H64);
+    double* Y64 = reinterpret_cast<double*>(c.ws + w.off_Y64);
+    float* gws = c.ws + w.off_gemm;
+    const float* Rm = reinterpret_cast<const float*>(c.state);
+    const int64_t st_bf = c.st_b / 4;
     auto sumsq = [&](int which) -> int {
         hipLaunchKernelGGL(ng_sumsq_partial_kernel, dim3(256, c.batch), dim3(256), 0, s, c.x, c.ldx, c.x_b, c.n, c.dim, part);
         NG_LAUNCHED();
@@ -526,18 +563,13 @@ int ng_run(const NgCall& c, hipStream_t s) {
         return gemm_launch(g, gws, w.gemm_floats, s);
     };
     auto finish_fold = [&](int bump, bool y64) -> int {     // from Y: Z, eigen-decomposition, new state
-        if (y64) hipLaunchKernelGGL(ng_z_kernel<double>, dim3(c.rank * c.rank, c.batch), dim3(256), 0, s, Y64, w.Y64_b / 2, w.ld, c.dim, c.rank, Z);
-        else hipLaunchKernelGGL(ng_z_kernel<float>, dim3(c.rank * c.rank, c.batch), dim3(256), 0, s, Y, w.RY_b, w.ld, c.dim, c.rank, Z);
-        NG_LAUNCHED();
-        hipLaunchKernelGGL(ng_eig_kernel, dim3(c.batch), dim3(256), smem, s, c.state, c.st_b, c.dim, c.rank, c.n, c.eta, Z, scal, Wt, bump);
-        NG_LAUNCHED();
-        const dim3 gr((unsigned)((w.ld + 31) / 32), c.batch);
-        if (y64) hipLaunchKernelGGL(ng_newr_kernel<double>, gr, dim3(256), 0, s, c.state, c.st_b, c.dim, c.rank, Y64, w.Y64_b / 2, Wt);
-        else hipLaunchKernelGGL(ng_newr_kernel<float>, gr, dim3(256), 0, s, c.state, c.st_b, c.dim, c.rank, Y, w.RY_b, Wt);
-        NG_LAUNCHED();
-        return 0;
+        NgFoldTable tb;
+        tb.state[0] = c.state; tb.st_b = c.st_b; tb.dim[0] = c.dim; tb.scal[0] = scal;
+        tb.Y[0] = y64 ? static_cast<const void*>(Y64) : static_cast<const void*>(Y);
+        tb.y_b[0] = y64 ? w.Y64_b / 2 : w.RY_b;
+        tb.nslots = 1; tb.batch = c.batch; tb.first = 0;
+        return ng_finish(tb, c.rank, c.n, c.eta, y64, Z, Wt, bump, s);
     };
-
     NG_CHECK(sumsq(0));
     if (c.mode == 2) {
         for (int f = 0; f < kInitFolds; ++f) {      // in float64: see ng_h64_kernel
@@ -570,7 +602,7 @@ int ng_run(const NgCall& c, hipStream_t s) {
         hipLaunchKernelGGL(ng_scale_kernel, dim3((unsigned)gx, c.batch), dim3(256), 0, s, c.x, c.ldx, c.x_b, c.n, c.dim, gamma);
         NG_LAUNCHED();
     }
-    if (c.mode >= 1) NG_CHECK(finish_fold(1, false));
+    if (c.mode >= 1 && !c.defer_Y) NG_CHECK(finish_fold(1, false));
     return 0;
 }
 
@@ -585,21 +617,74 @@ int64_t ng_layer_ws_floats(int d_in, int d_out, int n, int k, int rank) {
 }
 }  // namespace
 
-int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank) {
-    int64_t m = 0;
+namespace {
+// NG scratch of a whole backward pass (offsets in floats): what survives until the batched fold at the end
+// -- Y and the two squared norms of every (layer side, replica), then Z and Wt -- followed by the scratch
+// that one layer's update reuses.
+struct NgDnnLayout {
+    int64_t y_off[2 * 64], y_b[2 * 64];     // slot 2(l-1): input side of layer l, slot 2(l-1)+1: output side
+    int64_t scal_off, z_off, wt_off, layer_off, layer_floats, total;
+};
+NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
+    NgDnnLayout y;
+    int64_t off = 0;
+    for (int l = 1; l <= L; ++l)
+        for (int side = 0; side < 2; ++side) {
+            const int dim = side == 0 ? d[l - 1] + 1 : d[l];
+            const int j = 2 * (l - 1) + side;
+            y.y_b[j] = round_up((int64_t)rank * round_up(dim, 4), 64);
+            y.y_off[j] = off;
+            off += y.y_b[j] * k;
+        }
+    y.scal_off = off; off += round_up(2 * 2 * (int64_t)(2 * L) * k, 64);
+    y.z_off = off;    off += 2 * (int64_t)kMaxRank * kMaxRank * (2 * L) * k;
+    y.wt_off = off;   off += 2 * (int64_t)kMaxRank * kMaxRank * (2 * L) * k;
+    y.layer_off = off;
+    y.layer_floats = 0;
     for (int l = 1; l <= L; ++l) {
         const int64_t f = ng_layer_ws_floats(d[l - 1], d[l], n, k, rank);
-        if (f > m) m = f;
+        if (f > y.layer_floats) y.layer_floats = f;
     }
-    return m;
+    y.total = off + y.layer_floats;
+    return y;
+}
+}  // namespace
+
+int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank) { return ng_dnn_layout(d, L, n, k, rank).total; }
+
+// Finish the folds of all layer sides and replicas of one backward pass (three launches per 32 slots).
+int ng_dnn_finish(const int* d, int L, int n, int k, int rank, float eta, char* ng_state, int64_t state_stride, float* ws,
+                  hipStream_t s) {
+    const NgDnnLayout y = ng_dnn_layout(d, L, n, k, rank);
+    double* scal = reinterpret_cast<double*>(ws + y.scal_off);
+    double* Z = reinterpret_cast<double*>(ws + y.z_off);
+    double* Wt = reinterpret_cast<double*>(ws + y.wt_off);
+    for (int j0 = 0; j0 < 2 * L; j0 += kNgSlots) {
+        NgFoldTable tb;
+        tb.nslots = (2 * L - j0) < kNgSlots ? (2 * L - j0) : kNgSlots;
+        tb.batch = k; tb.first = j0; tb.st_b = (int64_t)2 * L * state_stride;
+        for (int i = 0; i < tb.nslots; ++i) {
+            const int j = j0 + i, l = j / 2 + 1;
+            tb.state[i] = ng_state + (int64_t)j * state_stride;
+            tb.dim[i] = (j % 2 == 0) ? d[l - 1] + 1 : d[l];
+            tb.Y[i] = ws + y.y_off[j];
+            tb.y_b[i] = y.y_b[j];
+            tb.scal[i] = scal + (int64_t)j * k * 2;
+        }
+        NG_CHECK(ng_finish(tb, rank, n, eta, false, Z, Wt, 1, s));
+    }
+    return 0;
 }
 
 int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
-    if (a.ws_floats < ng_layer_ws_floats(a.d_in, a.d_out, a.n, a.k, a.rank)) return (int)hipErrorInvalidValue;
+    const NgDnnLayout lay = ng_dnn_layout(a.dims, a.L, a.n, a.k, a.rank);
+    if (a.ws_floats < lay.total) return (int)hipErrorInvalidValue;
     const int dim_in = a.d_in + 1;
     const int64_t ld_in = round_up(dim_in, 4);
     const int64_t aug_b = (int64_t)a.n * ld_in;
-    float* Xaug = a.ws;
+    const int j_in = 2 * (a.l - 1), j_out = j_in + 1;
+    double* scal = reinterpret_cast<double*>(a.ws + lay.scal_off);
+    float* Xaug = a.ws + lay.layer_off;
     float* gamma_in = Xaug + round_up((int64_t)a.k * aug_b, 64);
     float* gamma_out = gamma_in + round_up(a.k, 64);
     float* ngws = gamma_out + round_up(a.k, 64);
@@ -614,8 +699,10 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
     c.rank = a.rank; c.n = a.n; c.batch = a.k; c.alpha = a.alpha; c.eta = a.eta; c.mode = a.mode; c.scale = false;
     c.ws = ngws;
     c.state = a.state_in; c.st_b = a.state_rstride; c.dim = dim_in; c.x = Xaug; c.ldx = ld_in; c.x_b = aug_b; c.gamma = gamma_in;
+    c.defer_Y = a.ws + lay.y_off[j_in]; c.defer_scal = scal + (int64_t)j_in * a.k * 2;
     NG_CHECK(ng_run(c, s));
     c.state = a.state_out; c.dim = a.d_out; c.x = a.delta; c.ldx = a.ldd; c.x_b = a.d_bstride; c.gamma = gamma_out;
+    c.defer_Y = a.ws + lay.y_off[j_out]; c.defer_scal = scal + (int64_t)j_out * a.k * 2;
     NG_CHECK(ng_run(c, s));
     {   // W <- W - lr g_out g_in  Xh_out^T Xh_in[:, :d_in]
         GemmDesc g;
