@@ -69,7 +69,7 @@ Workspace make_workspace(const Layout& y, int n, int k, uint32_t flags, int ng_r
         int64_t f = gemm_ws_floats(n, y.d[l], y.d[l - 1], k);                  // forward
         if (f > g) g = f;
         if (l > 1) { f = gemm_ws_floats(n, y.d[l - 1], y.d[l], k); if (f > g) g = f; }   // back-propagation
-        f = gemm_ws_floats(y.d[l], y.d[l - 1], n, k);                          // weight gradient (NG-SGD path)
+        f = gemm_ws_floats(y.d[l], y.d[l - 1] + 1, n, k);                      // weight + bias gradient (NG-SGD path)
         if (f > g) g = f;
     }
     w.gemm_floats = round_up(g, 64);

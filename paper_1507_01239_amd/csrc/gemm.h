@@ -32,6 +32,9 @@ struct Epilogue {
     // optional device-side factors of alpha (EPI_AXPBY): alpha_eff = alpha * alpha_dev0[b] * alpha_dev1[b]
     const float* alpha_dev0 = nullptr; const float* alpha_dev1 = nullptr;
     const float* rowvec = nullptr; int64_t rowvec_bstride = 0;     // EPI_ROWSCALE_ADD
+    // optional (EPI_AXPBY): output column `lastcol` is not part of C but a separate vector, lastcol_dst[b][m]
+    // (a weight matrix whose bias is the gradient's extra column)
+    int lastcol = -1; float* lastcol_dst = nullptr; int64_t lastcol_bstride = 0;
     // optional, only for an m-contiguous A operand (forces an unsplit contraction):
     //   rowsum_dst[b][m] = rowsum_beta * rowsum_dst[b][m] + rowsum_alpha * sum_k A(m,k)
     float* rowsum_dst = nullptr; int64_t rowsum_bstride = 0; float rowsum_alpha = 1.f, rowsum_beta = 0.f;

@@ -42,7 +42,7 @@ struct GemmKParams {
 // ---- epilogue ------------------------------------------------------------------------------------
 
 struct EpiCtx {       // per-batch resolved pointers and scalars
-    const float* bias; const float* aux; float* C; float* C2; const float* rowvec; float alpha;
+    const float* bias; const float* aux; float* C; float* C2; const float* rowvec; float alpha; float* lastcol_dst;
 };
 
 __device__ __forceinline__ EpiCtx epi_ctx(const Epilogue& e, float* C, int64_t c_bstride, int b) {
@@ -52,6 +52,7 @@ __device__ __forceinline__ EpiCtx epi_ctx(const Epilogue& e, float* C, int64_t c
     c.C = C ? C + (int64_t)b * c_bstride : nullptr;
     c.C2 = e.C2 ? e.C2 + (int64_t)b * e.c2_bstride : nullptr;
     c.rowvec = e.rowvec ? e.rowvec + (int64_t)b * e.rowvec_bstride : nullptr;
+    c.lastcol_dst = e.lastcol_dst ? e.lastcol_dst + (int64_t)b * e.lastcol_bstride : nullptr;
     c.alpha = e.alpha;
     if (e.alpha_dev0) c.alpha *= e.alpha_dev0[b];
     if (e.alpha_dev1) c.alpha *= e.alpha_dev1[b];
@@ -70,10 +71,10 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
         const float a = c.aux[(int64_t)m * e.ldaux + n];
         c.C[(int64_t)m * ldc + n] = v * a * (1.f - a);
     } else if (KIND == EPI_AXPBY) {
-        const int64_t i = (int64_t)m * ldc + n;
+        float* dst = (c.lastcol_dst && n == e.lastcol) ? c.lastcol_dst + m : c.C + (int64_t)m * ldc + n;
         float r = c.alpha * v;
-        if (e.beta != 0.f) r += e.beta * c.C[i];
-        c.C[i] = r;
+        if (e.beta != 0.f) r += e.beta * *dst;
+        *dst = r;
         if (c.C2) { const int64_t j = (int64_t)m * e.ldc2 + n; c.C2[j] += r; }
     } else if (KIND == EPI_BIAS_SIGMOID_SAMPLE) {
         const float p = sigmoidf_dev(v + c.bias[n]);
@@ -105,8 +106,10 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                 constexpr int v = decltype(vc)::value;
                 const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
                 old[v] = 0.f;
-                if (need_old && m < M && n < N)
-                    old[v] = kReadsC ? c.C[(int64_t)m * ldc + n] : c.aux[(int64_t)m * e.ldaux + n];
+                if (need_old && m < M && n < N) {
+                    if constexpr (kReadsC) old[v] = (c.lastcol_dst && n == e.lastcol) ? c.lastcol_dst[m] : c.C[(int64_t)m * ldc + n];
+                    else old[v] = c.aux[(int64_t)m * e.ldaux + n];
+                }
             });
             static_for<16>([&](auto vc) {
                 constexpr int v = decltype(vc)::value;
@@ -115,7 +118,8 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                     const float a = acc[i][j][v];
                     if constexpr (KIND == EPI_AXPBY) {
                         const float r = c.alpha * a + e.beta * old[v];
-                        c.C[(int64_t)m * ldc + n] = r;
+                        if (c.lastcol_dst && n == e.lastcol) c.lastcol_dst[m] = r;
+                        else c.C[(int64_t)m * ldc + n] = r;
                         if (c.C2) c.C2[(int64_t)m * e.ldc2 + n] += r;
                     } else if constexpr (KIND == EPI_MUL_DSIGMOID) {
                         c.C[(int64_t)m * ldc + n] = a * old[v] * (1.f - old[v]);
@@ -357,7 +361,7 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
         // split contraction: store the partial tile; gemm_reduce_kernel adds the partials in split order
         Epilogue raw;
         EpiCtx c;
-        c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr; c.rowvec = nullptr; c.alpha = 1.f;
+        c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr; c.rowvec = nullptr; c.alpha = 1.f; c.lastcol_dst = nullptr;
         c.C = p.ws + ((int64_t)bz * p.M) * p.N;
         write_tile<EPI_STORE, TM, TN>(acc, raw, c, p.N, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol);
     } else {
@@ -398,6 +402,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
         const int64_t nq = MN >> 2;
         for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256) {
             float4 s = *reinterpret_cast<const float4*>(W + q * 4);
+#pragma unroll 4
             for (int sp = 1; sp < p.splits; ++sp) {
                 const float4 t = *reinterpret_cast<const float4*>(W + sp * MN + q * 4);
                 s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
@@ -409,6 +414,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
     } else {
         for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < MN; e += (int64_t)gridDim.x * 256) {
             float s = W[e];
+#pragma unroll 8
             for (int sp = 1; sp < p.splits; ++sp) s += W[sp * MN + e];
             const int m = (int)(e / p.N), n = (int)(e - (int64_t)m * p.N);
             MAVG_EPI_DISPATCH(p.epi.kind, (epi_apply<KIND>(p.epi, c, p.ldc, p.N, m, n, s)))

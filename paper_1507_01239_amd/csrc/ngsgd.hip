@@ -221,9 +221,10 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
                                                      double* __restrict__ Wt, int bump_t) {
     extern __shared__ double smem[];
     const int r = rank;
-    double* Zs = smem;               // r x r
-    double* Us = Zs + r * r;         // r x r
-    double* cs = Us + r * r;         // 32 cos
+    const int rs = r | 1;            // odd row stride: column walks spread over the LDS banks
+    double* Zs = smem;               // r x rs
+    double* Us = Zs + r * rs;        // r x rs, holds U TRANSPOSED (row k = eigenvector k), so its update is a row rotation
+    double* cs = Us + r * rs;        // 32 cos
     double* sn = cs + 32;            // 32 sin
     double* red = sn + 32;           // 8
     int* pp = reinterpret_cast<int*>(red + 8);   // 32 + 32 pair indices
@@ -233,23 +234,28 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
     const int dim = tb.dim[slot];
     const int64_t zi = (int64_t)(tb.first + slot) * tb.batch + b;
     const double* __restrict__ Zb = Zg + zi * kMaxRank * kMaxRank;
-    for (int i = tid; i < r * r; i += 256) {
-        Zs[i] = Zb[i];
-        Us[i] = (i / r == i % r) ? 1.0 : 0.0;
-    }
+    // thread = (lane: an index along a row or column, grp: which rotation pair / which row)
+    const int lw = r <= 32 ? 32 : 64, ngrp = 256 / lw;
+    const int lane = tid & (lw - 1), grp = tid / lw;
+    for (int i = grp; i < r; i += ngrp)
+        if (lane < r) {
+            Zs[i * rs + lane] = Zb[i * r + lane];
+            Us[i * rs + lane] = (i == lane) ? 1.0 : 0.0;
+        }
     __syncthreads();
     const int m = (r + 1) & ~1;      // even number of players
     const int half = m / 2;
     for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
         // stop when the off-diagonal mass is negligible against the diagonal
         double off = 0.0, dg = 0.0;
-        for (int i = tid; i < r * r; i += 256) {
-            const double v = Zs[i];
-            if (i / r == i % r) dg += v * v; else off += v * v;
-        }
+        for (int i = grp; i < r; i += ngrp)
+            if (lane < r) {
+                const double v = Zs[i * rs + lane];
+                if (i == lane) dg += v * v; else off += v * v;
+            }
         off = block_sum_d(off, red);
         dg = block_sum_d(dg, red);
-        if (off <= 1e-26 * dg) break;       // off-diagonal norm below 1e-13 of the diagonal: eigenvalues converged to ~1e-26 relative
+        if (off <= 1e-26 * dg) break;       // off-diagonal norm below 1e-13 of the diagonal
         for (int round = 0; round < m - 1; ++round) {
             if (tid < half) {
                 int p, q;
@@ -258,9 +264,9 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
                 if (p > q) { const int t = p; p = q; q = t; }
                 double c = 1.0, s = 0.0;
                 if (q < r) {
-                    const double apq = Zs[p * r + q];
+                    const double apq = Zs[p * rs + q];
                     if (apq != 0.0) {
-                        const double tau = (Zs[q * r + q] - Zs[p * r + p]) / (2.0 * apq);
+                        const double tau = (Zs[q * rs + q] - Zs[p * rs + p]) / (2.0 * apq);
                         const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
                         c = 1.0 / sqrt(1.0 + t * t);
                         s = t * c;
@@ -269,30 +275,28 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
                 pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
             }
             __syncthreads();
-            // rows:  row_p <- c row_p - s row_q ;  row_q <- s row_p + c row_q
-            for (int w = tid; w < half * r; w += 256) {
-                const int k = w / r, j = w - k * r;
+            // rows of Z and of U^T:  row_p <- c row_p - s row_q ;  row_q <- s row_p + c row_q
+            for (int k = grp; k < half; k += ngrp) {
                 const int p = pp[k], q = qq[k];
-                if (q >= 0) {
+                if (q >= 0 && lane < r) {
                     const double c = cs[k], s = sn[k];
-                    const double zp = Zs[p * r + j], zq = Zs[q * r + j];
-                    Zs[p * r + j] = c * zp - s * zq;
-                    Zs[q * r + j] = s * zp + c * zq;
+                    const double zp = Zs[p * rs + lane], zq = Zs[q * rs + lane];
+                    Zs[p * rs + lane] = c * zp - s * zq;
+                    Zs[q * rs + lane] = s * zp + c * zq;
+                    const double up = Us[p * rs + lane], uq = Us[q * rs + lane];
+                    Us[p * rs + lane] = c * up - s * uq;
+                    Us[q * rs + lane] = s * up + c * uq;
                 }
             }
             __syncthreads();
-            // columns of Z and of U
-            for (int w = tid; w < half * r; w += 256) {
-                const int k = w / r, i = w - k * r;
+            // columns of Z
+            for (int k = grp; k < half; k += ngrp) {
                 const int p = pp[k], q = qq[k];
-                if (q >= 0) {
+                if (q >= 0 && lane < r) {
                     const double c = cs[k], s = sn[k];
-                    const double zp = Zs[i * r + p], zq = Zs[i * r + q];
-                    Zs[i * r + p] = c * zp - s * zq;
-                    Zs[i * r + q] = s * zp + c * zq;
-                    const double up = Us[i * r + p], uq = Us[i * r + q];
-                    Us[i * r + p] = c * up - s * uq;
-                    Us[i * r + q] = s * up + c * uq;
+                    const double zp = Zs[lane * rs + p], zq = Zs[lane * rs + q];
+                    Zs[lane * rs + p] = c * zp - s * zq;
+                    Zs[lane * rs + q] = s * zp + c * zq;
                 }
             }
             __syncthreads();
@@ -300,10 +304,10 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
     }
     // descending order of the eigenvalues (ties by index)
     if (tid < r) {
-        const double ci = Zs[tid * r + tid];
+        const double ci = Zs[tid * rs + tid];
         int pos = 0;
         for (int j = 0; j < r; ++j) {
-            const double cj = Zs[j * r + j];
+            const double cj = Zs[j * rs + j];
             if (cj > ci || (cj == ci && j < tid)) ++pos;
         }
         order[pos] = tid;
@@ -311,22 +315,22 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
     __syncthreads();
     const StateView v = state_view(tb.state[slot] + (int64_t)b * tb.st_b, dim, rank);
     if (tid == 0) {
-        const double cmax = Zs[order[0] * r + order[0]];
+        const double cmax = Zs[order[0] * rs + order[0]];
         double sumd = 0.0, sumsq = 0.0;
         for (int j = 0; j < r; ++j) sumd += v.d[j];
         const double rho = *v.rho;
         for (int i = 0; i < r; ++i) {
-            double c = Zs[order[i] * r + order[i]];
+            double c = Zs[order[i] * rs + order[i]];
             c = fmax(c, kCFloor * cmax);
             const double sq = sqrt(c);
-            Zs[order[i] * r + order[i]] = sq;          // keep sqrt(c_i) on the diagonal for the other threads
+            Zs[order[i] * rs + order[i]] = sq;          // keep sqrt(c_i) on the diagonal for the other threads
             sumsq += sq;
         }
         const double trT = (double)eta * tb.scal[slot][b * 2 + 0] / (double)n + (1.0 - (double)eta) * ((double)dim * rho + sumd);
         double rho_new = (trT - sumsq) / (double)(dim - rank);
         double dmax = -1e300;
         for (int i = 0; i < r; ++i) {
-            const double di = Zs[order[i] * r + order[i]] - rho_new;
+            const double di = Zs[order[i] * rs + order[i]] - rho_new;
             v.d[i] = di;
             dmax = fmax(dmax, di);
         }
@@ -341,7 +345,7 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
     for (int w = tid; w < r * r; w += 256) {
         const int i = w / r, k = w - i * r;
         const int col = order[i];
-        Wb[w] = Us[k * r + col] / Zs[col * r + col];
+        Wb[w] = Us[col * rs + k] / Zs[col * rs + col];
     }
 }
 
@@ -476,7 +480,7 @@ struct NgCall {
     } while (0)
 #define NG_LAUNCHED() NG_CHECK(note_hip_error(hipGetLastError()))
 
-int ng_eig_smem_bytes(int rank) { return (2 * rank * rank + 32 + 32 + 8) * 8 + (32 + 32 + 64) * 4; }
+int ng_eig_smem_bytes(int rank) { return (2 * rank * (rank | 1) + 32 + 32 + 8) * 8 + (32 + 32 + 64) * 4; }
 
 // Z = Y Y^T, eigen-decomposition, new (R, d, rho, t) for every (slot, replica) of the table: three launches.
 int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, double* Wt, int bump, hipStream_t s) {
@@ -704,22 +708,16 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
     c.state = a.state_out; c.dim = a.d_out; c.x = a.delta; c.ldx = a.ldd; c.x_b = a.d_bstride; c.gamma = gamma_out;
     c.defer_Y = a.ws + lay.y_off[j_out]; c.defer_scal = scal + (int64_t)j_out * a.k * 2;
     NG_CHECK(ng_run(c, s));
-    {   // W <- W - lr g_out g_in  Xh_out^T Xh_in[:, :d_in]
+    {   // [W | b] <- [W | b] - lr g_out g_in  Xh_out^T Xh_in : the last column of the product is the bias update
         GemmDesc g;
-        g.M = a.d_out; g.N = a.d_in; g.K = a.n; g.batch = a.k;
+        g.M = a.d_out; g.N = a.d_in + 1; g.K = a.n; g.batch = a.k;
         g.A = a.delta; g.lda = a.ldd; g.a_bstride = a.d_bstride; g.a_kc = false;
         g.B = Xaug; g.ldb = ld_in; g.b_bstride = aug_b; g.b_kc = false;
         g.C = a.W; g.ldc = a.d_in; g.c_bstride = a.theta_stride;
         g.epi.kind = EPI_AXPBY; g.epi.alpha = -a.lr; g.epi.beta = 1.f;
         g.epi.alpha_dev0 = gamma_in; g.epi.alpha_dev1 = gamma_out;
+        g.epi.lastcol = a.d_in; g.epi.lastcol_dst = a.b; g.epi.lastcol_bstride = a.theta_stride;
         NG_CHECK(gemm_launch(g, a.gemm_ws, a.gemm_ws_floats, s));
-    }
-    {   // b <- b - lr g_out g_in  Xh_out^T Xh_in[:, d_in]
-        ColsumExtras ex;
-        ex.roww = Xaug + a.d_in; ex.roww_ld = ld_in; ex.roww_bstride = aug_b;
-        ex.alpha_dev0 = gamma_in; ex.alpha_dev1 = gamma_out;
-        NG_CHECK(colsum_axpby_launch(a.delta, a.ldd, a.d_bstride, nullptr, 0, 0, a.b, a.theta_stride, nullptr, 0, a.n, a.d_out,
-                                     a.k, -a.lr, 1.f, s, &ex));
     }
     return 0;
 }
