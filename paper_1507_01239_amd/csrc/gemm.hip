@@ -165,6 +165,22 @@ __device__ __forceinline__ void epi_apply4(const Epilogue& e, const EpiCtx& c, i
 
 constexpr int kPad = 4;
 
+// XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so the
+// workgroups with equal (id mod 8) share an L2.  Each XCD gets one contiguous run of the tile sequence, which
+// walks fastest along the smaller operand: that one is re-read for every tile of the run and has to stay in
+// L2 (activations when M <= N, e.g. 256 x 8000; the other way round for a weight gradient), while a tile of
+// the larger operand crosses the fabric once instead of once per XCD (measured on the 256 x 8000 x 2048
+// layer: L2 fetch traffic 284 MB -> 85 MB).
+__device__ __forceinline__ void tile_coords(const GemmKParams& p, int tile, int& tm_i, int& tn_i) {
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int xcd = tile % kNumXCD, slot = tile / kNumXCD;
+    const int tq = ntiles / kNumXCD, tr = ntiles % kNumXCD;
+    const int seq = xcd * tq + min(xcd, tr) + slot;          // bijection of [0, ntiles)
+    if (p.M <= p.N) { tn_i = seq / p.tiles_m; tm_i = seq - tn_i * p.tiles_m; }
+    else { tm_i = seq / p.tiles_n; tn_i = seq - tm_i * p.tiles_n; }
+}
+
+
 // Global -> register load of one operand tile (BR rows of the non-contracted index by BK contraction
 // steps), zero-filled outside [0,R) x [k0,kend).  KC: the contraction index is the contiguous one.
 template <bool GUARD, bool KC, int NLD, int BR, int BK, int NT>
@@ -250,20 +266,8 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave / WN) * (BM / WM), wn = (wave % WN) * (BN / WN);
     const int b = bz / p.splits, split = bz - b * p.splits;
-    // XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so the
-    // workgroups with equal (id mod 8) share an L2.  Give each XCD one contiguous run of the column-major
-    // tile sequence: the tiles_m tiles that read the same B tile (the same rows of a weight matrix) then sit
-    // on one XCD in consecutive slots and the weight tile crosses the fabric once instead of once per XCD
-    // (measured on the 256 x 8000 x 2048 layer: L2 fetch traffic 284 MB -> 85 MB).
-    const int ntiles = p.tiles_m * p.tiles_n;
-    const int xcd = tile % kNumXCD, slot = tile / kNumXCD;
-    const int tq = ntiles / kNumXCD, tr = ntiles % kNumXCD;
-    const int seq = xcd * tq + min(xcd, tr) + slot;          // bijection of [0, ntiles)
-    // Walk fastest along the smaller operand: it is the one that is re-read for every tile of the run and has
-    // to stay in L2 (activations when M <= N, e.g. 256 x 8000; the other way round for a weight gradient).
     int tm_i, tn_i;
-    if (p.M <= p.N) { tn_i = seq / p.tiles_m; tm_i = seq - tn_i * p.tiles_m; }
-    else { tm_i = seq / p.tiles_n; tn_i = seq - tm_i * p.tiles_n; }
+    tile_coords(p, tile, tm_i, tn_i);
     const int m0 = tm_i * BM, n0 = tn_i * BN;
     const int kbeg = split * p.kper;
     const int kend = min(p.K, kbeg + p.kper);
@@ -375,6 +379,179 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmKParams p) {
     gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(p, blockIdx.x, blockIdx.z);
 }
 
+// ---- 64x64 tile fed by direct global -> LDS loads -------------------------------------------------
+//
+// The same 2x2 wavefronts of 32x32, but the operand tiles never pass through registers: every wavefront issues
+// two global_load_lds_dwordx4 per 16-step k-tile (1 KB of A and 1 KB of B; lane l's 16 bytes land at LDS
+// base + 16 l), into a ring of four LDS stages, three tiles ahead.  Addresses are a scalar base that advances
+// per tile plus a per-lane 32-bit offset fixed for the whole loop, so the loop holds no vector ALU work
+// besides the MFMAs: a wavefront issues in order, and vector instructions queued behind a chain of dependent
+// MFMAs (address arithmetic, and the loads that need it) would otherwise wait for that chain.
+//
+// LDS layouts.  An operand whose contraction index is contiguous in memory keeps its rows: [row][16], the
+// 16-byte chunk q of row r stored at chunk position q ^ ((r >> 1) & 3) (the xor spreads the eight rows a
+// ds_read_b128 phase touches over all banks); a lane reads one chunk = four contraction steps at once.  An
+// operand whose non-contracted index is contiguous is stored [k][64] as it comes and read with ds_read_b32.
+// Both feed the same assignment of contraction steps to MFMAs: step c (0..3) of pair p (0..1) multiplies
+// k = 8p + c in lanes 0-31 and k = 8p + 4 + c in lanes 32-63.
+//
+// Schedule of tile t (operands of t already in registers): first four MFMAs; issue the loads of tile t+3;
+// wait until the loads of tile t+1 have landed (younger ones stay in flight); barrier; read the operands of
+// tile t+1 into the other register set; last four MFMAs, which cover that LDS latency.  The stage that
+// receives tile t+3 held tile t-1, whose reads every wavefront finished before the barrier of tile t-1.
+//
+// The host picks this path only when the loads need no masking: 16-byte aligned operands and strides, a
+// contraction range per split that is a multiple of 16, row counts of m/n-contiguous operands that are
+// multiples of 4.  Rows or columns past the edge of a ragged tile are clamped to the last valid ones (their
+// products are never stored).
+constexpr int kDmaBK = 16, kDmaStages = 4;
+
+// One direct load: 16 bytes per lane from sbase + voff to LDS address lds_byte + 16 * lane.  The LDS base travels
+// in M0, which is saved and restored around the instruction.  Written as inline assembly (not the compiler's
+// builtin) on purpose: the compiler makes every LDS read wait for all such loads it knows of, which would
+// serialise the ring; here the waits are the explicit s_waitcnt vmcnt in the loop.
+__device__ __forceinline__ void dma16(uint32_t voff, const float* sbase, uint32_t lds_byte) {
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "s"(lds_byte), "v"(voff), "s"(sbase)
+                 : "memory");
+}
+
+template <bool AKC, bool BKC>
+__device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int tile, const int bz) {
+    constexpr int BK = kDmaBK, NST = kDmaStages, TILE = 64 * BK;
+    __shared__ __attribute__((aligned(1024))) float As[NST][TILE];
+    __shared__ __attribute__((aligned(1024))) float Bs[NST][TILE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lrow = lane >> 5, lcol = lane & 31;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    const int b = bz / p.splits, split = bz - b * p.splits;
+    int tm_i, tn_i;
+    tile_coords(p, tile, tm_i, tn_i);
+    const int m0 = tm_i * 64, n0 = tn_i * 64;
+    const int kbeg = split * p.kper;
+    const int kend = min(p.K, kbeg + p.kper);
+    const int nkt = (kend - kbeg) / BK;
+
+    // per-lane byte offset of this lane's 16 bytes inside the operand, and the scalar base / per-tile advance
+    auto lane_offset = [&](bool kc, int r0, int R, int64_t ld) -> uint32_t {
+        if (kc) {
+            const int r = wave * 16 + (lane >> 2), q = (lane & 3) ^ ((r >> 1) & 3);
+            const int row = min(r0 + r, R - 1);
+            return (uint32_t)(((int64_t)row * ld + q * 4) * 4);
+        }
+        const int k = wave * 4 + (lane >> 4), col = min(r0 + (lane & 15) * 4, R - 4);
+        return (uint32_t)(((int64_t)k * ld + col) * 4);
+    };
+    const uint32_t voa = lane_offset(AKC, m0, p.M, p.lda), vob = lane_offset(BKC, n0, p.N, p.ldb);
+    const float* sa = p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda);
+    const float* sb = p.B + (int64_t)b * p.b_bstride + (BKC ? (int64_t)kbeg : (int64_t)kbeg * p.ldb);
+    const int64_t stepa = AKC ? BK : BK * p.lda, stepb = BKC ? BK : BK * p.ldb;
+    const uint32_t la = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&As[0][wave * 256]);
+    const uint32_t lb = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&Bs[0][wave * 256]);
+    auto issue = [&](int t, int stage) {
+        dma16(voa, sa + t * stepa, la + stage * (TILE * 4));
+        dma16(vob, sb + t * stepb, lb + stage * (TILE * 4));
+    };
+
+    // operand reads: float offsets inside a stage
+    const int ia = wm + lcol, ib = wn + lcol;
+    int offa[2], offb[2];
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+        offa[pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ ((ia >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * 64 + ia;
+        offb[pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ ((ib >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * 64 + ib;
+    }
+    float fa[2][2][4], fb[2][2][4];
+    auto read_frags = [&](auto setc, auto stagec) {
+        constexpr int set = decltype(setc)::value, stage = decltype(stagec)::value;
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+            if (AKC) {
+                const float4 v = *reinterpret_cast<const float4*>(&As[stage][offa[pr]]);
+                fa[set][pr][0] = v.x; fa[set][pr][1] = v.y; fa[set][pr][2] = v.z; fa[set][pr][3] = v.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) fa[set][pr][c] = As[stage][offa[pr] + c * 64];
+            }
+            if (BKC) {
+                const float4 v = *reinterpret_cast<const float4*>(&Bs[stage][offb[pr]]);
+                fb[set][pr][0] = v.x; fb[set][pr][1] = v.y; fb[set][pr][2] = v.z; fb[set][pr][3] = v.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) fb[set][pr][c] = Bs[stage][offb[pr] + c * 64];
+            }
+        }
+    };
+
+    floatx16 acc[1][1];
+    acc[0][0] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    const bool do_rowsum = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0 && tid < 64;
+    float rowsum = 0.f;
+
+    if (nkt > 0) {
+#pragma unroll
+        for (int t = 0; t < NST - 1; ++t)
+            if (t < nkt) issue(t, t);
+        if (nkt >= NST - 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        auto step = [&](auto uc, const int t) {
+            constexpr int u = decltype(uc)::value;          // stage of tile t
+            constexpr int set = u & 1;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][0][c], fb[set][0][c], acc[0][0], 0, 0, 0);
+            if (do_rowsum) {      // the stage is overwritten after the coming barrier: read it before
+#pragma unroll
+                for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * 64 + tid];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + NST - 1 < nkt) {
+                issue(t + NST - 1, (u + NST - 1) % NST);
+                asm volatile("s_waitcnt vmcnt(4)" ::: "memory");      // tiles t+2, t+3 may stay in flight
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            __syncthreads();
+            if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][1][c], fb[set][1][c], acc[0][0], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        for (int t = 0; t < nkt; t += NST) {
+            step(std::integral_constant<int, 0>{}, t);
+            if (t + 1 < nkt) step(std::integral_constant<int, 1>{}, t + 1);
+            if (t + 2 < nkt) step(std::integral_constant<int, 2>{}, t + 2);
+            if (t + 3 < nkt) step(std::integral_constant<int, 3>{}, t + 3);
+        }
+    }
+
+    if (do_rowsum && m0 + tid < p.M) {
+        float* d = p.epi.rowsum_dst + (int64_t)b * p.epi.rowsum_bstride + m0 + tid;
+        float r = p.epi.rowsum_alpha * rowsum;
+        if (p.epi.rowsum_beta != 0.f) r += p.epi.rowsum_beta * *d;
+        *d = r;
+    }
+    if (p.splits > 1) {
+        Epilogue raw;
+        EpiCtx c;
+        c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr; c.rowvec = nullptr; c.alpha = 1.f; c.lastcol_dst = nullptr;
+        c.C = p.ws + ((int64_t)bz * p.M) * p.N;
+        write_tile<EPI_STORE, 1, 1>(acc, raw, c, p.N, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol);
+    } else {
+        const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
+        MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol)))
+    }
+}
+
+template <bool AKC, bool BKC>
+__global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
+    gemm_dma_body<AKC, BKC>(p, blockIdx.x, blockIdx.z);
+}
+
 // Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
 // layers): workgroup x belongs to the group whose tile range contains it.  Contractions are not split here.
 constexpr int kMaxGroups = 8;
@@ -390,6 +567,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_grouped_kernel(GemmGroupPar
     for (int i = 1; i < gp.ngroups; ++i)
         if ((int)blockIdx.x >= gp.tile_start[i]) gi = i;
     gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(gp.g[gi], (int)blockIdx.x - gp.tile_start[gi], blockIdx.z);
+}
+
+template <bool AKC, bool BKC>
+__global__ __launch_bounds__(256) void gemm_dma_grouped_kernel(GemmGroupParams gp) {
+    int gi = 0;
+    for (int i = 1; i < gp.ngroups; ++i)
+        if ((int)blockIdx.x >= gp.tile_start[i]) gi = i;
+    gemm_dma_body<AKC, BKC>(gp.g[gi], (int)blockIdx.x - gp.tile_start[gi], blockIdx.z);
 }
 
 // Sum the partial results of a split contraction in split order and apply the epilogue.
@@ -435,8 +620,9 @@ static const TileCfg kCfgs[] = {
     {256, 128, 16, 512},   // 5: 4x2 wavefronts of 64x64
     {128, 64, 32, 256},    // 6: as 3 with 32 contraction steps per stage
     {64, 64, 32, 256},     // 7: as 1 with 32 contraction steps per stage
+    {64, 64, 16, 256},     // 8: as 1, but never the direct-to-LDS variant (1 uses it whenever the operands allow)
 };
-constexpr int kNumCfgs = 8;
+constexpr int kNumCfgs = 9;
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
@@ -486,6 +672,26 @@ static void launch_cfg(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hi
 
 static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
+// May the direct-to-LDS kernel run this problem?  Its loads are unmasked 16-byte loads.
+static bool dma_eligible(const GemmDesc& d, const GemmKParams& p) {
+    if (!p.vecA || !p.vecB) return false;
+    if (d.K < kDmaBK || d.K % kDmaBK != 0 || p.kper % kDmaBK != 0) return false;
+    if (!d.a_kc && (d.M < 4 || d.M % 4 != 0)) return false;
+    if (!d.b_kc && (d.N < 4 || d.N % 4 != 0)) return false;
+    const int64_t lim = (int64_t)1 << 29;      // per-lane offsets are 32-bit byte offsets
+    if ((d.a_kc ? (int64_t)d.M * d.lda : kDmaBK * d.lda + d.M) >= lim) return false;
+    if ((d.b_kc ? (int64_t)d.N * d.ldb : kDmaBK * d.ldb + d.N) >= lim) return false;
+    return true;
+}
+
+static void launch_dma(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
+    const dim3 block(256);
+    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_kernel<true, true>), grid, block, 0, s, p);
+    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<true, false>), grid, block, 0, s, p);
+    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<false, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((gemm_dma_kernel<false, true>), grid, block, 0, s, p);
+}
+
 static GemmKParams fill_params(const GemmDesc& d, const GemmPlan& pl, float* ws) {
     GemmKParams p;
     p.A = d.A; p.lda = d.lda; p.a_bstride = d.a_bstride;
@@ -514,9 +720,10 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     const GemmKParams p = fill_params(d, pl, ws);
     if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return note_hip_error(hipErrorInvalidValue);
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
-    switch (pl.cfg) {
+    if (pl.cfg == 1 && dma_eligible(d, p)) launch_dma(p, d.a_kc, d.b_kc, grid, stream);
+    else switch (pl.cfg) {
     case 0: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 1: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 1: case 8: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 2: launch_cfg<128, 128, 16, 2, 4, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 3: launch_cfg<128, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 4: launch_cfg<64, 128, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
@@ -543,6 +750,7 @@ int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
         GemmGroupParams gp;
         gp.ngroups = 0;
         int tiles = 0;
+        bool dma = true;
         for (int i = 0; i < ng; ++i) {
             const GemmDesc& di = d[c0 + i];
             if (di.M <= 0 || di.N <= 0 || di.batch <= 0) continue;
@@ -550,6 +758,7 @@ int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
             if (di.epi.rowsum_dst != nullptr && di.a_kc) return note_hip_error(hipErrorInvalidValue);
             const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, 1, 1);      // 64x64 tiles, unsplit
             gp.g[gp.ngroups] = fill_params(di, pl, nullptr);
+            dma = dma && dma_eligible(di, gp.g[gp.ngroups]);
             gp.tile_start[gp.ngroups] = tiles;
             tiles += gp.g[gp.ngroups].tiles_m * gp.g[gp.ngroups].tiles_n;
             ++gp.ngroups;
@@ -558,7 +767,12 @@ int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
         gp.tile_start[gp.ngroups] = tiles;
         const dim3 grid((unsigned)tiles, 1, (unsigned)d[c0].batch), block(256);
         const bool a_kc = d[c0].a_kc, b_kc = d[c0].b_kc;
-        if (a_kc && b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, true>), grid, block, 0, stream, gp);
+        if (dma) {
+            if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, true>), grid, block, 0, stream, gp);
+            else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, false>), grid, block, 0, stream, gp);
+            else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, false>), grid, block, 0, stream, gp);
+            else hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, true>), grid, block, 0, stream, gp);
+        } else if (a_kc && b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, true>), grid, block, 0, stream, gp);
         else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, false>), grid, block, 0, stream, gp);
         else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, false>), grid, block, 0, stream, gp);
         else hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, true>), grid, block, 0, stream, gp);

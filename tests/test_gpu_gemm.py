@@ -58,6 +58,28 @@ def test_epilogues_with_and_without_split(epi, splits):
     assert _run(70, 132, 260, 0, 0, epi=epi, cfg=1, splits=splits, seed=4, alpha=0.25, beta=0.5) < 3e-6
 
 
+@pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
+@pytest.mark.parametrize("cfg", [1, 8])
+def test_direct_to_lds_variant_and_its_register_staged_twin(a_kc, b_kc, cfg):
+    # shapes the direct-to-LDS 64x64 kernel accepts (16-byte aligned rows, contraction a multiple of 16); cfg 1
+    # runs it, cfg 8 forces the register-staged kernel on the same problem.  Ragged tile edges in m and n
+    # (clamped loads), one to many k-tiles (ring start-up and tail), padded leading dimensions, splits.
+    assert _run(200, 328, 144, a_kc, b_kc, cfg=cfg, seed=21) < 2e-6
+    assert _run(132, 68, 16, a_kc, b_kc, cfg=cfg, seed=22, pad=4) < 2e-6
+    assert _run(64, 64, 32, a_kc, b_kc, cfg=cfg, seed=23) < 2e-6
+    assert _run(60, 124, 48, a_kc, b_kc, cfg=cfg, seed=24, pad=8) < 2e-6
+    assert _run(256, 192, 1040, a_kc, b_kc, cfg=cfg, seed=25) < 3e-6
+    assert _run(128, 256, 640, a_kc, b_kc, cfg=cfg, splits=5, seed=26, epi=2) < 3e-6
+    assert _run(4, 4, 80, a_kc, b_kc, cfg=cfg, seed=27) < 2e-6
+
+
+@pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
+def test_direct_to_lds_epilogues(epi):
+    assert _run(96, 160, 208, 1, 1, epi=epi, cfg=1, splits=1, seed=31, alpha=-0.5, beta=1.0) < 3e-6
+    assert _run(72, 132, 256, 0, 0, epi=epi, cfg=1, splits=2, seed=32, alpha=0.25, beta=0.5) < 3e-6
+    assert _run(100, 64, 96, 1, 0, epi=epi, cfg=1, splits=1, seed=33, alpha=2.0, beta=-1.0) < 3e-6
+
+
 def test_unaligned_operands_use_the_scalar_path():
     # leading dimensions that are not multiples of 4 (e.g. the paper's 8806-wide output layer)
     assert _run(37, 45, 51, 1, 1, seed=5, pad=1) < 2e-6
