@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the averaging / CD-1 side measurements")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle leg")
+    ap.add_argument("--no-warm", action="store_true",
+                    help="skip the clock warm-up bursts (for hardware-counter runs, where every launch is serialised)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (a kernel of known traffic, to scale HBM byte counters)")
     args = ap.parse_args()
@@ -91,6 +93,8 @@ def main():
     wws = torch.empty(B.mavg_gemm_workspace_bytes(n, dims[-1], dims[-2], -1, 0) + 256, dtype=torch.uint8, device="cuda")
 
     def warm_clocks(seconds=0.3):
+        if args.no_warm:
+            return
         t_end = time.perf_counter() + seconds
         while time.perf_counter() < t_end:
             for _ in range(200):

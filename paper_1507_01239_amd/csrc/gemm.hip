@@ -418,6 +418,13 @@ __device__ __forceinline__ void dma16(uint32_t voff, const float* sbase, uint32_
                  : "memory");
 }
 
+// Pin a workgroup-uniform 64-bit value to scalar registers (the compiler cannot always prove uniformity, e.g.
+// for fields of a kernel-argument array indexed by the workgroup's group number).
+__device__ __forceinline__ uint64_t uniform_u64(uint64_t x) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
 template <bool AKC, bool BKC>
 __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int tile, const int bz) {
     constexpr int BK = kDmaBK, NST = kDmaStages, TILE = 64 * BK;
@@ -432,7 +439,7 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
     const int m0 = tm_i * 64, n0 = tn_i * 64;
     const int kbeg = split * p.kper;
     const int kend = min(p.K, kbeg + p.kper);
-    const int nkt = (kend - kbeg) / BK;
+    const int nkt = __builtin_amdgcn_readfirstlane((kend - kbeg) / BK);
 
     // per-lane byte offset of this lane's 16 bytes inside the operand, and the scalar base / per-tile advance
     auto lane_offset = [&](bool kc, int r0, int R, int64_t ld) -> uint32_t {
@@ -445,9 +452,12 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         return (uint32_t)(((int64_t)k * ld + col) * 4);
     };
     const uint32_t voa = lane_offset(AKC, m0, p.M, p.lda), vob = lane_offset(BKC, n0, p.N, p.ldb);
-    const float* sa = p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda);
-    const float* sb = p.B + (int64_t)b * p.b_bstride + (BKC ? (int64_t)kbeg : (int64_t)kbeg * p.ldb);
-    const int64_t stepa = AKC ? BK : BK * p.lda, stepb = BKC ? BK : BK * p.ldb;
+    const float* sa = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
+        p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda))));
+    const float* sb = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
+        p.B + (int64_t)b * p.b_bstride + (BKC ? (int64_t)kbeg : (int64_t)kbeg * p.ldb))));
+    const int64_t stepa = (int64_t)uniform_u64((uint64_t)(AKC ? BK : BK * p.lda));
+    const int64_t stepb = (int64_t)uniform_u64((uint64_t)(BKC ? BK : BK * p.ldb));
     const uint32_t la = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&As[0][wave * 256]);
     const uint32_t lb = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&Bs[0][wave * 256]);
     auto issue = [&](int t, int stage) {
@@ -561,20 +571,31 @@ struct GemmGroupParams {
     int ngroups;
 };
 
+// Copy the parameters of the group this workgroup belongs to and return the group's first workgroup id.
+// Every index is a compile-time constant (a run-time index into the by-value kernel argument would send the
+// whole array through private memory); the selects are scalar, the condition being workgroup-uniform.
+__device__ __forceinline__ int select_group(const GemmGroupParams& gp, GemmKParams& p) {
+    p = gp.g[0];
+    int first = 0;
+    static_for<kMaxGroups - 1>([&](auto ic) {
+        constexpr int i = decltype(ic)::value + 1;
+        if (i < gp.ngroups && (int)blockIdx.x >= gp.tile_start[i]) { p = gp.g[i]; first = gp.tile_start[i]; }
+    });
+    return first;
+}
+
 template <int BM, int BN, int BK, int WM, int WN, int PF, bool AKC, bool BKC>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_grouped_kernel(GemmGroupParams gp) {
-    int gi = 0;
-    for (int i = 1; i < gp.ngroups; ++i)
-        if ((int)blockIdx.x >= gp.tile_start[i]) gi = i;
-    gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(gp.g[gi], (int)blockIdx.x - gp.tile_start[gi], blockIdx.z);
+    GemmKParams p;
+    const int first = select_group(gp, p);
+    gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
 template <bool AKC, bool BKC>
 __global__ __launch_bounds__(256) void gemm_dma_grouped_kernel(GemmGroupParams gp) {
-    int gi = 0;
-    for (int i = 1; i < gp.ngroups; ++i)
-        if ((int)blockIdx.x >= gp.tile_start[i]) gi = i;
-    gemm_dma_body<AKC, BKC>(gp.g[gi], (int)blockIdx.x - gp.tile_start[gi], blockIdx.z);
+    GemmKParams p;
+    const int first = select_group(gp, p);
+    gemm_dma_body<AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
 // Sum the partial results of a split contraction in split order and apply the epilogue.
