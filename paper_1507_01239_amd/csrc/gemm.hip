@@ -86,58 +86,85 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
     }
 }
 
+// Element at byte offset `off` from a pointer that is uniform over the wavefront: the form the hardware addresses
+// as scalar base + 32-bit per-lane offset, which costs one vector register per access pattern instead of a
+// 64-bit address per access.
+__device__ __forceinline__ float* at_off(float* ubase, uint32_t off) {
+    return reinterpret_cast<float*>(reinterpret_cast<char*>(ubase) + off);
+}
+__device__ __forceinline__ const float* at_off(const float* ubase, uint32_t off) {
+    return reinterpret_cast<const float*>(reinterpret_cast<const char*>(ubase) + off);
+}
+
 // Write a wavefront's accumulators through epilogue KIND.  Accumulator element v of a lane sits at
-// row 8*(v/4) + 4*(lane/32) + v%4, column lane%32 of its 32x32 block.
+// row 8*(v/4) + 4*(lane/32) + v%4, column lane%32 of its 32x32 block.  `mbase` is uniform over the wavefront.
+// Every access is (uniform row pointer) + (per-lane byte offset): row 8*(v/4) + v%4 of the block goes into the
+// scalar pointer, the lane's 4*(lane/32) rows and its column into one offset register per matrix.
 template <int KIND, int TM, int TN>
 __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const Epilogue& e, const EpiCtx& c,
                                            int64_t ldc, int M, int N, int mbase, int nbase, int lrow, int lcol) {
     constexpr bool kReadsC = KIND == EPI_AXPBY;
     constexpr bool kReadsAux = KIND == EPI_MUL_DSIGMOID || KIND == EPI_ROWSCALE_ADD;
-    if constexpr (kReadsC || kReadsAux) {
-        // read-modify-write epilogues: issue the 16 loads of a 32x32 block back to back, then combine and
-        // store, so that their latencies overlap instead of adding up
-        const bool need_old = kReadsAux || e.beta != 0.f;
-        static_for<TM * TN>([&](auto bc) {
-            constexpr int t = decltype(bc)::value;
-            constexpr int i = t / TN, j = t % TN;
-            const int n = nbase + j * 32 + lcol;
-            float old[16];
+    constexpr bool kBias = KIND == EPI_BIAS || KIND == EPI_BIAS_SIGMOID || KIND == EPI_BIAS_SIGMOID_SAMPLE;
+    const int mb = __builtin_amdgcn_readfirstlane(mbase);
+    static_for<TM * TN>([&](auto bc) {
+        constexpr int t = decltype(bc)::value;
+        constexpr int i = t / TN, j = t % TN;
+        const int n = nbase + j * 32 + lcol;
+        const bool n_ok = n < N;
+        const uint32_t offC = (uint32_t)(((int64_t)(4 * lrow) * ldc + n) * 4);
+        const uint32_t offAux = kReadsAux ? (uint32_t)(((int64_t)(4 * lrow) * e.ldaux + n) * 4) : 0u;
+        const uint32_t offC2 = (KIND == EPI_AXPBY || KIND == EPI_BIAS_SIGMOID_SAMPLE) ? (uint32_t)(((int64_t)(4 * lrow) * e.ldc2 + n) * 4) : 0u;
+        const bool lastcol = KIND == EPI_AXPBY && c.lastcol_dst != nullptr && n == e.lastcol;
+        float bias_n = 0.f;
+        if (kBias && n_ok) bias_n = c.bias[n];
+        float old[16];
+        if constexpr (kReadsC || kReadsAux) {
+            // read-modify-write epilogues: issue the 16 loads of a 32x32 block back to back, then combine and
+            // store, so that their latencies overlap instead of adding up
+            const bool need_old = kReadsAux || e.beta != 0.f;
             static_for<16>([&](auto vc) {
                 constexpr int v = decltype(vc)::value;
-                const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
+                const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
+                const int m = mu + 4 * lrow;
                 old[v] = 0.f;
-                if (need_old && m < M && n < N) {
-                    if constexpr (kReadsC) old[v] = (c.lastcol_dst && n == e.lastcol) ? c.lastcol_dst[m] : c.C[(int64_t)m * ldc + n];
-                    else old[v] = c.aux[(int64_t)m * e.ldaux + n];
+                if (need_old && m < M && n_ok) {
+                    if constexpr (kReadsC) old[v] = lastcol ? c.lastcol_dst[m] : *at_off(c.C + (int64_t)mu * ldc, offC);
+                    else old[v] = *at_off(c.aux + (int64_t)mu * e.ldaux, offAux);
                 }
             });
-            static_for<16>([&](auto vc) {
-                constexpr int v = decltype(vc)::value;
-                const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
-                if (m < M && n < N) {
-                    const float a = acc[i][j][v];
-                    if constexpr (KIND == EPI_AXPBY) {
-                        const float r = c.alpha * a + e.beta * old[v];
-                        if (c.lastcol_dst && n == e.lastcol) c.lastcol_dst[m] = r;
-                        else c.C[(int64_t)m * ldc + n] = r;
-                        if (c.C2) c.C2[(int64_t)m * e.ldc2 + n] += r;
-                    } else if constexpr (KIND == EPI_MUL_DSIGMOID) {
-                        c.C[(int64_t)m * ldc + n] = a * old[v] * (1.f - old[v]);
-                    } else {
-                        c.C[(int64_t)m * ldc + n] = c.alpha * a + c.rowvec[m] * old[v];
-                    }
+        }
+        static_for<16>([&](auto vc) {
+            constexpr int v = decltype(vc)::value;
+            const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
+            const int m = mu + 4 * lrow;
+            if (m < M && n_ok) {
+                const float a = acc[i][j][v];
+                float* dst = at_off(c.C + (int64_t)mu * ldc, offC);
+                if constexpr (KIND == EPI_STORE) {
+                    *dst = a;
+                } else if constexpr (KIND == EPI_BIAS) {
+                    *dst = a + bias_n;
+                } else if constexpr (KIND == EPI_BIAS_SIGMOID) {
+                    *dst = sigmoidf_dev(a + bias_n);
+                } else if constexpr (KIND == EPI_MUL_DSIGMOID) {
+                    *dst = a * old[v] * (1.f - old[v]);
+                } else if constexpr (KIND == EPI_AXPBY) {
+                    const float r = c.alpha * a + e.beta * old[v];
+                    if (lastcol) c.lastcol_dst[m] = r;
+                    else *dst = r;
+                    if (c.C2) *at_off(c.C2 + (int64_t)mu * e.ldc2, offC2) += r;
+                } else if constexpr (KIND == EPI_BIAS_SIGMOID_SAMPLE) {
+                    const float pr = sigmoidf_dev(a + bias_n);
+                    if (c.C) *dst = pr;
+                    const float u = philox_uniform((uint64_t)m * (uint64_t)N + (uint64_t)n, e.key0, e.key1, e.step, e.layer, e.phase);
+                    *at_off(c.C2 + (int64_t)mu * e.ldc2, offC2) = (u < pr) ? 1.f : 0.f;
+                } else {      // EPI_ROWSCALE_ADD
+                    *dst = c.alpha * a + c.rowvec[m] * old[v];
                 }
-            });
+            }
         });
-    } else {
-        static_for<TM * TN * 16>([&](auto tc) {
-            constexpr int t = decltype(tc)::value;
-            constexpr int i = t / (TN * 16), j = (t / 16) % TN, v = t % 16;
-            const int n = nbase + j * 32 + lcol;
-            const int m = mbase + i * 32 + 8 * (v >> 2) + 4 * lrow + (v & 3);
-            if (m < M && n < N) epi_apply<KIND>(e, c, ldc, N, m, n, acc[i][j][v]);
-        });
-    }
+    });
 }
 
 // Apply epilogue `kind` to four consecutive elements of a row (the split-contraction reducer).
