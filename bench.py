@@ -25,7 +25,7 @@ PEAK_HBM_GBPS = 8000.0
 # HBM-side traffic of one launch of the roofline kernel (256 x 8000 x 2048 forward GEMM), from the two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size) summarised in
 # profiles/gemm_output_layer_forward_hbm_counters.md: 85.2 MB fetched + 8.2 MB written.
-ROOFLINE_TRAFFIC_BYTES = {256: 93.4e6}
+ROOFLINE_TRAFFIC_BYTES = {256: 106.9e6}
 
 
 def log(msg):
