@@ -24,7 +24,7 @@ PEAK_FP32_MFMA_TFLOPS = 157.3     # 256 CU x 4 SIMD x 64 FLOP/cycle x 2.4 GHz
 PEAK_HBM_GBPS = 8000.0
 # HBM-side traffic of one launch of the roofline kernel (256 x 8000 x 2048 forward GEMM), from the two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size) summarised in
-# profiles/gemm_output_layer_forward_hbm_counters.md: 85.2 MB fetched + 8.2 MB written.
+# profiles/gemm_output_layer_forward_hbm_counters.md: 98.7 MB fetched + 8.2 MB written.
 ROOFLINE_TRAFFIC_BYTES = {256: 106.9e6}
 
 
@@ -135,7 +135,7 @@ def main():
     torch.cuda.synchronize()
     gemm_ms = e0.elapsed_time(e1) / reps
     gemm_tflops = 2.0 * M * N * K / (gemm_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"gemm_kernel fp32 {M}x{N}x{K} (output layer, forward)",
+    roofline = {"bound": "mfma", "kernel": f"gemm_dma_kernel fp32 {M}x{N}x{K} (output layer, forward)",
                 "achieved": round(gemm_tflops, 3), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(gemm_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": ROOFLINE_TRAFFIC_BYTES.get(n),
                 "avg_launch_us": round(gemm_ms * 1e3, 2)}
