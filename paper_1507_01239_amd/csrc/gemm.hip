@@ -1,11 +1,13 @@
-// fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32), LDS-staged and double-buffered, with
-// the fused epilogues the training path needs and a deterministic split of the contraction for
-// problems with too few output tiles to fill 256 compute units.
+// fp32 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x2_f32) with the fused epilogues the training path
+// needs and a deterministic split of the contraction for problems with too few output tiles to fill 256
+// compute units.
 //
-// One workgroup = 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN output tile; each
-// wavefront owns (BM/2) x (BN/2) as a grid of 32x32 MFMA accumulators.  Operand tiles are staged
-// in LDS k-major ([k][m] and [k][n]), so a lane's MFMA operand is one ds_read_b32 whose 32 lanes
-// read 32 consecutive floats.
+// Two families of kernels share the epilogues, the tile order and the split-contraction reducer:
+//  - gemm_dma_kernel: 64x64 tiles whose operands go from global memory straight into an LDS ring
+//    (global_load_lds_dwordx4); the kernel of the training step whenever the loads need no masking;
+//  - gemm_kernel<BM,BN,BK,...>: register-staged tiles of several shapes, with guarded loads for ragged and
+//    unaligned operands.  One workgroup = WM x WN wavefronts over a BM x BN tile, each wavefront owning a grid
+//    of 32x32 MFMA accumulators; operand tiles staged in LDS k-major ([k][m], [k][n]), double-buffered.
 #include "gemm.h"
 #include "../../include/mavg.h"
 #include "device_math.h"
