@@ -165,6 +165,30 @@ int32_t rbm_hidden_prob(int32_t n_vis, int32_t n_hid, const float* w, const floa
                         const float* v, int32_t n, float* out,
                         void* workspace, int64_t workspace_bytes, void* stream);
 
+/* ---- DNN initialisation from a pretrained RBM  (Sec. 5.1: the networks are initialised from a stack of RBMs
+        trained layer by layer; Sec. 5.3, Table 2 compares it with a random start) --------------------------- */
+/*
+ * Hidden layer `layer` (1-based) of each of the k replicas takes the RBM's parameters:
+ *   W_layer <- w  (device, d_layer x d_{layer-1} row-major, the RBM's n_hid x n_vis matrix),
+ *   b_layer <- c  (device, d_layer, the RBM's hidden bias).  The visible bias is not used.
+ * theta as in dnn_forward (device, read-write here); w, c are not modified.  Asynchronous on `stream`.
+ * Errors: MAVG_E_NULL, MAVG_E_DIM (layer outside 1..n_layers, k < 1), MAVG_E_ALIGN (theta_stride < P), MAVG_E_LAUNCH.
+ */
+int32_t dnn_init_layer_from_rbm(const mavg_shape* shape, int32_t k, float* theta, int64_t theta_stride,
+                                int32_t layer, const float* w, const float* c, void* stream);
+
+/* ---- frame accuracy  (Sec. 5.6: the learning-rate schedule is driven by the frame accuracy on held-out
+        data) ------------------------------------------------------------------------------------------- */
+/*
+ * correct[r] (device, int32[k], overwritten) <- number of rows i < n of replica r whose largest posterior
+ * acts_L(i, :) (as left by dnn_forward; lowest class index among equal maxima) is labels[r*label_stride + i].
+ * The comparison is made on the float32 posteriors.  acts / act_stride / labels / label_stride as in
+ * dnn_backward_update.  Asynchronous on `stream`.
+ * Errors: MAVG_E_NULL, MAVG_E_DIM, MAVG_E_ALIGN (strides too small for k > 1), MAVG_E_LAUNCH.
+ */
+int32_t dnn_count_correct(const mavg_shape* shape, int32_t k, const float* acts, int64_t act_stride,
+                          const int32_t* labels, int64_t label_stride, int32_t n, int32_t* correct, void* stream);
+
 /* ---- NG-SGD preconditioner  (Sec. 4, eq. 4: theta <- theta + alpha E g, E symmetric positive definite,
         standing for the inverse Fisher matrix of eq. 5, approximated online at low rank) ---------- */
 /*

@@ -68,6 +68,8 @@ _SIG = {
     "dnn_backward_update": (_i32, [_p, _i32, _p, _i64, _p, _i64, _p, _i64, _i32, _p, _i64, _f, _u32,
                                    _p, _i64, _i32, _f, _f, _p, _p, _i64, _p]),
     "replicas_average": (_i32, [_p, _i64, _i64, _i32, _p]),
+    "dnn_init_layer_from_rbm": (_i32, [_p, _i32, _p, _i64, _i32, _p, _p, _p]),
+    "dnn_count_correct": (_i32, [_p, _i32, _p, _i64, _p, _i64, _i32, _p, _p]),
     "rbm_workspace_bytes": (_i64, [_i32, _i32, _i32]),
     "rbm_cd1_step": (_i32, [_i32, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _i32, _f, _f, _u64, _u32, _u32, _u32,
                             _p, _p, _p, _p, _p, _i64, _p]),
@@ -154,6 +156,16 @@ def dnn_backward_update(shape, k, theta, theta_stride, x, x_stride, labels, labe
 
 def replicas_average(theta, theta_stride, count, k, stream=None):
     return _check(lib.replicas_average(ptr(theta), theta_stride, count, k, _stream(stream)), "replicas_average")
+
+
+def dnn_init_layer_from_rbm(shape, k, theta, theta_stride, layer, w, c, stream=None):
+    return _check(lib.dnn_init_layer_from_rbm(shape.ref, k, ptr(theta), theta_stride, layer, ptr(w), ptr(c), _stream(stream)),
+                  "dnn_init_layer_from_rbm")
+
+
+def dnn_count_correct(shape, k, acts, act_stride, labels, label_stride, n, correct, stream=None):
+    return _check(lib.dnn_count_correct(shape.ref, k, ptr(acts), act_stride, ptr(labels), label_stride, n, ptr(correct),
+                                        _stream(stream)), "dnn_count_correct")
 
 
 def rbm_workspace_bytes(n_vis, n_hid, n) -> int:

@@ -249,3 +249,30 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
     }
     return MAVG_OK;
 }
+
+extern "C" int32_t dnn_init_layer_from_rbm(const mavg_shape* shape, int32_t k, float* theta, int64_t theta_stride,
+                                           int32_t layer, const float* w, const float* c, void* stream) {
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!theta || !w || !c) return MAVG_E_NULL;
+    if (k < 1 || layer < 1 || layer > shape->n_layers) return MAVG_E_DIM;
+    const Layout y = make_layout(shape, 1);
+    if (k > 1 && theta_stride < y.P) return MAVG_E_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (copy_bcast_launch(w, (int64_t)y.d[layer] * y.d[layer - 1], theta + y.w_off[layer], theta_stride, k, s) != 0) return MAVG_E_LAUNCH;
+    if (copy_bcast_launch(c, y.d[layer], theta + y.b_off[layer], theta_stride, k, s) != 0) return MAVG_E_LAUNCH;
+    return MAVG_OK;
+}
+
+extern "C" int32_t dnn_count_correct(const mavg_shape* shape, int32_t k, const float* acts, int64_t act_stride,
+                                     const int32_t* labels, int64_t label_stride, int32_t n, int32_t* correct, void* stream) {
+    const int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!acts || !labels || !correct) return MAVG_E_NULL;
+    if (k < 1 || n < 1) return MAVG_E_DIM;
+    const Layout y = make_layout(shape, n);
+    if (k > 1 && (act_stride < y.acts || label_stride < n)) return MAVG_E_ALIGN;
+    if (count_correct_launch(acts + y.a_off[y.L], y.d[y.L], act_stride, labels, label_stride, n, y.d[y.L], k, correct,
+                             static_cast<hipStream_t>(stream)) != 0) return MAVG_E_LAUNCH;
+    return MAVG_OK;
+}

@@ -209,4 +209,65 @@ int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, 
     return sum_segments_launch(partial, kSqBlocks, 1, out, s);
 }
 
+// ---- broadcast copy: dst[b*dst_bstride + i] = src[i] -------------------------------------------------
+__global__ __launch_bounds__(kThreads) void copy_bcast_kernel(const float* __restrict__ src, int64_t count,
+                                                              float* __restrict__ dst, int64_t dst_bstride) {
+    float* d = dst + (int64_t)blockIdx.y * dst_bstride;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += (int64_t)gridDim.x * kThreads) d[i] = src[i];
+}
+
+int copy_bcast_launch(const float* src, int64_t count, float* dst, int64_t dst_bstride, int batch, hipStream_t s) {
+    if (count <= 0 || batch <= 0) return 0;
+    int64_t gx = (count + kThreads - 1) / kThreads;
+    if (gx > 8192) gx = 8192;
+    hipLaunchKernelGGL(copy_bcast_kernel, dim3((unsigned)gx, (unsigned)batch), dim3(kThreads), 0, s, src, count, dst, dst_bstride);
+    return note_hip_error(hipGetLastError());
+}
+
+// ---- frames whose largest posterior is the label's ---------------------------------------------------
+__global__ void zero_i32_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// One workgroup per row: arg max over the row (lowest index among equal maxima), compared with the label;
+// integer atomic count per batch entry (order-independent, so the result is reproducible).
+__global__ __launch_bounds__(kThreads) void argmax_correct_kernel(const float* __restrict__ p, int64_t ld, int64_t bstride,
+                                                                  const int32_t* __restrict__ labels, int64_t label_bstride,
+                                                                  int cols, int32_t* __restrict__ correct) {
+    __shared__ float shv[kThreads / 64];
+    __shared__ int shi[kThreads / 64];
+    const int row = blockIdx.x, b = blockIdx.y;
+    const float* r = p + (int64_t)b * bstride + (int64_t)row * ld;
+    float best = -INFINITY;
+    int idx = 0x7fffffff;
+    for (int j = threadIdx.x; j < cols; j += kThreads) {
+        const float v = r[j];
+        if (v > best) { best = v; idx = j; }       // ascending j per thread: the first maximum is kept
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_down(best, off, 64);
+        const int oi = __shfl_down(idx, off, 64);
+        if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { shv[wave] = best; shi[wave] = idx; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kThreads / 64; ++w)
+            if (shv[w] > best || (shv[w] == best && shi[w] < idx)) { best = shv[w]; idx = shi[w]; }
+        if (idx == labels[(int64_t)b * label_bstride + row]) atomicAdd(&correct[b], 1);
+    }
+}
+
+int count_correct_launch(const float* p, int64_t ld, int64_t bstride, const int32_t* labels, int64_t label_bstride,
+                         int rows, int cols, int batch, int32_t* correct, hipStream_t s) {
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)((batch + 63) / 64)), dim3(64), 0, s, correct, batch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return note_hip_error(e);
+    hipLaunchKernelGGL(argmax_correct_kernel, dim3((unsigned)rows, (unsigned)batch), dim3(kThreads), 0, s, p, ld, bstride,
+                       labels, label_bstride, cols, correct);
+    return note_hip_error(hipGetLastError());
+}
+
 }  // namespace mavg

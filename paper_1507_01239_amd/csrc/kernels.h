@@ -36,4 +36,12 @@ int sqdiff_partials();
 int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, int rows, int cols,
                       float* partial, float* out, hipStream_t s);
 
+// dst[b*dst_bstride + i] = src[i], i < count, b < batch.
+int copy_bcast_launch(const float* src, int64_t count, float* dst, int64_t dst_bstride, int batch, hipStream_t s);
+
+// correct[b] = number of rows n < rows whose arg max over p[b](n, :) (lowest index among equal maxima) equals
+// labels[b*label_bstride + n].
+int count_correct_launch(const float* p, int64_t ld, int64_t bstride, const int32_t* labels, int64_t label_bstride,
+                         int rows, int cols, int batch, int32_t* correct, hipStream_t s);
+
 }  // namespace mavg
