@@ -255,7 +255,46 @@ def main():
                                                "mfma_frac": round(Kr * nb / ms * 1e3 * flop_per_frame / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4)}
                 del xb, yb, ac, w8
             return out
+        # the paper's own shape (Sec. 5.1, 5.5): 440-6x2048-8806, minibatch 1024, m replicas averaged every
+        # 10 or 20 minibatches; m = 8, 16, 32 replicas all resident on the one GPU
+        def paper_shape():
+            pd = gen.CONFIG_PAPER_DIMS
+            pshape = B.Shape(pd)
+            PP = B.mavg_param_count(pshape)
+            pstride = (PP + 63) // 64 * 64
+            pflop = 2 * (3 * sum(pd[l] * pd[l - 1] for l in range(1, len(pd))) - pd[1] * pd[0])
+            nb, out = 1024, {}
+            th1 = torch.from_numpy(gen.init_theta(pd, seed, 0.05)).cuda()
+            for Kr in (8, 16, 32):
+                th = torch.zeros(Kr, pstride, device="cuda")
+                th[:, :PP] = th1
+                xb = torch.stack([torch.from_numpy(gen.features_speech_like(nb, pd[0], seed, r, 0)) for r in range(Kr)]).cuda()
+                yb = torch.stack([torch.from_numpy(gen.labels_zipf(nb, pd[-1], seed, r, 0)) for r in range(Kr)]).cuda()
+                astride = (B.mavg_act_count(pshape, nb) + 63) // 64 * 64
+                ac = torch.empty(Kr, astride, device="cuda")
+                wp = torch.empty(B.mavg_workspace_bytes(pshape, nb, Kr, B.MEAN_GRAD) + 256, dtype=torch.uint8, device="cuda")
+                for n_avg in (10, 20):
+                    def run(steps_):
+                        for t in range(steps_):
+                            B.dnn_forward(pshape, Kr, th, pstride, xb, nb * pd[0], nb, ac, astride, wp)
+                            B.dnn_backward_update(pshape, Kr, th, pstride, xb, nb * pd[0], yb, nb, nb, ac, astride, lr, B.MEAN_GRAD, None, wp)
+                            if (t + 1) % n_avg == 0:
+                                B.replicas_average(th, pstride, PP, Kr)
+                    warm_clocks(0.2)
+                    run(2)
+                    e0.record()
+                    run(n_avg)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms = e0.elapsed_time(e1) / n_avg
+                    out[f"m{Kr}_n{n_avg}"] = {"ms_per_minibatch_of_all_replicas": round(ms, 3),
+                                              "frames/s": round(Kr * nb / ms * 1e3, 1),
+                                              "mfma_frac": round(Kr * nb / ms * 1e3 * pflop / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4)}
+                del th, xb, yb, ac, wp
+            return out
         extras["averaging_sweep_8_replicas"] = sweep()
+        extras["paper_shape_440_6x2048_8806_mb1024"] = paper_shape()
+        log(f"paper shape: {extras['paper_shape_440_6x2048_8806_mb1024']}")
         log(f"sweep: {extras['averaging_sweep_8_replicas']}")
 
         sgd_ms, ng_ms = train_ms(512, False), train_ms(512, True)

@@ -795,39 +795,47 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
 }
 
 int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
-    for (int c0 = 0; c0 < count; c0 += kMaxGroups) {
-        const int ng = count - c0 < kMaxGroups ? count - c0 : kMaxGroups;
+    // Two passes over the problems: those the direct-to-LDS kernel accepts, then the rest (ragged or unaligned
+    // ones, e.g. a layer whose width is not a multiple of 4) with the register-staged kernel.
+    for (int pass = 0; pass < 2; ++pass) {
+        const bool dma = pass == 0;
         GemmGroupParams gp;
         gp.ngroups = 0;
-        int tiles = 0;
-        bool dma = true;
-        for (int i = 0; i < ng; ++i) {
-            const GemmDesc& di = d[c0 + i];
+        int tiles = 0, batch = 0;
+        bool a_kc = false, b_kc = false;
+        auto flush = [&]() -> int {
+            if (gp.ngroups == 0) return 0;
+            gp.tile_start[gp.ngroups] = tiles;
+            const dim3 grid((unsigned)tiles, 1, (unsigned)batch), block(256);
+            if (dma) {
+                if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, true>), grid, block, 0, stream, gp);
+                else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, false>), grid, block, 0, stream, gp);
+                else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, false>), grid, block, 0, stream, gp);
+                else hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, true>), grid, block, 0, stream, gp);
+            } else if (a_kc && b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, true>), grid, block, 0, stream, gp);
+            else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, false>), grid, block, 0, stream, gp);
+            else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, false>), grid, block, 0, stream, gp);
+            else hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, true>), grid, block, 0, stream, gp);
+            gp.ngroups = 0;
+            tiles = 0;
+            const hipError_t e = hipGetLastError();
+            return e == hipSuccess ? 0 : note_hip_error(e);
+        };
+        for (int i = 0; i < count; ++i) {
+            const GemmDesc& di = d[i];
             if (di.M <= 0 || di.N <= 0 || di.batch <= 0) continue;
-            if (di.a_kc != d[c0].a_kc || di.b_kc != d[c0].b_kc || di.batch != d[c0].batch) return note_hip_error(hipErrorInvalidValue);
+            if (di.a_kc != d[0].a_kc || di.b_kc != d[0].b_kc || di.batch != d[0].batch) return note_hip_error(hipErrorInvalidValue);
             if (di.epi.rowsum_dst != nullptr && di.a_kc) return note_hip_error(hipErrorInvalidValue);
             const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, 1, 1);      // 64x64 tiles, unsplit
-            gp.g[gp.ngroups] = fill_params(di, pl, nullptr);
-            dma = dma && dma_eligible(di, gp.g[gp.ngroups]);
+            const GemmKParams q = fill_params(di, pl, nullptr);
+            if (dma_eligible(di, q) != dma) continue;
+            a_kc = di.a_kc; b_kc = di.b_kc; batch = di.batch;
+            gp.g[gp.ngroups] = q;
             gp.tile_start[gp.ngroups] = tiles;
-            tiles += gp.g[gp.ngroups].tiles_m * gp.g[gp.ngroups].tiles_n;
-            ++gp.ngroups;
+            tiles += q.tiles_m * q.tiles_n;
+            if (++gp.ngroups == kMaxGroups && flush() != 0) return -1;
         }
-        if (gp.ngroups == 0) continue;
-        gp.tile_start[gp.ngroups] = tiles;
-        const dim3 grid((unsigned)tiles, 1, (unsigned)d[c0].batch), block(256);
-        const bool a_kc = d[c0].a_kc, b_kc = d[c0].b_kc;
-        if (dma) {
-            if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, true>), grid, block, 0, stream, gp);
-            else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, false>), grid, block, 0, stream, gp);
-            else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, false>), grid, block, 0, stream, gp);
-            else hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, true>), grid, block, 0, stream, gp);
-        } else if (a_kc && b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, true>), grid, block, 0, stream, gp);
-        else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, false>), grid, block, 0, stream, gp);
-        else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, false>), grid, block, 0, stream, gp);
-        else hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, true>), grid, block, 0, stream, gp);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return note_hip_error(e);
+        if (flush() != 0) return -1;
     }
     return 0;
 }
