@@ -219,6 +219,7 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
             GemmDesc& q = g[l - 1];
             q.M = y.d[l]; q.N = y.d[l - 1]; q.K = n; q.batch = k;
             q.A = delta_of(l); q.lda = w.ld_delta[l]; q.a_bstride = dstride_of(l); q.a_kc = false;
+            q.a_pad4 = true;       // rows of delta_l are ld_delta = round_up(d_l, 4) floats long
             q.B = (l == 1) ? x : acts + y.a_off[l - 1]; q.ldb = y.d[l - 1]; q.b_bstride = (l == 1) ? x_stride : act_stride;
             q.b_kc = false;
             q.C = theta + y.w_off[l]; q.ldc = y.d[l - 1]; q.c_bstride = theta_stride;

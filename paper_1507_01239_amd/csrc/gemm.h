@@ -50,6 +50,10 @@ struct GemmDesc {
     const float* B = nullptr; int64_t ldb = 0; int64_t b_bstride = 0; bool b_kc = true;
     float* C = nullptr;       int64_t ldc = 0; int64_t c_bstride = 0;
     int M = 0, N = 0, K = 0, batch = 1;
+    // For an operand whose m (or n) index is the contiguous one: its rows may be READ up to the next multiple of 4
+    // columns (the caller's buffer has that padding inside its row stride; what it holds is never used in a
+    // stored result).  Lets the direct-to-LDS kernel take widths that are not multiples of 4.
+    bool a_pad4 = false, b_pad4 = false;
     Epilogue epi;
     int force_cfg = -1;     // -1: choose; otherwise tile configuration index
     int force_splits = 0;   // 0: choose; otherwise number of contraction splits

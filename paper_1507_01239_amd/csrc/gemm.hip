@@ -35,6 +35,7 @@ struct GemmKParams {
     const float* B; int64_t ldb, b_bstride;
     float* C; int64_t ldc, c_bstride;
     int M, N, K, batch, splits, kper;   // kper: contraction elements per split (multiple of the k tile)
+    int Mr, Nr;                         // readable extents of m/n-contiguous operands (M, N or those rounded up to 4)
     int tiles_m, tiles_n;
     int vecA, vecB;                     // operands may be read with 16-byte loads
     float* ws;                          // partial sums [batch][split][M][N] when splits > 1
@@ -480,7 +481,7 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         const int k = wave * 4 + (lane >> 4), col = min(r0 + (lane & 15) * 4, R - 4);
         return (uint32_t)(((int64_t)k * ld + col) * 4);
     };
-    const uint32_t voa = lane_offset(AKC, m0, p.M, p.lda), vob = lane_offset(BKC, n0, p.N, p.ldb);
+    const uint32_t voa = lane_offset(AKC, m0, AKC ? p.M : p.Mr, p.lda), vob = lane_offset(BKC, n0, BKC ? p.N : p.Nr, p.ldb);
     const float* sa = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
         p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda))));
     const float* sb = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
@@ -636,11 +637,18 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
     if ((p.N & 3) == 0) {
         const int64_t nq = MN >> 2;
         for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256) {
-            float4 s = *reinterpret_cast<const float4*>(W + q * 4);
-#pragma unroll 4
-            for (int sp = 1; sp < p.splits; ++sp) {
-                const float4 t = *reinterpret_cast<const float4*>(W + sp * MN + q * 4);
-                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            // request all (at most 16) partial sums before adding any: one memory latency, not one per few splits
+            float4 t[16];
+#pragma unroll
+            for (int sp = 0; sp < 16; ++sp)
+                if (sp < p.splits) t[sp] = *reinterpret_cast<const float4*>(W + sp * MN + q * 4);
+            float4 s = t[0];
+#pragma unroll
+            for (int sp = 1; sp < 16; ++sp)
+                if (sp < p.splits) { s.x += t[sp].x; s.y += t[sp].y; s.z += t[sp].z; s.w += t[sp].w; }
+            for (int sp = 16; sp < p.splits; ++sp) {
+                const float4 u = *reinterpret_cast<const float4*>(W + sp * MN + q * 4);
+                s.x += u.x; s.y += u.y; s.z += u.z; s.w += u.w;
             }
             const int64_t e = q * 4;
             const int m = (int)(e / p.N), n = (int)(e - (int64_t)m * p.N);
@@ -676,12 +684,11 @@ constexpr int kNumCfgs = 9;
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
-    // Measured on MI355X (minibatch-256 layer shapes): 64x64 tiles win whenever a launch has fewer than about a
-    // thousand of them -- many small workgroups per compute unit run out of phase and hide each other's
-    // load, barrier and epilogue latencies -- and 128x128 tiles with 8 wavefronts win for the largest problems.
-    const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
+    // Measured on MI355X (layer shapes at minibatch 256 to 1024, 1 and 8 replicas): the 64x64 direct-to-LDS
+    // kernel wins everywhere; many small workgroups per compute unit run out of phase and hide each other's
+    // load, barrier and epilogue latencies.
     int cfg = force_cfg;
-    if (cfg < 0 || cfg >= kNumCfgs) cfg = (t64 >= 3072 && M >= 512 && N >= 512) ? 2 : 1;
+    if (cfg < 0 || cfg >= kNumCfgs) cfg = 1;
     pl.cfg = cfg;
     pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
     const int bk = kCfgs[cfg].bk;
@@ -689,7 +696,7 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
     int splits = force_splits;
     if (splits <= 0) {
         splits = 1;
-        if (tiles < kNumCU) {
+        if (tiles <= kNumCU + kNumCU / 2) {                        // (500 tiles measured faster unsplit than split in two)
             splits = (int)((2 * kNumCU + tiles - 1) / tiles);      // aim at two workgroups per compute unit
             const int max_by_k = (K + 8 * bk - 1) / (8 * bk);       // keep >= 8 k-tiles per split
             if (splits > max_by_k) splits = max_by_k;
@@ -726,8 +733,8 @@ static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 
 static bool dma_eligible(const GemmDesc& d, const GemmKParams& p) {
     if (!p.vecA || !p.vecB) return false;
     if (d.K < kDmaBK || d.K % kDmaBK != 0 || p.kper % kDmaBK != 0) return false;
-    if (!d.a_kc && (d.M < 4 || d.M % 4 != 0)) return false;
-    if (!d.b_kc && (d.N < 4 || d.N % 4 != 0)) return false;
+    if (!d.a_kc && (p.Mr < 4 || p.Mr % 4 != 0 || p.Mr > d.lda)) return false;
+    if (!d.b_kc && (p.Nr < 4 || p.Nr % 4 != 0 || p.Nr > d.ldb)) return false;
     const int64_t lim = (int64_t)1 << 29;      // per-lane offsets are 32-bit byte offsets
     if ((d.a_kc ? (int64_t)d.M * d.lda : kDmaBK * d.lda + d.M) >= lim) return false;
     if ((d.b_kc ? (int64_t)d.N * d.ldb : kDmaBK * d.ldb + d.N) >= lim) return false;
@@ -748,6 +755,8 @@ static GemmKParams fill_params(const GemmDesc& d, const GemmPlan& pl, float* ws)
     p.B = d.B; p.ldb = d.ldb; p.b_bstride = d.b_bstride;
     p.C = d.C; p.ldc = d.ldc; p.c_bstride = d.c_bstride;
     p.M = d.M; p.N = d.N; p.K = d.K; p.batch = d.batch;
+    p.Mr = d.a_pad4 ? (d.M + 3) / 4 * 4 : d.M;
+    p.Nr = d.b_pad4 ? (d.N + 3) / 4 * 4 : d.N;
     p.splits = pl.splits;
     const int bk = kCfgs[pl.cfg].bk;
     int kper = ((d.K + pl.splits - 1) / pl.splits + bk - 1) / bk * bk;
@@ -766,8 +775,17 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     if (d.M <= 0 || d.N <= 0 || d.batch <= 0) return 0;
     const bool rowsum = d.epi.rowsum_dst != nullptr;
     if (rowsum && d.a_kc) return note_hip_error(hipErrorInvalidValue);
-    const GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
-    const GemmKParams p = fill_params(d, pl, ws);
+    GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
+    GemmKParams p = fill_params(d, pl, ws);
+    if (d.force_cfg < 0 && pl.splits == 1 && !dma_eligible(d, p)) {
+        // a large problem the direct-to-LDS kernel cannot take (ragged contraction, unaligned rows): among the
+        // register-staged kernels the 128x128 tile with 8 wavefronts is the fastest from about 3000 64x64 tiles on
+        const int64_t t64 = (int64_t)p.tiles_m * p.tiles_n * d.batch;
+        if (t64 >= 3072 && d.M >= 512 && d.N >= 512) {
+            pl = gemm_plan(d.M, d.N, d.K, d.batch, 2, 1);
+            p = fill_params(d, pl, ws);
+        }
+    }
     if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return note_hip_error(hipErrorInvalidValue);
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
     if (pl.cfg == 1 && dma_eligible(d, p)) launch_dma(p, d.a_kc, d.b_kc, grid, stream);

@@ -712,7 +712,9 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
         GemmDesc g;
         g.M = a.d_out; g.N = a.d_in + 1; g.K = a.n; g.batch = a.k;
         g.A = a.delta; g.lda = a.ldd; g.a_bstride = a.d_bstride; g.a_kc = false;
+        g.a_pad4 = true;       // rows of delta are round_up(d_out, 4) floats long
         g.B = Xaug; g.ldb = ld_in; g.b_bstride = aug_b; g.b_kc = false;
+        g.b_pad4 = true;       // rows of Xaug are ld_in = round_up(d_in + 1, 4) floats long
         g.C = a.W; g.ldc = a.d_in; g.c_bstride = a.theta_stride;
         g.epi.kind = EPI_AXPBY; g.epi.alpha = -a.lr; g.epi.beta = 1.f;
         g.epi.alpha_dev0 = gamma_in; g.epi.alpha_dev1 = gamma_out;
