@@ -656,9 +656,15 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
         }
     } else {
         for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < MN; e += (int64_t)gridDim.x * 256) {
-            float s = W[e];
-#pragma unroll 8
-            for (int sp = 1; sp < p.splits; ++sp) s += W[sp * MN + e];
+            float t[16];
+#pragma unroll
+            for (int sp = 0; sp < 16; ++sp)
+                if (sp < p.splits) t[sp] = W[sp * MN + e];
+            float s = t[0];
+#pragma unroll
+            for (int sp = 1; sp < 16; ++sp)
+                if (sp < p.splits) s += t[sp];
+            for (int sp = 16; sp < p.splits; ++sp) s += W[sp * MN + e];
             const int m = (int)(e / p.N), n = (int)(e - (int64_t)m * p.N);
             MAVG_EPI_DISPATCH(p.epi.kind, (epi_apply<KIND>(p.epi, c, p.ldc, p.N, m, n, s)))
         }
@@ -802,7 +808,8 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return note_hip_error(e);
     if (pl.splits > 1) {
-        const int64_t work = ((int64_t)d.M * d.N + 3) / 4;
+        // one float4 per thread when rows are multiples of 4 long, else one element per thread
+        const int64_t work = (d.N & 3) == 0 ? (int64_t)d.M * d.N / 4 : (int64_t)d.M * d.N;
         int64_t gx = (work + 255) / 256;
         if (gx > 4096) gx = 4096;
         if (gx < 1) gx = 1;
