@@ -455,33 +455,46 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t x) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-template <bool AKC, bool BKC>
+template <int TM, int TN, bool AKC, bool BKC>
 __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int tile, const int bz) {
-    constexpr int BK = kDmaBK, NST = kDmaStages, TILE = 64 * BK;
-    __shared__ __attribute__((aligned(1024))) float As[NST][TILE];
-    __shared__ __attribute__((aligned(1024))) float Bs[NST][TILE];
+    // workgroup tile BM x BN = (64 TM) x (64 TN): 2x2 wavefronts, each TM x TN accumulators of 32x32
+    constexpr int BK = kDmaBK, NST = kDmaStages, BM = 64 * TM, BN = 64 * TN;
+    constexpr int TILE_A = BM * BK, TILE_B = BN * BK;          // floats per stage
+    constexpr int LOADS = TM + TN;                             // direct loads per wavefront per k-tile
+    static_assert(LOADS <= 4, "the vmcnt limits below are written for at most 4 loads per k-tile");
+    __shared__ __attribute__((aligned(1024))) float As[NST][TILE_A];
+    __shared__ __attribute__((aligned(1024))) float Bs[NST][TILE_B];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane >> 5, lcol = lane & 31;
-    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32;
+    const int wm = (wave >> 1) * (32 * TM), wn = (wave & 1) * (32 * TN);
     const int b = bz / p.splits, split = bz - b * p.splits;
     int tm_i, tn_i;
     tile_coords(p, tile, tm_i, tn_i);
-    const int m0 = tm_i * 64, n0 = tn_i * 64;
+    const int m0 = tm_i * BM, n0 = tn_i * BN;
     const int kbeg = split * p.kper;
     const int kend = min(p.K, kbeg + p.kper);
     const int nkt = __builtin_amdgcn_readfirstlane((kend - kbeg) / BK);
 
-    // per-lane byte offset of this lane's 16 bytes inside the operand, and the scalar base / per-tile advance
-    auto lane_offset = [&](bool kc, int r0, int R, int64_t ld) -> uint32_t {
+    // Direct load number i (0 .. T-1) of this wavefront for an operand of BR = 64 T rows covers the 256 floats
+    // [256 (4 i + wave), +256) of the stage.  k-contiguous operand ([row][16]): 16 rows, lane -> row lane/4, chunk
+    // position lane%4 (holding chunk position ^ swizzle(row)).  m/n-contiguous operand ([k][BR]): 256/BR k-rows,
+    // lane -> k-row lane / (BR/4), columns 4 (lane % (BR/4)).  Returns the lane's byte offset inside the operand.
+    auto lane_offset = [&](bool kc, int i, int BR, int r0, int R, int64_t ld) -> uint32_t {
+        const int blk = 4 * i + wave;
         if (kc) {
-            const int r = wave * 16 + (lane >> 2), q = (lane & 3) ^ ((r >> 1) & 3);
+            const int r = blk * 16 + (lane >> 2), q = (lane & 3) ^ ((r >> 1) & 3);
             const int row = min(r0 + r, R - 1);
             return (uint32_t)(((int64_t)row * ld + q * 4) * 4);
         }
-        const int k = wave * 4 + (lane >> 4), col = min(r0 + (lane & 15) * 4, R - 4);
+        const int per = BR / 4;                     // lanes per k-row
+        const int k = blk * (256 / BR) + lane / per, col = min(r0 + (lane % per) * 4, R - 4);
         return (uint32_t)(((int64_t)k * ld + col) * 4);
     };
-    const uint32_t voa = lane_offset(AKC, m0, AKC ? p.M : p.Mr, p.lda), vob = lane_offset(BKC, n0, BKC ? p.N : p.Nr, p.ldb);
+    uint32_t voa[TM], vob[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) voa[i] = lane_offset(AKC, i, BM, m0, AKC ? p.M : p.Mr, p.lda);
+#pragma unroll
+    for (int i = 0; i < TN; ++i) vob[i] = lane_offset(BKC, i, BN, n0, BKC ? p.N : p.Nr, p.ldb);
     const float* sa = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
         p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda))));
     const float* sb = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
@@ -491,74 +504,104 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
     const uint32_t la = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&As[0][wave * 256]);
     const uint32_t lb = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&Bs[0][wave * 256]);
     auto issue = [&](int t, int stage) {
-        dma16(voa, sa + t * stepa, la + stage * (TILE * 4));
-        dma16(vob, sb + t * stepb, lb + stage * (TILE * 4));
+#pragma unroll
+        for (int i = 0; i < TM; ++i) dma16(voa[i], sa + t * stepa, la + stage * (TILE_A * 4) + i * 4096);
+#pragma unroll
+        for (int i = 0; i < TN; ++i) dma16(vob[i], sb + t * stepb, lb + stage * (TILE_B * 4) + i * 4096);
+    };
+    // younger k-tiles that may stay in flight while the next one is awaited: two tiles of LOADS loads each
+    auto wait_next = [&]() {
+        if constexpr (LOADS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if constexpr (LOADS == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     };
 
-    // operand reads: float offsets inside a stage
-    const int ia = wm + lcol, ib = wn + lcol;
-    int offa[2], offb[2];
+    // operand reads: float offsets inside a stage, per 32-row block of the wavefront and pair of chunks
+    int offa[TM][2], offb[TN][2];
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
-        offa[pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ ((ia >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * 64 + ia;
-        offb[pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ ((ib >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * 64 + ib;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int ia = wm + i * 32 + lcol;
+            offa[i][pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ ((ia >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int ib = wn + j * 32 + lcol;
+            offb[j][pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ ((ib >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
+        }
     }
-    float fa[2][2][4], fb[2][2][4];
+    float fa[2][TM][2][4], fb[2][TN][2][4];
     auto read_frags = [&](auto setc, auto stagec) {
         constexpr int set = decltype(setc)::value, stage = decltype(stagec)::value;
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
-            if (AKC) {
-                const float4 v = *reinterpret_cast<const float4*>(&As[stage][offa[pr]]);
-                fa[set][pr][0] = v.x; fa[set][pr][1] = v.y; fa[set][pr][2] = v.z; fa[set][pr][3] = v.w;
-            } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) fa[set][pr][c] = As[stage][offa[pr] + c * 64];
+            for (int i = 0; i < TM; ++i) {
+                if (AKC) {
+                    const float4 v = *reinterpret_cast<const float4*>(&As[stage][offa[i][pr]]);
+                    fa[set][i][pr][0] = v.x; fa[set][i][pr][1] = v.y; fa[set][i][pr][2] = v.z; fa[set][i][pr][3] = v.w;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) fa[set][i][pr][c] = As[stage][offa[i][pr] + c * BM];
+                }
             }
-            if (BKC) {
-                const float4 v = *reinterpret_cast<const float4*>(&Bs[stage][offb[pr]]);
-                fb[set][pr][0] = v.x; fb[set][pr][1] = v.y; fb[set][pr][2] = v.z; fb[set][pr][3] = v.w;
-            } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) fb[set][pr][c] = Bs[stage][offb[pr] + c * 64];
+            for (int j = 0; j < TN; ++j) {
+                if (BKC) {
+                    const float4 v = *reinterpret_cast<const float4*>(&Bs[stage][offb[j][pr]]);
+                    fb[set][j][pr][0] = v.x; fb[set][j][pr][1] = v.y; fb[set][j][pr][2] = v.z; fb[set][j][pr][3] = v.w;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) fb[set][j][pr][c] = Bs[stage][offb[j][pr] + c * BN];
+                }
             }
         }
     };
 
-    floatx16 acc[1][1];
-    acc[0][0] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const bool do_rowsum = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0 && tid < 64;
+    floatx16 acc[TM][TN];
+    static_for<TM * TN>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        acc[t / TN][t % TN] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    });
+    const bool do_rowsum = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0 && tid < BM;
     float rowsum = 0.f;
 
     if (nkt > 0) {
 #pragma unroll
         for (int t = 0; t < NST - 1; ++t)
             if (t < nkt) issue(t, t);
-        if (nkt >= NST - 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        if (nkt >= NST - 1) wait_next();
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        auto multiply = [&](auto setc, auto prc) {
+            constexpr int set = decltype(setc)::value, pr = decltype(prc)::value;
+            static_for<4 * TM * TN>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                constexpr int c = q / (TM * TN), i = (q / TN) % TM, j = q % TN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][i][pr][c], fb[set][j][pr][c], acc[i][j], 0, 0, 0);
+            });
+        };
         auto step = [&](auto uc, const int t) {
             constexpr int u = decltype(uc)::value;          // stage of tile t
             constexpr int set = u & 1;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][0][c], fb[set][0][c], acc[0][0], 0, 0, 0);
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{});
             if (do_rowsum) {      // the stage is overwritten after the coming barrier: read it before
 #pragma unroll
-                for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * 64 + tid];
+                for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * BM + tid];
             }
             __builtin_amdgcn_sched_barrier(0);
             if (t + NST - 1 < nkt) {
                 issue(t + NST - 1, (u + NST - 1) % NST);
-                asm volatile("s_waitcnt vmcnt(4)" ::: "memory");      // tiles t+2, t+3 may stay in flight
+                wait_next();                                  // tiles t+2, t+3 may stay in flight
             } else {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
             __syncthreads();
             if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][1][c], fb[set][1][c], acc[0][0], 0, 0, 0);
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{});
             __builtin_amdgcn_sched_barrier(0);
         };
         for (int t = 0; t < nkt; t += NST) {
@@ -580,16 +623,16 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         EpiCtx c;
         c.bias = nullptr; c.aux = nullptr; c.C2 = nullptr; c.rowvec = nullptr; c.alpha = 1.f; c.lastcol_dst = nullptr;
         c.C = p.ws + ((int64_t)bz * p.M) * p.N;
-        write_tile<EPI_STORE, 1, 1>(acc, raw, c, p.N, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol);
+        write_tile<EPI_STORE, TM, TN>(acc, raw, c, p.N, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol);
     } else {
         const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
-        MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol)))
+        MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, TM, TN>(acc, p.epi, c, p.ldc, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol)))
     }
 }
 
-template <bool AKC, bool BKC>
+template <int TM, int TN, bool AKC, bool BKC>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
-    gemm_dma_body<AKC, BKC>(p, blockIdx.x, blockIdx.z);
+    gemm_dma_body<TM, TN, AKC, BKC>(p, blockIdx.x, blockIdx.z);
 }
 
 // Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
@@ -621,11 +664,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_grouped_kernel(GemmGroupPar
     gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
-template <bool AKC, bool BKC>
+template <int TM, int TN, bool AKC, bool BKC>
 __global__ __launch_bounds__(256) void gemm_dma_grouped_kernel(GemmGroupParams gp) {
     GemmKParams p;
     const int first = select_group(gp, p);
-    gemm_dma_body<AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
+    gemm_dma_body<TM, TN, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
 // Sum the partial results of a split contraction in split order and apply the epilogue.
@@ -685,8 +728,11 @@ static const TileCfg kCfgs[] = {
     {128, 64, 32, 256},    // 6: as 3 with 32 contraction steps per stage
     {64, 64, 32, 256},     // 7: as 1 with 32 contraction steps per stage
     {64, 64, 16, 256},     // 8: as 1, but never the direct-to-LDS variant (1 uses it whenever the operands allow)
+    {128, 64, 16, 256},    // 9: direct-to-LDS, 2x2 wavefronts of 64x32 (register-staged 3 when the operands do not allow)
+    {64, 128, 16, 256},    // 10: direct-to-LDS, 2x2 wavefronts of 32x64 (else 4)
+    {128, 128, 16, 256},   // 11: direct-to-LDS, 2x2 wavefronts of 64x64 (else 0)
 };
-constexpr int kNumCfgs = 9;
+constexpr int kNumCfgs = 12;
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
@@ -694,7 +740,9 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
     // kernel wins everywhere; many small workgroups per compute unit run out of phase and hide each other's
     // load, barrier and epilogue latencies.
     int cfg = force_cfg;
-    if (cfg < 0 || cfg >= kNumCfgs) cfg = 1;
+    // Only GEMMs that are large in all three dimensions (none of the training shapes: there one of the three is
+    // the minibatch) gain from 128x128 tiles: 141 against 127 TFLOP/s at 4096^3.
+    if (cfg < 0 || cfg >= kNumCfgs) cfg = (M >= 2048 && N >= 2048 && K >= 2048) ? 11 : 1;
     pl.cfg = cfg;
     pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
     const int bk = kCfgs[cfg].bk;
@@ -747,12 +795,19 @@ static bool dma_eligible(const GemmDesc& d, const GemmKParams& p) {
     return true;
 }
 
-static void launch_dma(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
+template <int TM, int TN>
+static void launch_dma_t(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
     const dim3 block(256);
-    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_kernel<true, true>), grid, block, 0, s, p);
-    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<true, false>), grid, block, 0, s, p);
-    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<false, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((gemm_dma_kernel<false, true>), grid, block, 0, s, p);
+    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, true, true>), grid, block, 0, s, p);
+    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, true, false>), grid, block, 0, s, p);
+    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, false, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, false, true>), grid, block, 0, s, p);
+}
+static void launch_dma(int cfg, const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
+    if (cfg == 9) launch_dma_t<2, 1>(p, a_kc, b_kc, grid, s);
+    else if (cfg == 10) launch_dma_t<1, 2>(p, a_kc, b_kc, grid, s);
+    else if (cfg == 11) launch_dma_t<2, 2>(p, a_kc, b_kc, grid, s);
+    else launch_dma_t<1, 1>(p, a_kc, b_kc, grid, s);
 }
 
 static GemmKParams fill_params(const GemmDesc& d, const GemmPlan& pl, float* ws) {
@@ -794,13 +849,13 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     }
     if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return note_hip_error(hipErrorInvalidValue);
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
-    if (pl.cfg == 1 && dma_eligible(d, p)) launch_dma(p, d.a_kc, d.b_kc, grid, stream);
+    if ((pl.cfg == 1 || pl.cfg >= 9) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
     else switch (pl.cfg) {
-    case 0: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 0: case 11: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 1: case 8: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 2: launch_cfg<128, 128, 16, 2, 4, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 3: launch_cfg<128, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 4: launch_cfg<64, 128, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 3: case 9: launch_cfg<128, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 4: case 10: launch_cfg<64, 128, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 5: launch_cfg<256, 128, 16, 4, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 6: launch_cfg<128, 64, 32, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
     default: launch_cfg<64, 64, 32, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
@@ -833,10 +888,10 @@ int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
             gp.tile_start[gp.ngroups] = tiles;
             const dim3 grid((unsigned)tiles, 1, (unsigned)batch), block(256);
             if (dma) {
-                if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, true>), grid, block, 0, stream, gp);
-                else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<true, false>), grid, block, 0, stream, gp);
-                else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, false>), grid, block, 0, stream, gp);
-                else hipLaunchKernelGGL((gemm_dma_grouped_kernel<false, true>), grid, block, 0, stream, gp);
+                if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, true, true>), grid, block, 0, stream, gp);
+                else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, true, false>), grid, block, 0, stream, gp);
+                else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, false, false>), grid, block, 0, stream, gp);
+                else hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, false, true>), grid, block, 0, stream, gp);
             } else if (a_kc && b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, true>), grid, block, 0, stream, gp);
             else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, false>), grid, block, 0, stream, gp);
             else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, false>), grid, block, 0, stream, gp);

@@ -59,11 +59,12 @@ def test_epilogues_with_and_without_split(epi, splits):
 
 
 @pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
-@pytest.mark.parametrize("cfg", [1, 8])
+@pytest.mark.parametrize("cfg", [1, 8, 9, 10, 11])
 def test_direct_to_lds_variant_and_its_register_staged_twin(a_kc, b_kc, cfg):
-    # shapes the direct-to-LDS 64x64 kernel accepts (16-byte aligned rows, contraction a multiple of 16); cfg 1
-    # runs it, cfg 8 forces the register-staged kernel on the same problem.  Ragged tile edges in m and n
-    # (clamped loads), one to many k-tiles (ring start-up and tail), padded leading dimensions, splits.
+    # shapes the direct-to-LDS kernels accept (16-byte aligned rows, contraction a multiple of 16); cfg 1 runs the
+    # 64x64 one, cfg 8 forces the register-staged kernel on the same problem, 9 / 10 / 11 are the 128x64, 64x128
+    # and 128x128 direct-to-LDS tiles.  Ragged tile edges in m and n (clamped loads), one to many k-tiles (ring
+    # start-up and tail), padded leading dimensions, splits.
     assert _run(200, 328, 144, a_kc, b_kc, cfg=cfg, seed=21) < 2e-6
     assert _run(132, 68, 16, a_kc, b_kc, cfg=cfg, seed=22, pad=4) < 2e-6
     assert _run(64, 64, 32, a_kc, b_kc, cfg=cfg, seed=23) < 2e-6
@@ -75,6 +76,8 @@ def test_direct_to_lds_variant_and_its_register_staged_twin(a_kc, b_kc, cfg):
 
 @pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
 def test_direct_to_lds_epilogues(epi):
+    assert _run(200, 264, 64, 0, 0, epi=epi, cfg=11, splits=1, seed=34, alpha=-0.5, beta=1.0) < 3e-6
+    assert _run(136, 72, 96, 1, 0, epi=epi, cfg=9, splits=2, seed=35, alpha=0.5, beta=2.0) < 3e-6
     assert _run(96, 160, 208, 1, 1, epi=epi, cfg=1, splits=1, seed=31, alpha=-0.5, beta=1.0) < 3e-6
     assert _run(72, 132, 256, 0, 0, epi=epi, cfg=1, splits=2, seed=32, alpha=0.25, beta=0.5) < 3e-6
     assert _run(100, 64, 96, 1, 0, epi=epi, cfg=1, splits=1, seed=33, alpha=2.0, beta=-1.0) < 3e-6
@@ -99,6 +102,7 @@ def test_training_shapes_auto_plan():
     assert _run(256, 2048, 2048, 1, 0, epi=3, seed=12) < 3e-6
     assert _run(2048, 440, 256, 0, 0, epi=4, alpha=-0.008, beta=1.0, seed=13) < 3e-6
     assert _run(256, 8000, 2048, 1, 1, epi=1, seed=14) < 3e-6
+    assert _run(2048, 2112, 2048, 1, 0, epi=0, seed=15) < 3e-6      # large in all three dimensions: 128x128 tiles
 
 
 def test_runs_are_bitwise_reproducible():
