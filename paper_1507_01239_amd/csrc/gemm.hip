@@ -434,7 +434,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmKParams p) {
 // contraction range per split that is a multiple of 16, row counts of m/n-contiguous operands that are
 // multiples of 4.  Rows or columns past the edge of a ragged tile are clamped to the last valid ones (their
 // products are never stored).
-constexpr int kDmaBK = 16, kDmaStages = 4;
+constexpr int kDmaBK = 16;
 
 // One direct load: 16 bytes per lane from sbase + voff to LDS address lds_byte + 16 * lane.  The LDS base travels
 // in M0, which is saved and restored around the instruction.  Written as inline assembly (not the compiler's
@@ -455,10 +455,11 @@ __device__ __forceinline__ uint64_t uniform_u64(uint64_t x) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-template <int TM, int TN, bool AKC, bool BKC>
+template <int TM, int TN, int NST, bool AKC, bool BKC>
 __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int tile, const int bz) {
     // workgroup tile BM x BN = (64 TM) x (64 TN): 2x2 wavefronts, each TM x TN accumulators of 32x32
-    constexpr int BK = kDmaBK, NST = kDmaStages, BM = 64 * TM, BN = 64 * TN;
+    constexpr int BK = kDmaBK, BM = 64 * TM, BN = 64 * TN;
+    static_assert(NST == 3 || NST == 4, "ring of 3 or 4 stages");
     constexpr int TILE_A = BM * BK, TILE_B = BN * BK;          // floats per stage
     constexpr int LOADS = TM + TN;                             // direct loads per wavefront per k-tile
     static_assert(LOADS <= 4, "the vmcnt limits below are written for at most 4 loads per k-tile");
@@ -509,11 +510,14 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
 #pragma unroll
         for (int i = 0; i < TN; ++i) dma16(vob[i], sb + t * stepb, lb + stage * (TILE_B * 4) + i * 4096);
     };
-    // younger k-tiles that may stay in flight while the next one is awaited: two tiles of LOADS loads each
+    // younger k-tiles that may stay in flight while the next one is awaited: NST - 2 tiles of LOADS loads each
     auto wait_next = [&]() {
-        if constexpr (LOADS == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else if constexpr (LOADS == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        constexpr int OUT = LOADS * (NST - 2);
+        if constexpr (OUT == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else if constexpr (OUT == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else if constexpr (OUT == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if constexpr (OUT == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else { static_assert(OUT == 8, "unexpected number of loads in flight"); asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
     };
 
     // operand reads: float offsets inside a stage, per 32-row block of the wavefront and pair of chunks
@@ -584,8 +588,8 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
             });
         };
         auto step = [&](auto uc, const int t) {
-            constexpr int u = decltype(uc)::value;          // stage of tile t
-            constexpr int set = u & 1;
+            constexpr int u = decltype(uc)::value % NST;    // stage of tile t
+            constexpr int set = decltype(uc)::value & 1;    // register set of tile t
             multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{});
             if (do_rowsum) {      // the stage is overwritten after the coming barrier: read it before
 #pragma unroll
@@ -604,11 +608,11 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
             multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{});
             __builtin_amdgcn_sched_barrier(0);
         };
-        for (int t = 0; t < nkt; t += NST) {
-            step(std::integral_constant<int, 0>{}, t);
-            if (t + 1 < nkt) step(std::integral_constant<int, 1>{}, t + 1);
-            if (t + 2 < nkt) step(std::integral_constant<int, 2>{}, t + 2);
-            if (t + 3 < nkt) step(std::integral_constant<int, 3>{}, t + 3);
+        constexpr int PERIOD = (NST % 2 == 0) ? NST : 2 * NST;      // stages and register sets repeat together
+        for (int t = 0; t < nkt; t += PERIOD) {
+            static_for<PERIOD>([&](auto uc) {
+                if (t + decltype(uc)::value < nkt) step(uc, t + decltype(uc)::value);
+            });
         }
     }
 
@@ -630,9 +634,9 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
     }
 }
 
-template <int TM, int TN, bool AKC, bool BKC>
+template <int TM, int TN, int NST, bool AKC, bool BKC>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
-    gemm_dma_body<TM, TN, AKC, BKC>(p, blockIdx.x, blockIdx.z);
+    gemm_dma_body<TM, TN, NST, AKC, BKC>(p, blockIdx.x, blockIdx.z);
 }
 
 // Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
@@ -664,11 +668,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_grouped_kernel(GemmGroupPar
     gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
-template <int TM, int TN, bool AKC, bool BKC>
+template <int TM, int TN, int NST, bool AKC, bool BKC>
 __global__ __launch_bounds__(256) void gemm_dma_grouped_kernel(GemmGroupParams gp) {
     GemmKParams p;
     const int first = select_group(gp, p);
-    gemm_dma_body<TM, TN, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
+    gemm_dma_body<TM, TN, NST, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
 // Sum the partial results of a split contraction in split order and apply the epilogue.
@@ -731,8 +735,9 @@ static const TileCfg kCfgs[] = {
     {128, 64, 16, 256},    // 9: direct-to-LDS, 2x2 wavefronts of 64x32 (register-staged 3 when the operands do not allow)
     {64, 128, 16, 256},    // 10: direct-to-LDS, 2x2 wavefronts of 32x64 (else 4)
     {128, 128, 16, 256},   // 11: direct-to-LDS, 2x2 wavefronts of 64x64 (else 0)
+    {64, 64, 16, 256},     // 12: as 1 with a ring of three LDS stages instead of four (else as 8)
 };
-constexpr int kNumCfgs = 12;
+constexpr int kNumCfgs = 13;
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
@@ -742,7 +747,14 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
     int cfg = force_cfg;
     // Only GEMMs that are large in all three dimensions (none of the training shapes: there one of the three is
     // the minibatch) gain from 128x128 tiles: 141 against 127 TFLOP/s at 4096^3.
-    if (cfg < 0 || cfg >= kNumCfgs) cfg = (M >= 2048 && N >= 2048 && K >= 2048) ? 11 : 1;
+    // A short contraction over many tiles (the weight gradients: K is the minibatch) runs better with a ring of
+    // three stages: a quarter less LDS lets one more workgroup share the compute unit, and it is the overlap of
+    // one workgroup's read-modify-write epilogue with its neighbours' multiplies that is short there
+    // (8000x2048x256: 90 against 95 us); the long contractions want the deeper ring (256x8000x2048: 73 against 81).
+    if (cfg < 0 || cfg >= kNumCfgs) {
+        const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
+        cfg = (M >= 2048 && N >= 2048 && K >= 2048) ? 11 : (K <= 1024 && t64 >= 1024) ? 12 : 1;
+    }
     pl.cfg = cfg;
     pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
     const int bk = kCfgs[cfg].bk;
@@ -795,19 +807,20 @@ static bool dma_eligible(const GemmDesc& d, const GemmKParams& p) {
     return true;
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int NST>
 static void launch_dma_t(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
     const dim3 block(256);
-    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, true, true>), grid, block, 0, s, p);
-    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, true, false>), grid, block, 0, s, p);
-    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, false, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, false, true>), grid, block, 0, s, p);
+    if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, NST, true, true>), grid, block, 0, s, p);
+    else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, NST, true, false>), grid, block, 0, s, p);
+    else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, NST, false, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((gemm_dma_kernel<TM, TN, NST, false, true>), grid, block, 0, s, p);
 }
 static void launch_dma(int cfg, const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
-    if (cfg == 9) launch_dma_t<2, 1>(p, a_kc, b_kc, grid, s);
-    else if (cfg == 10) launch_dma_t<1, 2>(p, a_kc, b_kc, grid, s);
-    else if (cfg == 11) launch_dma_t<2, 2>(p, a_kc, b_kc, grid, s);
-    else launch_dma_t<1, 1>(p, a_kc, b_kc, grid, s);
+    if (cfg == 9) launch_dma_t<2, 1, 4>(p, a_kc, b_kc, grid, s);
+    else if (cfg == 10) launch_dma_t<1, 2, 4>(p, a_kc, b_kc, grid, s);
+    else if (cfg == 11) launch_dma_t<2, 2, 4>(p, a_kc, b_kc, grid, s);
+    else if (cfg == 12) launch_dma_t<1, 1, 3>(p, a_kc, b_kc, grid, s);
+    else launch_dma_t<1, 1, 4>(p, a_kc, b_kc, grid, s);
 }
 
 static GemmKParams fill_params(const GemmDesc& d, const GemmPlan& pl, float* ws) {
@@ -852,7 +865,7 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     if ((pl.cfg == 1 || pl.cfg >= 9) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
     else switch (pl.cfg) {
     case 0: case 11: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 1: case 8: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 1: case 8: case 12: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 2: launch_cfg<128, 128, 16, 2, 4, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 3: case 9: launch_cfg<128, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 4: case 10: launch_cfg<64, 128, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
@@ -874,6 +887,8 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     return note_hip_error(e);
 }
 
+constexpr int kGroupedStages = 3;
+
 int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
     // Two passes over the problems: those the direct-to-LDS kernel accepts, then the rest (ragged or unaligned
     // ones, e.g. a layer whose width is not a multiple of 4) with the register-staged kernel.
@@ -888,10 +903,10 @@ int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
             gp.tile_start[gp.ngroups] = tiles;
             const dim3 grid((unsigned)tiles, 1, (unsigned)batch), block(256);
             if (dma) {
-                if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, true, true>), grid, block, 0, stream, gp);
-                else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, true, false>), grid, block, 0, stream, gp);
-                else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, false, false>), grid, block, 0, stream, gp);
-                else hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, false, true>), grid, block, 0, stream, gp);
+                if (a_kc && b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, kGroupedStages, true, true>), grid, block, 0, stream, gp);
+                else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, kGroupedStages, true, false>), grid, block, 0, stream, gp);
+                else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, kGroupedStages, false, false>), grid, block, 0, stream, gp);
+                else hipLaunchKernelGGL((gemm_dma_grouped_kernel<1, 1, kGroupedStages, false, true>), grid, block, 0, stream, gp);
             } else if (a_kc && b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, true>), grid, block, 0, stream, gp);
             else if (a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, true, false>), grid, block, 0, stream, gp);
             else if (!a_kc && !b_kc) hipLaunchKernelGGL((gemm_grouped_kernel<64, 64, 16, 2, 2, 4, false, false>), grid, block, 0, stream, gp);

@@ -59,11 +59,11 @@ def test_epilogues_with_and_without_split(epi, splits):
 
 
 @pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
-@pytest.mark.parametrize("cfg", [1, 8, 9, 10, 11])
+@pytest.mark.parametrize("cfg", [1, 8, 9, 10, 11, 12])
 def test_direct_to_lds_variant_and_its_register_staged_twin(a_kc, b_kc, cfg):
     # shapes the direct-to-LDS kernels accept (16-byte aligned rows, contraction a multiple of 16); cfg 1 runs the
     # 64x64 one, cfg 8 forces the register-staged kernel on the same problem, 9 / 10 / 11 are the 128x64, 64x128
-    # and 128x128 direct-to-LDS tiles.  Ragged tile edges in m and n (clamped loads), one to many k-tiles (ring
+    # and 128x128 direct-to-LDS tiles, 12 the 64x64 one with a ring of three LDS stages.  Ragged tile edges in m and n (clamped loads), one to many k-tiles (ring
     # start-up and tail), padded leading dimensions, splits.
     assert _run(200, 328, 144, a_kc, b_kc, cfg=cfg, seed=21) < 2e-6
     assert _run(132, 68, 16, a_kc, b_kc, cfg=cfg, seed=22, pad=4) < 2e-6
