@@ -189,8 +189,10 @@ def test_config2_full_size_fifty_steps():
         assert rel_err(Wg, Wr) < PARAM_TOL and rel_err(bg - 0.0, br) < 5e-3
 
 
-def test_full_size_first_step_gradient():
-    dims, n, seed = gen.CONFIG_FULL_DIMS, 256, 22
+@pytest.mark.parametrize("n", [128, 256, 512, 1024])
+def test_full_size_first_step_gradient(n):
+    # the minibatch sizes of the averaging sweep: each takes different tile plans (contraction splits, ring depth)
+    dims, seed = gen.CONFIG_FULL_DIMS, 22
     theta0 = gen.init_theta(dims, seed, 0.05)
     X, y = _full_batch(seed, 0, 0, n)
     lr = 16.0       # a power of two large enough that (theta - theta')/lr resolves the gradient in float32
@@ -220,3 +222,32 @@ def test_config3_eight_full_size_replicas_two_averaging_periods():
     th = g.params()
     assert rel_err(th[0], ref[0]) < PARAM_TOL
     assert all(np.array_equal(th[0], th[r]) for r in range(1, K))
+
+
+def test_full_size_activations_two_replicas_minibatch_512():
+    # forward pass at full size through the grouped (2-replica) launch: every layer's activations per replica
+    dims, n, K, seed = gen.CONFIG_FULL_DIMS, 512, 2, 24
+    theta0 = gen.init_theta(dims, seed, 0.05)
+    Xs = np.stack([_full_batch(seed, k, 0, n)[0] for k in range(K)])
+    g = Gpu(dims, K, n, theta0)
+    g.forward(Xs)
+    for k in range(K):
+        ref = dnn.forward(theta0, dims, Xs[k])
+        for a_gpu, a_ref in zip(g.activations(k), ref):
+            assert rel_err(a_gpu, a_ref) < ACT_TOL
+
+
+def test_single_frame_minibatch_and_many_replicas():
+    # degenerate sizes: one frame per minibatch; 16 replicas of a small ragged network in one launch
+    dims, seed = [12, 9, 7, 5], 31        # (replica strides of the inputs must be multiples of 4 floats)
+    theta0 = gen.init_theta(dims, seed, 0.3)
+    for K, n in ((1, 1), (16, 1), (16, 3)):
+        X = np.stack([gen.features_iid(n, dims[0], seed, k, 0) for k in range(K)])
+        Y = np.stack([gen.labels_uniform(n, dims[-1], seed, k, 0) for k in range(K)])
+        g = Gpu(dims, K, n, theta0)
+        g.step(X, Y, 0.5)
+        th = g.params()
+        for k in range(K):
+            ref, loss, acts = dnn.sgd_step(theta0, dims, X[k], Y[k], 0.5)
+            assert rel_err(th[k], ref) < 1e-5
+            assert abs(float(host(g.loss)[k]) - loss) < 1e-4 * max(1.0, abs(loss))
