@@ -639,6 +639,154 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
     gemm_dma_body<TM, TN, NST, AKC, BKC>(p, blockIdx.x, blockIdx.z);
 }
 
+// ---- skinny problems: 32x64 tile, contraction split four ways INSIDE the workgroup ---------------------
+//
+// A 256-row layer has 128 tiles of 64x64: too few for 256 compute units unless the contraction is split, and a
+// split across workgroups costs a pass of partial sums through memory plus a reducer launch per layer.  Here
+// the split stays inside the workgroup: 8 wavefronts = 4 k-groups of 2, every k-group multiplies its own
+// quarter of the contraction range for the same 32x64 output tile (each wavefront one 32x32 block) out of its
+// own ring of LDS stages, with the schedule of gemm_dma_body; at the end the groups' accumulators are added in
+// group order through LDS and k-group 0 applies the epilogue.  256 workgroups for a 256x2048 output, two
+// wavefronts per SIMD, no partial sums in memory, no reducer.  The price: an A tile serves 2 wavefronts
+// instead of 4 (3 direct loads per wavefront and k-tile instead of 2).
+constexpr int kKGroups = 4;
+
+template <bool AKC, bool BKC>
+__device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int tile, const int bz) {
+    constexpr int BK = kDmaBK, NST = 4, BM = 32, BN = 64, KG = kKGroups;
+    constexpr int TILE_A = BM * BK, TILE_B = BN * BK;
+    __shared__ __attribute__((aligned(1024))) float As[KG][NST][TILE_A];
+    __shared__ __attribute__((aligned(1024))) float Bs[KG][NST][TILE_B];
+    __shared__ float red[KG - 1][2][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kg = wave >> 1, gw = wave & 1;
+    const int lrow = lane >> 5, lcol = lane & 31;
+    const int wn = gw * 32;
+    const int b = bz;                                  // the contraction is not split across workgroups here
+    int tm_i, tn_i;
+    tile_coords(p, tile, tm_i, tn_i);
+    const int m0 = tm_i * BM, n0 = tn_i * BN;
+    // k-tiles of this k-group: a contiguous share of the K / 16 tiles
+    const int nkt_all = p.K / BK, base = nkt_all / KG, rem = nkt_all % KG;
+    const int nkt = __builtin_amdgcn_readfirstlane(base + (kg < rem ? 1 : 0));
+    const int first = kg * base + min(kg, rem);
+    const int nloop = base + (rem > 0 ? 1 : 0);        // every wavefront takes part in this many barriers
+    const int kbeg = first * BK;
+
+    // direct loads of this wavefront: unit gw of the A stage (2 units of 256 floats), units gw and gw + 2 of B
+    auto lane_offset = [&](bool kc, int unit, int BR, int r0, int R, int64_t ld) -> uint32_t {
+        if (kc) {
+            const int r = unit * 16 + (lane >> 2), q = (lane & 3) ^ ((r >> 1) & 3);
+            const int row = min(r0 + r, R - 1);
+            return (uint32_t)(((int64_t)row * ld + q * 4) * 4);
+        }
+        const int per = BR / 4;
+        const int k = unit * (256 / BR) + lane / per, col = min(r0 + (lane % per) * 4, R - 4);
+        return (uint32_t)(((int64_t)k * ld + col) * 4);
+    };
+    const uint32_t voa = lane_offset(AKC, gw, BM, m0, AKC ? p.M : p.Mr, p.lda);
+    const uint32_t vob0 = lane_offset(BKC, gw, BN, n0, BKC ? p.N : p.Nr, p.ldb);
+    const uint32_t vob1 = lane_offset(BKC, gw + 2, BN, n0, BKC ? p.N : p.Nr, p.ldb);
+    const float* sa = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
+        p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda))));
+    const float* sb = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
+        p.B + (int64_t)b * p.b_bstride + (BKC ? (int64_t)kbeg : (int64_t)kbeg * p.ldb))));
+    const int64_t stepa = (int64_t)uniform_u64((uint64_t)(AKC ? BK : BK * p.lda));
+    const int64_t stepb = (int64_t)uniform_u64((uint64_t)(BKC ? BK : BK * p.ldb));
+    const uint32_t la = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&As[kg][0][gw * 256]);
+    const uint32_t lb = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&Bs[kg][0][gw * 256]);
+    auto issue = [&](int t, int stage) {
+        dma16(voa, sa + t * stepa, la + stage * (TILE_A * 4));
+        dma16(vob0, sb + t * stepb, lb + stage * (TILE_B * 4));
+        dma16(vob1, sb + t * stepb, lb + stage * (TILE_B * 4) + 2048);
+    };
+
+    int offa[2], offb[2];
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+        const int ia = lcol, ib = wn + lcol;
+        offa[pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ ((ia >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
+        offb[pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ ((ib >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
+    }
+    float fa[2][2][4], fb[2][2][4];
+    auto read_frags = [&](auto setc, auto stagec) {
+        constexpr int set = decltype(setc)::value, stage = decltype(stagec)::value;
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr) {
+            if (AKC) {
+                const float4 v = *reinterpret_cast<const float4*>(&As[kg][stage][offa[pr]]);
+                fa[set][pr][0] = v.x; fa[set][pr][1] = v.y; fa[set][pr][2] = v.z; fa[set][pr][3] = v.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) fa[set][pr][c] = As[kg][stage][offa[pr] + c * BM];
+            }
+            if (BKC) {
+                const float4 v = *reinterpret_cast<const float4*>(&Bs[kg][stage][offb[pr]]);
+                fb[set][pr][0] = v.x; fb[set][pr][1] = v.y; fb[set][pr][2] = v.z; fb[set][pr][3] = v.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) fb[set][pr][c] = Bs[kg][stage][offb[pr] + c * BN];
+            }
+        }
+    };
+
+    floatx16 acc[1][1];
+    acc[0][0] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < NST - 1; ++t)
+        if (t < nkt) issue(t, t);
+    if (nkt >= NST - 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");      // tiles 1 and 2: three loads each
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (nkt > 0) read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    auto step = [&](auto uc, const int t) {
+        constexpr int u = decltype(uc)::value;
+        constexpr int set = u & 1;
+        if (t < nkt) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][0][c], fb[set][0][c], acc[0][0], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + NST - 1 < nkt) {
+            issue(t + NST - 1, (u + NST - 1) % NST);
+            asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        __syncthreads();
+        if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
+        __builtin_amdgcn_sched_barrier(0);
+        if (t < nkt) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][1][c], fb[set][1][c], acc[0][0], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int t = 0; t < nloop; t += NST) {
+        static_for<NST>([&](auto uc) {
+            if (t + decltype(uc)::value < nloop) step(uc, t + decltype(uc)::value);
+        });
+    }
+
+    // add the k-groups' accumulators in group order; every LDS read of the rings is behind the last barrier
+    if (kg > 0) {
+        static_for<16>([&](auto vc) { red[kg - 1][gw][decltype(vc)::value][lane] = acc[0][0][decltype(vc)::value]; });
+    }
+    __syncthreads();
+    if (kg > 0) return;
+    static_for<16>([&](auto vc) {
+        constexpr int v = decltype(vc)::value;
+        acc[0][0][v] = ((acc[0][0][v] + red[0][gw][v][lane]) + red[1][gw][v][lane]) + red[2][gw][v][lane];
+    });
+    const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
+    MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0, n0 + wn, lrow, lcol)))
+}
+
+template <bool AKC, bool BKC>
+__global__ __launch_bounds__(512) void gemm_dma_kg_kernel(GemmKParams p) {
+    gemm_dma_kg_body<AKC, BKC>(p, blockIdx.x, blockIdx.z);
+}
+
 // Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
 // layers): workgroup x belongs to the group whose tile range contains it.  Contractions are not split here.
 constexpr int kMaxGroups = 8;
@@ -736,8 +884,9 @@ static const TileCfg kCfgs[] = {
     {64, 128, 16, 256},    // 10: direct-to-LDS, 2x2 wavefronts of 32x64 (else 4)
     {128, 128, 16, 256},   // 11: direct-to-LDS, 2x2 wavefronts of 64x64 (else 0)
     {64, 64, 16, 256},     // 12: as 1 with a ring of three LDS stages instead of four (else as 8)
+    {32, 64, 16, 512},     // 13: direct-to-LDS, 32x64 tile, contraction split four ways inside the workgroup (else as 8, 64x64)
 };
-constexpr int kNumCfgs = 13;
+constexpr int kNumCfgs = 14;
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
@@ -754,12 +903,17 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
     if (cfg < 0 || cfg >= kNumCfgs) {
         const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
         cfg = (M >= 2048 && N >= 2048 && K >= 2048) ? 11 : (K <= 1024 && t64 >= 1024) ? 12 : 1;
+        // A skinny problem whose 32x64 tiles come to about one per compute unit (the 256 x 2048 x 2048 hidden
+        // layers of the minibatch-256 step) does its contraction split inside the workgroup: 24.5 against
+        // 26.9 us including the reducer.  Not at half or twice that many tiles, nor for K = 8000 (measured).
+        const int64_t t3264 = (int64_t)((M + 31) / 32) * ((N + 63) / 64) * batch;
+        if (cfg == 1 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU + kNumCU / 8 && K >= 1024 && K <= 4096) cfg = 13;
     }
     pl.cfg = cfg;
     pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
     const int bk = kCfgs[cfg].bk;
     const int64_t tiles = (int64_t)((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn) * batch;
-    int splits = force_splits;
+    int splits = cfg == 13 ? 1 : force_splits;      // 13 splits the contraction inside the workgroup only
     if (splits <= 0) {
         splits = 1;
         if (tiles <= kNumCU + kNumCU / 2) {                        // (500 tiles measured faster unsplit than split in two)
@@ -780,7 +934,8 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
 }
 
 int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg, int force_splits) {
-    const GemmPlan pl = gemm_plan(M, N, K, batch, force_cfg, force_splits);
+    GemmPlan pl = gemm_plan(M, N, K, batch, force_cfg, force_splits);
+    if (pl.cfg == 13) pl = gemm_plan(M, N, K, batch, 8, force_splits);      // what runs if the operands rule 13 out
     return pl.splits > 1 ? (int64_t)pl.splits * batch * M * N : 0;
 }
 
@@ -851,6 +1006,10 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     if (rowsum && d.a_kc) return note_hip_error(hipErrorInvalidValue);
     GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
     GemmKParams p = fill_params(d, pl, ws);
+    if (pl.cfg == 13 && !(dma_eligible(d, p) && !rowsum && d.K / kDmaBK >= kKGroups)) {
+        pl = gemm_plan(d.M, d.N, d.K, d.batch, 8, d.force_splits);
+        p = fill_params(d, pl, ws);
+    }
     if (d.force_cfg < 0 && pl.splits == 1 && !dma_eligible(d, p)) {
         // a large problem the direct-to-LDS kernel cannot take (ragged contraction, unaligned rows): among the
         // register-staged kernels the 128x128 tile with 8 wavefronts is the fastest from about 3000 64x64 tiles on
@@ -862,7 +1021,13 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     }
     if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return note_hip_error(hipErrorInvalidValue);
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
-    if ((pl.cfg == 1 || pl.cfg >= 9) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
+    if (pl.cfg == 13) {
+        const dim3 block(512);
+        if (d.a_kc && d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<true, true>), grid, block, 0, stream, p);
+        else if (d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<true, false>), grid, block, 0, stream, p);
+        else if (!d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<false, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((gemm_dma_kg_kernel<false, true>), grid, block, 0, stream, p);
+    } else if ((pl.cfg == 1 || pl.cfg >= 9) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
     else switch (pl.cfg) {
     case 0: case 11: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
     case 1: case 8: case 12: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
