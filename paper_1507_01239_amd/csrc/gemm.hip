@@ -651,15 +651,19 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
 // instead of 4 (3 direct loads per wavefront and k-tile instead of 2).
 constexpr int kKGroups = 4;
 
-template <bool AKC, bool BKC>
+template <int GW, bool AKC, bool BKC>
 __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int tile, const int bz) {
-    constexpr int BK = kDmaBK, NST = 4, BM = 32, BN = 64, KG = kKGroups;
+    // GW wavefronts per k-group: 2 (32x64 tile, one barrier per k-tile) or 1 (32x32 tile: a k-group is a single
+    // wavefront with a ring of its own, so the loop needs no barrier at all, only the wavefront's own vmcnt waits)
+    constexpr int BK = kDmaBK, NST = 4, BM = 32, BN = 32 * GW, KG = kKGroups;
+    constexpr int A_LOADS = 2 / GW, LOADS = A_LOADS + 2;
+    static_assert(GW == 1 || GW == 2, "one or two wavefronts per k-group");
     constexpr int TILE_A = BM * BK, TILE_B = BN * BK;
     __shared__ __attribute__((aligned(1024))) float As[KG][NST][TILE_A];
     __shared__ __attribute__((aligned(1024))) float Bs[KG][NST][TILE_B];
-    __shared__ float red[KG - 1][2][16][64];
+    __shared__ float red[KG - 1][GW][16][64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int kg = wave >> 1, gw = wave & 1;
+    const int kg = wave / GW, gw = wave % GW;
     const int lrow = lane >> 5, lcol = lane & 31;
     const int wn = gw * 32;
     const int b = bz;                                  // the contraction is not split across workgroups here
@@ -684,9 +688,13 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         const int k = unit * (256 / BR) + lane / per, col = min(r0 + (lane % per) * 4, R - 4);
         return (uint32_t)(((int64_t)k * ld + col) * 4);
     };
-    const uint32_t voa = lane_offset(AKC, gw, BM, m0, AKC ? p.M : p.Mr, p.lda);
+    // units of 256 floats: the A stage has 2 (a wavefront takes unit gw, or both when it is alone in its k-group),
+    // the B stage 2 GW (a wavefront takes units gw and gw + GW)
+    uint32_t voa[A_LOADS];
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) voa[i] = lane_offset(AKC, gw + i * GW, BM, m0, AKC ? p.M : p.Mr, p.lda);
     const uint32_t vob0 = lane_offset(BKC, gw, BN, n0, BKC ? p.N : p.Nr, p.ldb);
-    const uint32_t vob1 = lane_offset(BKC, gw + 2, BN, n0, BKC ? p.N : p.Nr, p.ldb);
+    const uint32_t vob1 = lane_offset(BKC, gw + GW, BN, n0, BKC ? p.N : p.Nr, p.ldb);
     const float* sa = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
         p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda))));
     const float* sb = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
@@ -696,9 +704,10 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     const uint32_t la = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&As[kg][0][gw * 256]);
     const uint32_t lb = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&Bs[kg][0][gw * 256]);
     auto issue = [&](int t, int stage) {
-        dma16(voa, sa + t * stepa, la + stage * (TILE_A * 4));
+#pragma unroll
+        for (int i = 0; i < A_LOADS; ++i) dma16(voa[i], sa + t * stepa, la + stage * (TILE_A * 4) + i * GW * 1024);
         dma16(vob0, sb + t * stepb, lb + stage * (TILE_B * 4));
-        dma16(vob1, sb + t * stepb, lb + stage * (TILE_B * 4) + 2048);
+        dma16(vob1, sb + t * stepb, lb + stage * (TILE_B * 4) + GW * 1024);
     };
 
     int offa[2], offb[2];
@@ -735,9 +744,16 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
 #pragma unroll
     for (int t = 0; t < NST - 1; ++t)
         if (t < nkt) issue(t, t);
-    if (nkt >= NST - 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");      // tiles 1 and 2: three loads each
+    auto wait_next = [&]() {       // two younger k-tiles of LOADS loads each may stay in flight
+        if constexpr (LOADS == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    };
+    auto group_barrier = [&]() {   // publish the landed tile to the other wavefront of the k-group, if there is one
+        if constexpr (GW > 1) __syncthreads();
+    };
+    if (nkt >= NST - 1) wait_next();
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    group_barrier();
     if (nkt > 0) read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     auto step = [&](auto uc, const int t) {
         constexpr int u = decltype(uc)::value;
@@ -749,11 +765,11 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         __builtin_amdgcn_sched_barrier(0);
         if (t + NST - 1 < nkt) {
             issue(t + NST - 1, (u + NST - 1) % NST);
-            asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            wait_next();
         } else {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
-        __syncthreads();
+        group_barrier();
         if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
         __builtin_amdgcn_sched_barrier(0);
         if (t < nkt) {
@@ -782,9 +798,9 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0, n0 + wn, lrow, lcol)))
 }
 
-template <bool AKC, bool BKC>
-__global__ __launch_bounds__(512) void gemm_dma_kg_kernel(GemmKParams p) {
-    gemm_dma_kg_body<AKC, BKC>(p, blockIdx.x, blockIdx.z);
+template <int GW, bool AKC, bool BKC>
+__global__ __launch_bounds__(64 * kKGroups * GW) void gemm_dma_kg_kernel(GemmKParams p) {
+    gemm_dma_kg_body<GW, AKC, BKC>(p, blockIdx.x, blockIdx.z);
 }
 
 // Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
@@ -885,8 +901,9 @@ static const TileCfg kCfgs[] = {
     {128, 128, 16, 256},   // 11: direct-to-LDS, 2x2 wavefronts of 64x64 (else 0)
     {64, 64, 16, 256},     // 12: as 1 with a ring of three LDS stages instead of four (else as 8)
     {32, 64, 16, 512},     // 13: direct-to-LDS, 32x64 tile, contraction split four ways inside the workgroup (else as 8, 64x64)
+    {32, 32, 16, 256},     // 14: as 13 with one wavefront per k-group (32x32 tile, no barrier in the loop)
 };
-constexpr int kNumCfgs = 14;
+constexpr int kNumCfgs = 15;
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
@@ -908,12 +925,16 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
         // 26.9 us including the reducer.  Not at half or twice that many tiles, nor for K = 8000 (measured).
         const int64_t t3264 = (int64_t)((M + 31) / 32) * ((N + 63) / 64) * batch;
         if (cfg == 1 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU + kNumCU / 8 && K >= 1024 && K <= 4096) cfg = 13;
+        // Half as many rows again (128 x 2048 x 2048): 32x32 tiles, one wavefront per k-group, no barrier in the
+        // loop: 18.0 against 19.8 us.
+        const int64_t t3232 = (int64_t)((M + 31) / 32) * ((N + 31) / 32) * batch;
+        if (cfg == 1 && t3232 >= 3 * kNumCU / 4 && t3232 <= kNumCU + kNumCU / 8 && K >= 1024 && K <= 4096) cfg = 14;
     }
     pl.cfg = cfg;
     pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
     const int bk = kCfgs[cfg].bk;
     const int64_t tiles = (int64_t)((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn) * batch;
-    int splits = cfg == 13 ? 1 : force_splits;      // 13 splits the contraction inside the workgroup only
+    int splits = (cfg == 13 || cfg == 14) ? 1 : force_splits;      // 13, 14 split the contraction inside the workgroup only
     if (splits <= 0) {
         splits = 1;
         if (tiles <= kNumCU + kNumCU / 2) {                        // (500 tiles measured faster unsplit than split in two)
@@ -935,7 +956,7 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
 
 int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl = gemm_plan(M, N, K, batch, force_cfg, force_splits);
-    if (pl.cfg == 13) pl = gemm_plan(M, N, K, batch, 8, force_splits);      // what runs if the operands rule 13 out
+    if (pl.cfg == 13 || pl.cfg == 14) pl = gemm_plan(M, N, K, batch, 8, force_splits);      // what runs if the operands rule them out
     return pl.splits > 1 ? (int64_t)pl.splits * batch * M * N : 0;
 }
 
@@ -1006,7 +1027,7 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     if (rowsum && d.a_kc) return note_hip_error(hipErrorInvalidValue);
     GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
     GemmKParams p = fill_params(d, pl, ws);
-    if (pl.cfg == 13 && !(dma_eligible(d, p) && !rowsum && d.K / kDmaBK >= kKGroups)) {
+    if ((pl.cfg == 13 || pl.cfg == 14) && !(dma_eligible(d, p) && !rowsum && d.K / kDmaBK >= kKGroups)) {
         pl = gemm_plan(d.M, d.N, d.K, d.batch, 8, d.force_splits);
         p = fill_params(d, pl, ws);
     }
@@ -1023,10 +1044,16 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
     if (pl.cfg == 13) {
         const dim3 block(512);
-        if (d.a_kc && d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<true, true>), grid, block, 0, stream, p);
-        else if (d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<true, false>), grid, block, 0, stream, p);
-        else if (!d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<false, false>), grid, block, 0, stream, p);
-        else hipLaunchKernelGGL((gemm_dma_kg_kernel<false, true>), grid, block, 0, stream, p);
+        if (d.a_kc && d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<2, true, true>), grid, block, 0, stream, p);
+        else if (d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<2, true, false>), grid, block, 0, stream, p);
+        else if (!d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<2, false, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((gemm_dma_kg_kernel<2, false, true>), grid, block, 0, stream, p);
+    } else if (pl.cfg == 14) {
+        const dim3 block(256);
+        if (d.a_kc && d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<1, true, true>), grid, block, 0, stream, p);
+        else if (d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<1, true, false>), grid, block, 0, stream, p);
+        else if (!d.a_kc && !d.b_kc) hipLaunchKernelGGL((gemm_dma_kg_kernel<1, false, false>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((gemm_dma_kg_kernel<1, false, true>), grid, block, 0, stream, p);
     } else if ((pl.cfg == 1 || pl.cfg >= 9) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
     else switch (pl.cfg) {
     case 0: case 11: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
