@@ -39,15 +39,29 @@ def softmax_rows(z: np.ndarray) -> np.ndarray:
     return e / e.sum(axis=1, keepdims=True)
 
 
-def forward(theta, dims, X):
-    """Activations [A_1, ..., A_L]; A_l = sigmoid(A_{l-1} W_l^T + b_l), A_L = softmax posteriors."""
+def hidden_activation(z, hidden):
+    """Sec. 5.1 names both: tanh hidden units in one sentence, sigmoids in the next.  Sigmoid is this build's
+    reading for every benchmarked configuration; tanh is kept as the variant."""
+    if hidden == "tanh":
+        return np.tanh(z)
+    assert hidden == "sigmoid"
+    return sigmoid(z)
+
+
+def hidden_derivative(a, hidden):
+    """d activation / d pre-activation, written in terms of the activation a."""
+    return (1.0 - a * a) if hidden == "tanh" else a * (1.0 - a)
+
+
+def forward(theta, dims, X, hidden="sigmoid"):
+    """Activations [A_1, ..., A_L]; A_l = act(A_{l-1} W_l^T + b_l), A_L = softmax posteriors."""
     theta = np.asarray(theta, dtype=np.float64)
     A = np.asarray(X, dtype=np.float64)
     acts = []
     layers = unpack(theta, dims)
     for l, (W, b) in enumerate(layers, start=1):
         Z = A @ W.T + b[None, :]
-        A = softmax_rows(Z) if l == len(layers) else sigmoid(Z)
+        A = softmax_rows(Z) if l == len(layers) else hidden_activation(Z, hidden)
         acts.append(A)
     return acts
 
@@ -64,7 +78,7 @@ def output_delta(p: np.ndarray, y: np.ndarray, mean_grad: bool) -> np.ndarray:
     return d / p.shape[0] if mean_grad else d
 
 
-def gradient(theta, dims, X, y, acts=None, mean_grad=True, precondition=None):
+def gradient(theta, dims, X, y, acts=None, mean_grad=True, precondition=None, hidden="sigmoid"):
     """Flat gradient of the (mean or summed) cross-entropy w.r.t. theta, and the summed loss.
 
     precondition, if given, is a callable (layer l, A_in_aug [N x (d_{l-1}+1)], delta_l [N x d_l])
@@ -75,7 +89,7 @@ def gradient(theta, dims, X, y, acts=None, mean_grad=True, precondition=None):
     X = np.asarray(X, dtype=np.float64)
     y = np.asarray(y)
     if acts is None:
-        acts = forward(theta, dims, X)
+        acts = forward(theta, dims, X, hidden)
     layers = unpack(theta, dims)
     L = len(layers)
     grad = np.zeros_like(theta)
@@ -95,20 +109,20 @@ def gradient(theta, dims, X, y, acts=None, mean_grad=True, precondition=None):
             GW[:, :] = G[:, :-1]
             Gb[:] = G[:, -1]
         if l > 1:
-            delta = (delta @ W) * A_in * (1.0 - A_in)
+            delta = (delta @ W) * hidden_derivative(A_in, hidden)
     return grad, cross_entropy_sum(acts[-1], y)
 
 
-def sgd_step(theta, dims, X, y, lr, mean_grad=True, precondition=None):
+def sgd_step(theta, dims, X, y, lr, mean_grad=True, precondition=None, hidden="sigmoid"):
     """One update theta - lr * gradient (eq. 3).  Returns (new theta, summed loss, activations)."""
     theta = np.asarray(theta, dtype=np.float64)
-    acts = forward(theta, dims, X)
-    g, loss = gradient(theta, dims, X, y, acts, mean_grad, precondition)
+    acts = forward(theta, dims, X, hidden)
+    g, loss = gradient(theta, dims, X, y, acts, mean_grad, precondition, hidden)
     return theta - lr * g, loss, acts
 
 
-def loss_only(theta, dims, X, y, mean=True) -> float:
+def loss_only(theta, dims, X, y, mean=True, hidden="sigmoid") -> float:
     """Scalar objective whose gradient `gradient` returns (used by finite-difference pins)."""
-    p = forward(theta, dims, X)[-1]
+    p = forward(theta, dims, X, hidden)[-1]
     s = cross_entropy_sum(p, np.asarray(y))
     return s / X.shape[0] if mean else s

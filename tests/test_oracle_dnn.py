@@ -49,6 +49,36 @@ def test_gradient_matches_central_differences(dims, mean):
     assert np.linalg.norm(fd - g) <= 1e-7 * np.linalg.norm(g)
 
 
+@pytest.mark.parametrize("dims", [(5, 4, 3, 3), (3, 5, 4, 2, 6)])
+def test_tanh_variant_gradient_matches_central_differences_and_a_rescaled_sigmoid_network(dims):
+    theta, X, y = _tiny(7, dims, n=4)
+    g, _ = dnn.gradient(theta, dims, X, y, mean_grad=True, hidden="tanh")
+    h = 1e-5
+    fd = np.zeros_like(theta)
+    for i in range(theta.size):
+        tp, tm = theta.copy(), theta.copy()
+        tp[i] += h
+        tm[i] -= h
+        fd[i] = (dnn.loss_only(tp, dims, X, y, True, hidden="tanh") - dnn.loss_only(tm, dims, X, y, True, hidden="tanh")) / (2 * h)
+    assert np.linalg.norm(fd - g) <= 1e-7 * np.linalg.norm(g)
+    # closed form: tanh(z) = 2 sigmoid(2z) - 1, so the tanh network equals a sigmoid network whose hidden
+    # layers have their weights and biases doubled and whose next layer sees 2 a - 1:
+    # W'_1 = 2 W_1, b'_1 = 2 b_1; for l > 1: W'_l = s_l * 2 W_l, b'_l = s_l (b_l - W_l 1), s_l = 2 (hidden) or 1 (softmax)
+    layers = dnn.unpack(theta, dims)
+    t2 = theta.copy()
+    l2 = dnn.unpack(t2, dims)
+    L = len(layers)
+    for l, ((W, b), (W2, b2)) in enumerate(zip(layers, l2), start=1):
+        s_out = 2.0 if l < L else 1.0
+        if l == 1:
+            W2[:, :] = s_out * W
+            b2[:] = s_out * b
+        else:
+            W2[:, :] = s_out * 2.0 * W
+            b2[:] = s_out * (b - W.sum(axis=1))
+    np.testing.assert_allclose(dnn.forward(theta, dims, X, hidden="tanh")[-1], dnn.forward(t2, dims, X)[-1], rtol=1e-11, atol=1e-14)
+
+
 def test_gradient_and_loss_match_autograd_library():
     dims = (7, 6, 5, 9)
     theta, X, y = _tiny(2, dims, n=11)
