@@ -60,9 +60,16 @@ extern "C" {
 #define MAVG_VIS_GAUSSIAN  1
 #define MAVG_SAMPLE_V1     1u   /* flags bit0: sample the Bernoulli reconstruction               */
 
-/* Network shape: n_layers affine layers, dims = host array of n_layers+1 widths d_0..d_L (all >= 1). */
+/* Hidden-unit nonlinearity (Sec. 5.1 names tanh in one sentence and sigmoids in the next; every benchmarked
+   configuration uses the sigmoid). */
+#define MAVG_ACT_SIGMOID 0
+#define MAVG_ACT_TANH    1
+
+/* Network shape: n_layers affine layers, dims = host array of n_layers+1 widths d_0..d_L (all >= 1);
+   hidden_act = MAVG_ACT_* for layers 1..L-1 (the output layer is always a softmax). */
 typedef struct {
     int32_t n_layers;
+    int32_t hidden_act;
     const int32_t* dims;
 } mavg_shape;
 

@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmavg.so")
 
 OK, E_NULL, E_DIM, E_ALIGN, E_FLAG, E_LAUNCH, E_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
+ACT_SIGMOID, ACT_TANH = 0, 1
 MEAN_GRAD, USE_NGSGD, NG_FIRST = 1, 2, 4
 VIS_BERNOULLI, VIS_GAUSSIAN = 0, 1
 SAMPLE_V1 = 1
@@ -41,16 +42,17 @@ lib = C.CDLL(LIB_PATH)
 
 
 class _Shape(C.Structure):
-    _fields_ = [("n_layers", C.c_int32), ("dims", C.POINTER(C.c_int32))]
+    _fields_ = [("n_layers", C.c_int32), ("hidden_act", C.c_int32), ("dims", C.POINTER(C.c_int32))]
 
 
 class Shape:
-    """Network widths d_0..d_L."""
+    """Network widths d_0..d_L and the hidden-unit nonlinearity (ACT_SIGMOID / ACT_TANH)."""
 
-    def __init__(self, dims):
+    def __init__(self, dims, hidden_act=0):
         self.dims = tuple(int(d) for d in dims)
+        self.hidden_act = int(hidden_act)
         self._arr = (C.c_int32 * len(self.dims))(*self.dims)
-        self._s = _Shape(len(self.dims) - 1, C.cast(self._arr, C.POINTER(C.c_int32)))
+        self._s = _Shape(len(self.dims) - 1, self.hidden_act, C.cast(self._arr, C.POINTER(C.c_int32)))
 
     @property
     def ref(self):

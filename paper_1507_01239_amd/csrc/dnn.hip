@@ -18,6 +18,7 @@ inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 int check_shape(const mavg_shape* sh) {
     if (!sh || !sh->dims) return MAVG_E_NULL;
     if (sh->n_layers < 1 || sh->n_layers > MAVG_MAX_LAYERS) return MAVG_E_DIM;
+    if (sh->hidden_act != MAVG_ACT_SIGMOID && sh->hidden_act != MAVG_ACT_TANH) return MAVG_E_FLAG;
     for (int l = 0; l <= sh->n_layers; ++l)
         if (sh->dims[l] < 1) return MAVG_E_DIM;
     return MAVG_OK;
@@ -154,6 +155,7 @@ extern "C" int32_t dnn_forward(const mavg_shape* shape, int32_t k, const float* 
         g.B = theta + y.w_off[l]; g.ldb = y.d[l - 1]; g.b_bstride = theta_stride; g.b_kc = true;
         g.C = acts + y.a_off[l]; g.ldc = y.d[l]; g.c_bstride = act_stride;
         g.epi.kind = (l < y.L) ? EPI_BIAS_SIGMOID : EPI_BIAS;
+        g.epi.act_tanh = shape->hidden_act == MAVG_ACT_TANH;
         g.epi.bias = theta + y.b_off[l]; g.epi.bias_bstride = theta_stride;
         if (gemm_launch(g, ws ? ws + w.off_gemm : nullptr, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
@@ -208,6 +210,7 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
         g.B = theta + y.w_off[l]; g.ldb = y.d[l - 1]; g.b_bstride = theta_stride; g.b_kc = false;
         g.C = delta_of(l - 1); g.ldc = w.ld_delta[l - 1]; g.c_bstride = dstride_of(l - 1);
         g.epi.kind = EPI_MUL_DSIGMOID;
+        g.epi.act_tanh = shape->hidden_act == MAVG_ACT_TANH;
         g.epi.aux = acts + y.a_off[l - 1]; g.epi.ldaux = y.d[l - 1]; g.epi.aux_bstride = act_stride;
         if (gemm_launch(g, gws, w.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }

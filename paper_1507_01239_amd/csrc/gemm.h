@@ -29,6 +29,8 @@ struct Epilogue {
     const float* aux = nullptr;  int64_t ldaux = 0; int64_t aux_bstride = 0;
     float* C2 = nullptr;         int64_t ldc2 = 0;  int64_t c2_bstride = 0;
     float alpha = 1.f, beta = 0.f;
+    // EPI_BIAS_SIGMOID / EPI_MUL_DSIGMOID with tanh in place of the sigmoid: C = tanh(v + bias[n]) / C = v * (1 - a^2)
+    int act_tanh = 0;
     // optional device-side factors of alpha (EPI_AXPBY): alpha_eff = alpha * alpha_dev0[b] * alpha_dev1[b]
     const float* alpha_dev0 = nullptr; const float* alpha_dev1 = nullptr;
     const float* rowvec = nullptr; int64_t rowvec_bstride = 0;     // EPI_ROWSCALE_ADD

@@ -57,6 +57,8 @@ def test_bad_shapes_are_rejected():
     assert _rc(B.mavg_workspace_bytes, B.Shape((4, 3)), 8, 0) == B.E_DIM
     assert _rc(B.mavg_workspace_bytes, B.Shape((4, 3)), 8, 1, 8) == B.E_FLAG
     assert _rc(B.mavg_param_count, B.Shape(tuple([3] * 70))) == B.E_DIM  # too many layers
+    assert _rc(B.mavg_param_count, B.Shape((4, 3), hidden_act=7)) == B.E_FLAG      # unknown nonlinearity
+    assert B.mavg_param_count(B.Shape((4, 3), hidden_act=B.ACT_TANH)) == 15
 
 
 def test_dnn_calls_validate_before_touching_the_device():

@@ -17,12 +17,12 @@ ACT_TOL, GRAD_TOL, PARAM_TOL = 1e-4, 1e-4, 1e-3
 class Gpu:
     """k replicas of one network on the device, driven through the C ABI."""
 
-    def __init__(self, dims, k, n, theta0, flags=None):
+    def __init__(self, dims, k, n, theta0, flags=None, hidden_act=0):
         import torch
         from paper_1507_01239_amd import binding as B
         self.B, self.torch = B, torch
         self.dims, self.k, self.n = dims, k, n
-        self.shape = B.Shape(dims)
+        self.shape = B.Shape(dims, hidden_act)
         self.P = B.mavg_param_count(self.shape)
         self.stride = (self.P + 63) // 64 * 64
         self.act_stride = (B.mavg_act_count(self.shape, n) + 63) // 64 * 64
@@ -251,3 +251,31 @@ def test_single_frame_minibatch_and_many_replicas():
             ref, loss, acts = dnn.sgd_step(theta0, dims, X[k], Y[k], 0.5)
             assert rel_err(th[k], ref) < 1e-5
             assert abs(float(host(g.loss)[k]) - loss) < 1e-4 * max(1.0, abs(loss))
+
+
+@pytest.mark.parametrize("dims,n", [([13, 11, 9, 7, 6], 10), ([440, 256, 192, 500], 96)])
+def test_tanh_hidden_units_activations_gradient_and_five_steps(dims, n):
+    # the variant nonlinearity (tanh hidden units): per-step activations and gradient, then a short trajectory
+    seed = 41
+    theta0 = gen.init_theta(dims, seed, 0.2)
+    X = gen.features_iid(n, dims[0], seed, 0, 0)
+    y = gen.labels_uniform(n, dims[-1], seed, 0, 0)
+    lr = 4.0
+    g = Gpu(dims, 1, n, theta0, hidden_act=1)
+    g.step(X[None], y[None], lr)
+    ref_acts = dnn.forward(theta0, dims, X, hidden="tanh")
+    for a_gpu, a_ref in zip(g.activations(0), ref_acts):
+        assert rel_err(a_gpu, a_ref) < ACT_TOL
+    grad_ref, loss_ref = dnn.gradient(theta0, dims, X, y, mean_grad=True, hidden="tanh")
+    grad_gpu = (theta0.astype(np.float64) - g.params()[0].astype(np.float64)) / lr
+    for (Wg, bg), (Wr, br) in zip(dnn.unpack(grad_gpu, dims), dnn.unpack(grad_ref, dims)):
+        assert rel_err(Wg, Wr) < GRAD_TOL and rel_err(bg, br) < GRAD_TOL
+    assert abs(float(host(g.loss)[0]) - loss_ref) < 1e-4 * abs(loss_ref)
+    g2 = Gpu(dims, 1, n, theta0, hidden_act=1)
+    ref = theta0.astype(np.float64)
+    for t in range(5):
+        Xt = gen.features_iid(n, dims[0], seed, 0, t)
+        yt = gen.labels_uniform(n, dims[-1], seed, 0, t)
+        g2.step(Xt[None], yt[None], 0.05)
+        ref, _, _ = dnn.sgd_step(ref, dims, Xt, yt, 0.05, hidden="tanh")
+    assert rel_err(g2.params()[0], ref) < PARAM_TOL
