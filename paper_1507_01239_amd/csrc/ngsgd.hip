@@ -155,10 +155,31 @@ __global__ __launch_bounds__(256) void ng_sumsq_partial_kernel(const float* __re
     const int b = blockIdx.y;
     const float* __restrict__ xb = x + (int64_t)b * x_b;
     double s = 0.0;
+    const bool vec = (ldx & 3) == 0 && (x_b & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
     for (int r = blockIdx.x; r < n; r += gridDim.x) {
         const float* __restrict__ row = xb + (int64_t)r * ldx;
         float a = 0.f;
-        for (int c = threadIdx.x; c < dim; c += 256) { const float q = row[c]; a += q * q; }
+        if (vec) {      // 16-byte loads, four in flight per thread; the tail of the row one element at a time
+            const int nq = dim >> 2;
+            int q = threadIdx.x;
+            for (; q + 768 < nq; q += 1024) {
+                const float4 v0 = *reinterpret_cast<const float4*>(row + 4 * q);
+                const float4 v1 = *reinterpret_cast<const float4*>(row + 4 * (q + 256));
+                const float4 v2 = *reinterpret_cast<const float4*>(row + 4 * (q + 512));
+                const float4 v3 = *reinterpret_cast<const float4*>(row + 4 * (q + 768));
+                a += (v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w);
+                a += (v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w);
+                a += (v2.x * v2.x + v2.y * v2.y) + (v2.z * v2.z + v2.w * v2.w);
+                a += (v3.x * v3.x + v3.y * v3.y) + (v3.z * v3.z + v3.w * v3.w);
+            }
+            for (; q < nq; q += 256) {
+                const float4 v0 = *reinterpret_cast<const float4*>(row + 4 * q);
+                a += (v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w);
+            }
+            for (int c = 4 * nq + threadIdx.x; c < dim; c += 256) { const float e = row[c]; a += e * e; }
+        } else {
+            for (int c = threadIdx.x; c < dim; c += 256) { const float e = row[c]; a += e * e; }
+        }
         s += (double)a;
     }
     s = block_sum_d(s, sh);
@@ -178,6 +199,41 @@ __global__ __launch_bounds__(256) void ng_sumsq_final_kernel(const double* __res
             const double nx = scal[b * 2 + 0];
             gamma[b] = (nx > 0.0 && s > 0.0) ? (float)sqrt(nx / s) : 1.f;
         }
+    }
+}
+
+// X <- X + sign * Cm R  for a thin Cm (n x rank) and R (rank x dim): a rank-`rank` update of an n x dim matrix,
+// bound by reading and writing X.  One thread per column keeps that column of R in registers and walks 16 rows;
+// the 16 x rank block of Cm sits in LDS.  (As an MFMA GEMM with a contraction of 30 it took 10 us per call.)
+constexpr int kRuRows = 16;
+template <int RANK_MAX>
+__global__ __launch_bounds__(256) void ng_rank_update_kernel(float* __restrict__ x, int64_t ldx, int64_t x_b,
+                                                             const float* __restrict__ cm, int64_t ldc, int64_t c_b,
+                                                             const float* __restrict__ r, int64_t ldr, int64_t r_b,
+                                                             int n, int dim, int rank, float sign) {
+    __shared__ float cs[kRuRows][RANK_MAX];
+    const int b = blockIdx.z, col = blockIdx.x * 256 + threadIdx.x, row0 = blockIdx.y * kRuRows;
+    const float* __restrict__ cb = cm + (int64_t)b * c_b;
+    for (int i = threadIdx.x; i < kRuRows * RANK_MAX; i += 256) {       // zero beyond `rank` and beyond the last row
+        const int rr = i / RANK_MAX, k = i - rr * RANK_MAX;
+        cs[rr][k] = (k < rank && row0 + rr < n) ? cb[(int64_t)(row0 + rr) * ldc + k] : 0.f;
+    }
+    __syncthreads();
+    if (col >= dim) return;
+    float rc[RANK_MAX];
+    const float* __restrict__ rb = r + (int64_t)b * r_b + col;
+#pragma unroll
+    for (int k = 0; k < RANK_MAX; ++k) rc[k] = k < rank ? rb[(int64_t)k * ldr] : 0.f;
+    float* __restrict__ xb = x + (int64_t)b * x_b + col;
+    float old[kRuRows];
+#pragma unroll
+    for (int rr = 0; rr < kRuRows; ++rr) old[rr] = row0 + rr < n ? xb[(int64_t)(row0 + rr) * ldx] : 0.f;
+#pragma unroll
+    for (int rr = 0; rr < kRuRows; ++rr) {
+        float acc = 0.f;
+#pragma unroll
+        for (int k = 0; k < RANK_MAX; ++k) acc += cs[rr][k] * rc[k];       // both factors are 0 beyond `rank`
+        if (row0 + rr < n) xb[(int64_t)(row0 + rr) * ldx] = old[rr] + sign * acc;
     }
 }
 
@@ -557,14 +613,15 @@ int ng_run(const NgCall& c, hipStream_t s) {
         return gemm_launch(g, gws, w.gemm_floats, s);
     };
     auto gemm_XR = [&](const float* coefmat, float sign) -> int {     // X <- X + sign * coefmat R
-        GemmDesc g;
-        g.M = c.n; g.N = c.dim; g.K = c.rank; g.batch = c.batch;
-        g.A = coefmat; g.lda = w.ldr; g.a_bstride = w.H_b; g.a_kc = true;
-        g.B = Rm; g.ldb = w.ld; g.b_bstride = st_bf; g.b_kc = false;
-        g.C = c.x; g.ldc = c.ldx; g.c_bstride = c.x_b;
-        g.epi.kind = EPI_AXPBY; g.epi.alpha = sign; g.epi.beta = 1.f;
-        g.force_splits = 1;
-        return gemm_launch(g, gws, w.gemm_floats, s);
+        const dim3 grid((unsigned)((c.dim + 255) / 256), (unsigned)((c.n + kRuRows - 1) / kRuRows), (unsigned)c.batch);
+        if (c.rank <= 32)
+            hipLaunchKernelGGL(ng_rank_update_kernel<32>, grid, dim3(256), 0, s, c.x, c.ldx, c.x_b, coefmat, (int64_t)w.ldr, w.H_b,
+                               Rm, (int64_t)w.ld, st_bf, c.n, c.dim, c.rank, sign);
+        else
+            hipLaunchKernelGGL(ng_rank_update_kernel<kMaxRank>, grid, dim3(256), 0, s, c.x, c.ldx, c.x_b, coefmat, (int64_t)w.ldr, w.H_b,
+                               Rm, (int64_t)w.ld, st_bf, c.n, c.dim, c.rank, sign);
+        NG_LAUNCHED();
+        return 0;
     };
     auto finish_fold = [&](int bump, bool y64) -> int {     // from Y: Z, eigen-decomposition, new state
         NgFoldTable tb;
