@@ -1028,7 +1028,7 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
     GemmKParams p = fill_params(d, pl, ws);
     if ((pl.cfg == 13 || pl.cfg == 14) && !(dma_eligible(d, p) && !rowsum && d.K / kDmaBK >= kKGroups)) {
-        pl = gemm_plan(d.M, d.N, d.K, d.batch, 8, d.force_splits);
+        pl = gemm_plan(d.M, d.N, d.K, d.batch, 8, rowsum ? 1 : d.force_splits);
         p = fill_params(d, pl, ws);
     }
     if (d.force_cfg < 0 && pl.splits == 1 && !dma_eligible(d, p)) {
