@@ -887,20 +887,22 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
 struct TileCfg { int bm, bn, bk, threads; };
 // index = the `cfg` argument of the exported test entry point
 static const TileCfg kCfgs[] = {
-    {128, 128, 16, 256},   // 0: 2x2 wavefronts of 64x64
-    {64, 64, 16, 256},     // 1: 2x2 wavefronts of 32x32
+    // register-staged kernels (guarded loads: any shape, any alignment)
+    {128, 128, 16, 512},   // 0: = 2 (retired variant)
+    {64, 64, 16, 256},     // 1: 2x2 wavefronts of 32x32; runs as the direct-to-LDS 64x64 kernel whenever the operands allow
     {128, 128, 16, 512},   // 2: 2x4 wavefronts of 64x32
-    {128, 64, 16, 256},    // 3: 2x2 wavefronts of 64x32
-    {64, 128, 16, 256},    // 4: 2x2 wavefronts of 32x64
-    {256, 128, 16, 512},   // 5: 4x2 wavefronts of 64x64
-    {128, 64, 32, 256},    // 6: as 3 with 32 contraction steps per stage
-    {64, 64, 32, 256},     // 7: as 1 with 32 contraction steps per stage
-    {64, 64, 16, 256},     // 8: as 1, but never the direct-to-LDS variant (1 uses it whenever the operands allow)
-    {128, 64, 16, 256},    // 9: direct-to-LDS, 2x2 wavefronts of 64x32 (register-staged 3 when the operands do not allow)
-    {64, 128, 16, 256},    // 10: direct-to-LDS, 2x2 wavefronts of 32x64 (else 4)
-    {128, 128, 16, 256},   // 11: direct-to-LDS, 2x2 wavefronts of 64x64 (else 0)
-    {64, 64, 16, 256},     // 12: as 1 with a ring of three LDS stages instead of four (else as 8)
-    {32, 64, 16, 512},     // 13: direct-to-LDS, 32x64 tile, contraction split four ways inside the workgroup (else as 8, 64x64)
+    {64, 64, 16, 256},     // 3..7: = 8 (retired variants: 128x64, 64x128, 256x128 tiles, 32 contraction steps per stage)
+    {64, 64, 16, 256},
+    {64, 64, 16, 256},
+    {64, 64, 16, 256},
+    {64, 64, 16, 256},
+    {64, 64, 16, 256},     // 8: as 1, but never the direct-to-LDS variant
+    // direct-to-LDS only; replanned as 8 when the operands do not allow it
+    {128, 64, 16, 256},    // 9: 2x2 wavefronts of 64x32
+    {64, 128, 16, 256},    // 10: 2x2 wavefronts of 32x64
+    {128, 128, 16, 256},   // 11: 2x2 wavefronts of 64x64
+    {64, 64, 16, 256},     // 12: as 1 with a ring of three LDS stages instead of four
+    {32, 64, 16, 512},     // 13: 32x64 tile, contraction split four ways inside the workgroup
     {32, 32, 16, 256},     // 14: as 13 with one wavefront per k-group (32x32 tile, no barrier in the loop)
 };
 constexpr int kNumCfgs = 15;
@@ -955,9 +957,13 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
 }
 
 int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg, int force_splits) {
-    GemmPlan pl = gemm_plan(M, N, K, batch, force_cfg, force_splits);
-    if (pl.cfg == 13 || pl.cfg == 14) pl = gemm_plan(M, N, K, batch, 8, force_splits);      // what runs if the operands rule them out
-    return pl.splits > 1 ? (int64_t)pl.splits * batch * M * N : 0;
+    const GemmPlan pl = gemm_plan(M, N, K, batch, force_cfg, force_splits);
+    int splits = pl.splits;
+    if (pl.cfg >= 9 && pl.cfg != 12) {      // direct-to-LDS only: also cover what runs if the operands rule it out
+        const GemmPlan fb = gemm_plan(M, N, K, batch, 8, force_splits);
+        if (fb.splits > splits) splits = fb.splits;
+    }
+    return splits > 1 ? (int64_t)splits * batch * M * N : 0;
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int PF>
@@ -1027,7 +1033,8 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     if (rowsum && d.a_kc) return note_hip_error(hipErrorInvalidValue);
     GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
     GemmKParams p = fill_params(d, pl, ws);
-    if ((pl.cfg == 13 || pl.cfg == 14) && !(dma_eligible(d, p) && !rowsum && d.K / kDmaBK >= kKGroups)) {
+    const bool kg_cfg = pl.cfg == 13 || pl.cfg == 14;
+    if (pl.cfg >= 9 && pl.cfg != 12 && !(dma_eligible(d, p) && (!kg_cfg || (!rowsum && d.K / kDmaBK >= kKGroups)))) {
         pl = gemm_plan(d.M, d.N, d.K, d.batch, 8, rowsum ? 1 : d.force_splits);
         p = fill_params(d, pl, ws);
     }
@@ -1056,14 +1063,8 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
         else hipLaunchKernelGGL((gemm_dma_kg_kernel<1, false, true>), grid, block, 0, stream, p);
     } else if ((pl.cfg == 1 || pl.cfg >= 9) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
     else switch (pl.cfg) {
-    case 0: case 11: launch_cfg<128, 128, 16, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 1: case 8: case 12: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 2: launch_cfg<128, 128, 16, 2, 4, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 3: case 9: launch_cfg<128, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 4: case 10: launch_cfg<64, 128, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 5: launch_cfg<256, 128, 16, 4, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
-    case 6: launch_cfg<128, 64, 32, 2, 2, 2>(p, d.a_kc, d.b_kc, grid, stream); break;
-    default: launch_cfg<64, 64, 32, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    case 0: case 2: launch_cfg<128, 128, 16, 2, 4, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
+    default: launch_cfg<64, 64, 16, 2, 2, 4>(p, d.a_kc, d.b_kc, grid, stream); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return note_hip_error(e);
