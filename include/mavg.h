@@ -229,10 +229,16 @@ int32_t ngsgd_precondition(void* state, int32_t dim, int32_t rank,
  *   C(m,n) = c[m*ldc + n]
  *   epi: 0  C = v            1  C = v + bias[n]          2  C = sigmoid(v + bias[n])
  *        3  C = v * aux(m,n) * (1 - aux(m,n))            4  C = beta*C + alpha*v
- *   cfg: -1 = choose the tile shape, else its index;  splits: 0 = choose how many ways the contraction
- *   is split (partial sums are combined in split order by a second kernel), else that many.
- * All pointers device; operands that are not 16-byte aligned (or whose leading dimension is not a
- * multiple of 4) are read with scalar loads.
+ *   cfg: -1 = choose the kernel, else its index:
+ *        1  64x64 tiles, operands loaded global -> LDS directly when they allow it (16-byte aligned rows, k a
+ *           multiple of 16, widths of m/n-contiguous operands multiples of 4), else through registers
+ *        8  64x64 tiles, always through registers (guarded loads: any shape and alignment);  2  128x128 likewise
+ *        9 / 10 / 11  direct-to-LDS 128x64 / 64x128 / 128x128 tiles;  12  as 1 with a shallower LDS ring
+ *        13 / 14  direct-to-LDS 32x64 / 32x32 tiles whose contraction is split four ways inside the workgroup
+ *        (9..14 run as 8 when the operands do not allow direct loads; 0 and 3..7 are retired aliases of 2 and 8)
+ *   splits: 0 = choose how many ways the contraction is split across workgroups (partial sums are combined
+ *   in split order by a second kernel), else that many; ignored by 13 and 14.
+ * All pointers device.  Results are bitwise reproducible for a given (shape, cfg, splits).
  */
 int64_t mavg_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t cfg, int32_t splits);
 int32_t mavg_gemm(const float* a, int64_t lda, int32_t a_kc, const float* b, int64_t ldb, int32_t b_kc,
