@@ -430,10 +430,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmKParams p) {
 // tile t+1 into the other register set; last four MFMAs, which cover that LDS latency.  The stage that
 // receives tile t+3 held tile t-1, whose reads every wavefront finished before the barrier of tile t-1.
 //
-// The host picks this path only when the loads need no masking: 16-byte aligned operands and strides, a
-// contraction range per split that is a multiple of 16, row counts of m/n-contiguous operands that are
-// multiples of 4.  Rows or columns past the edge of a ragged tile are clamped to the last valid ones (their
-// products are never stored).
+// The host picks this path only when the loads need no masking: 16-byte aligned operands and strides, row
+// counts of m/n-contiguous operands that are multiples of 4 (or padded to one).  Rows or columns past the edge
+// of a ragged tile are clamped to the last valid ones (their products are never stored); contraction steps
+// past the last whole k-tile (fewer than 16) are multiplied after the loop from operands read element by
+// element.
 constexpr int kDmaBK = 16;
 
 // One direct load: 16 bytes per lane from sbase + voff to LDS address lds_byte + 16 * lane.  The LDS base travels
@@ -616,6 +617,45 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         }
     }
 
+    // Contraction steps past the last whole k-tile of this split (fewer than 16; only the last split has any):
+    // operands straight from global memory into registers, element by element, zero past the end.
+    const int ktail = kbeg + nkt * BK;
+    if (ktail < kend) {
+        const float* __restrict__ Ab = p.A + (int64_t)b * p.a_bstride;
+        const float* __restrict__ Bb = p.B + (int64_t)b * p.b_bstride;
+        static_for<2>([&](auto prc) {
+            constexpr int pr = decltype(prc)::value;
+            float ta[TM][4], tb[TN][4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int k = ktail + 8 * pr + 4 * lrow + c;
+                const bool ok = k < kend;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int m = min(m0 + wm + i * 32 + lcol, p.M - 1);
+                    ta[i][c] = ok ? (AKC ? Ab[(int64_t)m * p.lda + k] : Ab[(int64_t)k * p.lda + m]) : 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = min(n0 + wn + j * 32 + lcol, p.N - 1);
+                    tb[j][c] = ok ? (BKC ? Bb[(int64_t)n * p.ldb + k] : Bb[(int64_t)k * p.ldb + n]) : 0.f;
+                }
+            }
+            if (do_rowsum) {      // (rows of A summed over k: this thread's row is tid, not its MFMA lane's)
+#pragma unroll
+                for (int c = 0; c < 8; ++c) {
+                    const int k = ktail + 8 * pr + c;
+                    if (k < kend && m0 + tid < p.M) rowsum += Ab[(int64_t)k * p.lda + m0 + tid];
+                }
+            }
+            static_for<4 * TM * TN>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                constexpr int c = q / (TM * TN), i = (q / TN) % TM, j = q % TN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(ta[i][c], tb[j][c], acc[i][j], 0, 0, 0);
+            });
+        });
+    }
+
     if (do_rowsum && m0 + tid < p.M) {
         float* d = p.epi.rowsum_dst + (int64_t)b * p.epi.rowsum_bstride + m0 + tid;
         float r = p.epi.rowsum_alpha * rowsum;
@@ -784,6 +824,26 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         });
     }
 
+    // contraction steps past the last whole k-tile (fewer than 16): the last k-group, straight from global memory
+    if (kg == KG - 1 && nkt_all * BK < p.K) {
+        const float* __restrict__ Ab = p.A + (int64_t)b * p.a_bstride;
+        const float* __restrict__ Bb = p.B + (int64_t)b * p.b_bstride;
+        const int m = min(m0 + lcol, p.M - 1), n = min(n0 + wn + lcol, p.N - 1);
+        static_for<2>([&](auto prc) {
+            constexpr int pr = decltype(prc)::value;
+            float ta[4], tb[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int k = nkt_all * BK + 8 * pr + 4 * lrow + c;
+                const bool ok = k < p.K;
+                ta[c] = ok ? (AKC ? Ab[(int64_t)m * p.lda + k] : Ab[(int64_t)k * p.lda + m]) : 0.f;
+                tb[c] = ok ? (BKC ? Bb[(int64_t)n * p.ldb + k] : Bb[(int64_t)k * p.ldb + n]) : 0.f;
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ta[c], tb[c], acc[0][0], 0, 0, 0);
+        });
+    }
+
     // add the k-groups' accumulators in group order; every LDS read of the rings is behind the last barrier
     if (kg > 0) {
         static_for<16>([&](auto vc) { red[kg - 1][gw][decltype(vc)::value][lane] = acc[0][0][decltype(vc)::value]; });
@@ -924,9 +984,10 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
         cfg = (M >= 2048 && N >= 2048 && K >= 2048) ? 11 : (K <= 1024 && t64 >= 1024) ? 12 : 1;
         // A skinny problem whose 32x64 tiles come to about one per compute unit (the 256 x 2048 x 2048 hidden
         // layers of the minibatch-256 step) does its contraction split inside the workgroup: 24.5 against
-        // 26.9 us including the reducer.  Not at half or twice that many tiles, nor for K = 8000 (measured).
+        // 26.9 us including the reducer (13.1 against 15.9 us for the 440-wide first layer).  Not at half or
+        // twice that many tiles, nor for K = 8000 (measured).
         const int64_t t3264 = (int64_t)((M + 31) / 32) * ((N + 63) / 64) * batch;
-        if (cfg == 1 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU + kNumCU / 8 && K >= 1024 && K <= 4096) cfg = 13;
+        if (cfg == 1 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU + kNumCU / 8 && K >= 256 && K <= 4096) cfg = 13;
         // Half as many rows again (128 x 2048 x 2048): 32x32 tiles, one wavefront per k-group, no barrier in the
         // loop: 18.0 against 19.8 us.
         const int64_t t3232 = (int64_t)((M + 31) / 32) * ((N + 31) / 32) * batch;
@@ -980,7 +1041,7 @@ static bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 
 // May the direct-to-LDS kernel run this problem?  Its loads are unmasked 16-byte loads.
 static bool dma_eligible(const GemmDesc& d, const GemmKParams& p) {
     if (!p.vecA || !p.vecB) return false;
-    if (d.K < kDmaBK || d.K % kDmaBK != 0 || p.kper % kDmaBK != 0) return false;
+    if (d.K < kDmaBK || p.kper % kDmaBK != 0) return false;      // (a contraction tail of fewer than 16 steps is handled)
     if (!d.a_kc && (p.Mr < 4 || p.Mr % 4 != 0 || p.Mr > d.lda)) return false;
     if (!d.b_kc && (p.Nr < 4 || p.Nr % 4 != 0 || p.Nr > d.ldb)) return false;
     const int64_t lim = (int64_t)1 << 29;      // per-lane offsets are 32-bit byte offsets

@@ -74,6 +74,10 @@ def test_direct_to_lds_variant_and_its_register_staged_twin(a_kc, b_kc, cfg):
     assert _run(256, 192, 1040, a_kc, b_kc, cfg=cfg, seed=25) < 3e-6
     assert _run(128, 256, 640, a_kc, b_kc, cfg=cfg, splits=5, seed=26, epi=2) < 3e-6
     assert _run(4, 4, 80, a_kc, b_kc, cfg=cfg, seed=27) < 2e-6
+    # contraction lengths that are not multiples of 16 (a tail after the last whole k-tile), nor of 4
+    assert _run(136, 200, 440, a_kc, b_kc, cfg=cfg, seed=28) < 3e-6
+    assert _run(72, 100, 90, a_kc, b_kc, cfg=cfg, seed=29, pad=2) < 2e-6
+    assert _run(128, 192, 1000, a_kc, b_kc, cfg=cfg, splits=3, seed=30, epi=1) < 3e-6
 
 
 @pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
