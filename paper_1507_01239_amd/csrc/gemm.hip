@@ -419,8 +419,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmKParams p) {
 // MFMAs (address arithmetic, and the loads that need it) would otherwise wait for that chain.
 //
 // LDS layouts.  An operand whose contraction index is contiguous in memory keeps its rows: [row][16], the
-// 16-byte chunk q of row r stored at chunk position q ^ ((r >> 1) & 3) (the xor spreads the eight rows a
-// ds_read_b128 phase touches over all banks); a lane reads one chunk = four contraction steps at once.  An
+// 16-byte chunk q of row r stored at chunk position q ^ ((r >> 2) & 3) (a ds_read_b128 serves 16 lanes = 16
+// rows per cycle from 64 banks; rows r, r+4, r+8, r+12 start at the same bank, the xor moves their chunks to the
+// four different quarters of the 64-byte row: SQ_LDS_BANK_CONFLICT reads zero with it, half of the LDS cycles
+// with (r >> 1) & 3); a lane reads one chunk = four contraction steps at once.  An
 // operand whose non-contracted index is contiguous is stored [k][64] as it comes and read with ds_read_b32.
 // Both feed the same assignment of contraction steps to MFMAs: step c (0..3) of pair p (0..1) multiplies
 // k = 8p + c in lanes 0-31 and k = 8p + 4 + c in lanes 32-63.
@@ -436,6 +438,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_kernel(GemmKParams p) {
 // past the last whole k-tile (fewer than 16) are multiplied after the loop from operands read element by
 // element.
 constexpr int kDmaBK = 16;
+
+__device__ __forceinline__ constexpr int chunk_swizzle(int r) { return (r >> 2) & 3; }
 
 // One direct load: 16 bytes per lane from sbase + voff to LDS address lds_byte + 16 * lane.  The LDS base travels
 // in M0, which is saved and restored around the instruction.  Written as inline assembly (not the compiler's
@@ -484,7 +488,7 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
     auto lane_offset = [&](bool kc, int i, int BR, int r0, int R, int64_t ld) -> uint32_t {
         const int blk = 4 * i + wave;
         if (kc) {
-            const int r = blk * 16 + (lane >> 2), q = (lane & 3) ^ ((r >> 1) & 3);
+            const int r = blk * 16 + (lane >> 2), q = (lane & 3) ^ chunk_swizzle(r);
             const int row = min(r0 + r, R - 1);
             return (uint32_t)(((int64_t)row * ld + q * 4) * 4);
         }
@@ -528,12 +532,12 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int ia = wm + i * 32 + lcol;
-            offa[i][pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ ((ia >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
+            offa[i][pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ chunk_swizzle(ia)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int ib = wn + j * 32 + lcol;
-            offb[j][pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ ((ib >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
+            offb[j][pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ chunk_swizzle(ib)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
         }
     }
     float fa[2][TM][2][4], fb[2][TN][2][4];
@@ -720,7 +724,7 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     // direct loads of this wavefront: unit gw of the A stage (2 units of 256 floats), units gw and gw + 2 of B
     auto lane_offset = [&](bool kc, int unit, int BR, int r0, int R, int64_t ld) -> uint32_t {
         if (kc) {
-            const int r = unit * 16 + (lane >> 2), q = (lane & 3) ^ ((r >> 1) & 3);
+            const int r = unit * 16 + (lane >> 2), q = (lane & 3) ^ chunk_swizzle(r);
             const int row = min(r0 + r, R - 1);
             return (uint32_t)(((int64_t)row * ld + q * 4) * 4);
         }
@@ -754,8 +758,8 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
         const int ia = lcol, ib = wn + lcol;
-        offa[pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ ((ia >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
-        offb[pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ ((ib >> 1) & 3)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
+        offa[pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ chunk_swizzle(ia)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
+        offb[pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ chunk_swizzle(ib)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
     }
     float fa[2][2][4], fb[2][2][4];
     auto read_frags = [&](auto setc, auto stagec) {
