@@ -232,8 +232,11 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
         }
         if (gemm_launch_grouped(g, y.L, s) != 0) return MAVG_E_LAUNCH;
     } else {
+        // the first minibatch (three folds from the initial state first) layer by layer; afterwards every layer
+        // side in the same launches
+        static thread_local NgLayerArgs la[MAVG_MAX_LAYERS];
         for (int l = y.L; l >= 1; --l) {
-            NgLayerArgs a;
+            NgLayerArgs& a = la[l - 1];
             a.dims = y.d; a.L = y.L; a.l = l;
             a.k = k; a.n = n; a.d_in = y.d[l - 1]; a.d_out = y.d[l];
             a.A_in = (l == 1) ? x : acts + y.a_off[l - 1]; a.a_ld = y.d[l - 1]; a.a_bstride = (l == 1) ? x_stride : act_stride;
@@ -246,8 +249,9 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
             a.mode = (flags & MAVG_NG_FIRST) ? 2 : 1;
             a.ws = ws + w.off_ng; a.ws_floats = w.ng_floats;
             a.gemm_ws = gws; a.gemm_ws_floats = w.gemm_floats;
-            if (ng_layer_update(a, s) != 0) return MAVG_E_LAUNCH;
+            if ((flags & MAVG_NG_FIRST) && ng_layer_update(a, s) != 0) return MAVG_E_LAUNCH;
         }
+        if (!(flags & MAVG_NG_FIRST) && ng_dnn_update(la, y.L, s) != 0) return MAVG_E_LAUNCH;
         if (ng_dnn_finish(y.d, y.L, n, k, ng_rank, ng_eta, static_cast<char*>(ng_state), ng_state_stride, ws + w.off_ng, s) != 0)
             return MAVG_E_LAUNCH;
     }

@@ -70,7 +70,8 @@ int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg = -1, int f
 int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t stream);
 
 // Several independent GEMMs of the same operand layouts and batch count in ONE launch (64x64 tiles, unsplit
-// contraction, no scratch).  Returns hipError_t as int.
-int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream);
+// contraction, no scratch).  `thin`: products with few output columns and a long contraction, both operands
+// k-contiguous (32x32 tiles, the contraction split four ways inside each workgroup).  Returns hipError_t as int.
+int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream, bool thin = false);
 
 }  // namespace mavg

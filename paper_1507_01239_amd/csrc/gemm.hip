@@ -903,6 +903,14 @@ __global__ __launch_bounds__(256) void gemm_dma_grouped_kernel(GemmGroupParams g
     gemm_dma_body<TM, TN, NST, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
+// Several thin products (few output columns, long contraction) in one launch of the in-workgroup-split kernel.
+template <int GW, bool AKC, bool BKC>
+__global__ __launch_bounds__(64 * kKGroups * GW) void gemm_dma_kg_grouped_kernel(GemmGroupParams gp) {
+    GemmKParams p;
+    const int first = select_group(gp, p);
+    gemm_dma_kg_body<GW, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
+}
+
 // Sum the partial results of a split contraction in split order and apply the epilogue.
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
     const int b = blockIdx.y;
@@ -1147,7 +1155,45 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
 
 constexpr int kGroupedStages = 3;
 
-int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream) {
+// Thin products X R^T (both operands k-contiguous) on 32x32 tiles with the contraction split inside the workgroup;
+// a problem that kernel cannot take is launched by itself, unsplit.
+static int gemm_launch_grouped_thin(const GemmDesc* d, int count, hipStream_t stream) {
+    GemmGroupParams gp;
+    gp.ngroups = 0;
+    int tiles = 0, batch = 0;
+    auto flush = [&]() -> int {
+        if (gp.ngroups == 0) return 0;
+        gp.tile_start[gp.ngroups] = tiles;
+        const dim3 grid((unsigned)tiles, 1, (unsigned)batch), block(64 * kKGroups);
+        hipLaunchKernelGGL((gemm_dma_kg_grouped_kernel<1, true, true>), grid, block, 0, stream, gp);
+        gp.ngroups = 0;
+        tiles = 0;
+        const hipError_t e = hipGetLastError();
+        return e == hipSuccess ? 0 : note_hip_error(e);
+    };
+    for (int i = 0; i < count; ++i) {
+        const GemmDesc& di = d[i];
+        if (di.M <= 0 || di.N <= 0 || di.batch <= 0) continue;
+        if (!di.a_kc || !di.b_kc || di.batch != d[0].batch || di.epi.rowsum_dst != nullptr) return note_hip_error(hipErrorInvalidValue);
+        const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, 14, 1);
+        const GemmKParams q = fill_params(di, pl, nullptr);
+        if (!dma_eligible(di, q) || di.K / kDmaBK < kKGroups) {
+            GemmDesc one = di;
+            one.force_cfg = -1; one.force_splits = 1;
+            if (gemm_launch(one, nullptr, 0, stream) != 0) return -1;
+            continue;
+        }
+        batch = di.batch;
+        gp.g[gp.ngroups] = q;
+        gp.tile_start[gp.ngroups] = tiles;
+        tiles += q.tiles_m * q.tiles_n;
+        if (++gp.ngroups == kMaxGroups && flush() != 0) return -1;
+    }
+    return flush();
+}
+
+int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream, bool thin) {
+    if (thin) return gemm_launch_grouped_thin(d, count, stream);
     // Two passes over the problems: those the direct-to-LDS kernel accepts, then the rest (ragged or unaligned
     // ones, e.g. a layer whose width is not a multiple of 4) with the register-staged kernel.
     for (int pass = 0; pass < 2; ++pass) {

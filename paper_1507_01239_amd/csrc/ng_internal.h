@@ -24,6 +24,9 @@ int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank);
 // returns 0 or a hipError_t.  Preconditions the two factors and applies the update; the folds of the states are
 // left pending (their Y matrices stay in the scratch) until ng_dnn_finish.
 int ng_layer_update(const NgLayerArgs& a, hipStream_t s);
+// The same for all layers of the network at once (layers[l - 1] describes layer l; all share k, n, rank, alpha, eta,
+// ws): one launch per step of the recipe instead of one per step and layer side.  Steady state only (mode 1).
+int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s);
 // Fold this minibatch into all 2*L*k states (after ng_layer_update has run for every layer).
 int ng_dnn_finish(const int* d, int L, int n, int k, int rank, float eta, char* ng_state, int64_t state_stride, float* ws,
                   hipStream_t s);

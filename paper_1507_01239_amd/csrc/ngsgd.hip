@@ -511,6 +511,172 @@ __global__ __launch_bounds__(256) void ng_augment_kernel(const float* __restrict
     }
 }
 
+
+// ---- every layer side of a backward pass at once ---------------------------------------------------
+//
+// Between the end of the back-propagation chain and the weight updates the 2 L preconditioned matrices of a
+// network (input and output side of every layer) are independent of each other.  One preconditioning is a dozen
+// small launches, each a few microseconds of mostly latency; the kernels below take a table of slots (one slot =
+// one matrix, times `batch` replicas) so that a whole backward pass needs one launch per step of the recipe
+// instead of one per step and matrix.  Same arithmetic per element as the single-matrix kernels above.
+struct NgSlots {
+    char* state[kNgSlots];          // state of (slot, replica 0); replica b at + b * st_b bytes
+    float* x[kNgSlots];             // matrix of (slot, replica 0), n x dim, preconditioned in place
+    int64_t ldx[kNgSlots], x_b[kNgSlots];
+    int dim[kNgSlots];
+    int64_t st_b;
+    int nslots, batch, n, rank;
+    // scratch with one stride per (slot, replica) pair q = slot * batch + b
+    float* H; float* H2; int64_t ldr, H_b;      // n x ldr each, at + q * H_b
+    float* coef;                                // at + q * 3 kMaxRank
+    double* part;                               // at + q * 256
+    double* scal;                               // at + q * 2: ||X||^2, ||Xh||^2
+    float* gamma;                               // at + q
+};
+
+__global__ __launch_bounds__(256) void ng_sumsq_partial_slots_kernel(NgSlots t) {
+    __shared__ double sh[4];
+    const int slot = blockIdx.y, b = blockIdx.z;
+    const int64_t q = (int64_t)slot * t.batch + b;
+    const float* __restrict__ xb = t.x[slot] + (int64_t)b * t.x_b[slot];
+    const int64_t ldx = t.ldx[slot];
+    const int dim = t.dim[slot], n = t.n;
+    const bool vec = (ldx & 3) == 0 && (t.x_b[slot] & 3) == 0 && (reinterpret_cast<uintptr_t>(t.x[slot]) & 15u) == 0;
+    double s = 0.0;
+    for (int r = blockIdx.x; r < n; r += gridDim.x) {
+        const float* __restrict__ row = xb + (int64_t)r * ldx;
+        float a = 0.f;
+        if (vec) {
+            const int nq = dim >> 2;
+            int c4 = threadIdx.x;
+            for (; c4 + 768 < nq; c4 += 1024) {
+                const float4 v0 = *reinterpret_cast<const float4*>(row + 4 * c4);
+                const float4 v1 = *reinterpret_cast<const float4*>(row + 4 * (c4 + 256));
+                const float4 v2 = *reinterpret_cast<const float4*>(row + 4 * (c4 + 512));
+                const float4 v3 = *reinterpret_cast<const float4*>(row + 4 * (c4 + 768));
+                a += (v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w);
+                a += (v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w);
+                a += (v2.x * v2.x + v2.y * v2.y) + (v2.z * v2.z + v2.w * v2.w);
+                a += (v3.x * v3.x + v3.y * v3.y) + (v3.z * v3.z + v3.w * v3.w);
+            }
+            for (; c4 < nq; c4 += 256) {
+                const float4 v0 = *reinterpret_cast<const float4*>(row + 4 * c4);
+                a += (v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w);
+            }
+            for (int c = 4 * nq + threadIdx.x; c < dim; c += 256) { const float e = row[c]; a += e * e; }
+        } else {
+            for (int c = threadIdx.x; c < dim; c += 256) { const float e = row[c]; a += e * e; }
+        }
+        s += (double)a;
+    }
+    s = block_sum_d(s, sh);
+    if (threadIdx.x == 0) t.part[q * 256 + blockIdx.x] = s;
+}
+
+// which == 0: scal[q][0] = ||X||^2 and the coefficients of the apply and the fold (as ng_coeff_kernel);
+// which == 1: scal[q][1] = ||Xh||^2 and gamma[q] = ||X|| / ||Xh|| (1 if either is 0)
+__global__ __launch_bounds__(256) void ng_sumsq_final_slots_kernel(NgSlots t, int which, float alpha, float eta) {
+    __shared__ double sh[4];
+    const int slot = blockIdx.x, b = blockIdx.y;
+    const int64_t q = (int64_t)slot * t.batch + b;
+    double s = t.part[q * 256 + threadIdx.x];
+    s = block_sum_d(s, sh);
+    if (threadIdx.x == 0) {
+        t.scal[q * 2 + which] = s;
+        if (which == 1) {
+            const double nx = t.scal[q * 2 + 0];
+            t.gamma[q] = (nx > 0.0 && s > 0.0) ? (float)sqrt(nx / s) : 1.f;
+        }
+    }
+    if (which == 0) {
+        const int dim = t.dim[slot], rank = t.rank;
+        const StateView v = state_view(t.state[slot] + (int64_t)b * t.st_b, dim, rank);
+        double sumd = 0.0;
+        for (int j = 0; j < rank; ++j) sumd += v.d[j];
+        const double rho = *v.rho;
+        const double beta = rho * (1.0 + (double)alpha) + (double)alpha * sumd / (double)dim;
+        if ((int)threadIdx.x < rank) {
+            const double di = v.d[threadIdx.x];
+            float* __restrict__ cf = t.coef + q * (3 * kMaxRank);
+            cf[threadIdx.x] = (float)(di / (di + beta));
+            cf[kMaxRank + threadIdx.x] = (float)((1.0 - (double)eta) * (di + rho));
+            cf[2 * kMaxRank + threadIdx.x] = (float)(beta / (di + beta));
+        }
+    }
+}
+
+// H2 <- H (I - E) - H2 for every slot
+__global__ __launch_bounds__(256) void ng_combine_slots_kernel(NgSlots t) {
+    const int slot = blockIdx.y, b = blockIdx.z;
+    const int64_t q = (int64_t)slot * t.batch + b;
+    const float* __restrict__ ome = t.coef + q * (3 * kMaxRank) + 2 * kMaxRank;
+    const float* __restrict__ H = t.H + q * t.H_b;
+    float* __restrict__ H2 = t.H2 + q * t.H_b;
+    const int64_t total = (int64_t)t.n * t.ldr;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int i = (int)(e % t.ldr);
+        if (i < t.rank) H2[e] = H[e] * ome[i] - H2[e];
+    }
+}
+
+// X <- X + sign * Cm R for every slot (Cm = H or H2 of the slot); see ng_rank_update_kernel
+template <int RANK_MAX>
+__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign) {
+    __shared__ float cs[kRuRows][RANK_MAX];
+    const int slot = blockIdx.z / t.batch, b = blockIdx.z - slot * t.batch;
+    const int dim = t.dim[slot], n = t.n, rank = t.rank;
+    if ((int)blockIdx.x * 256 >= dim) return;          // the grid is as wide as the widest slot
+    const int64_t q = (int64_t)slot * t.batch + b;
+    const int col = blockIdx.x * 256 + threadIdx.x, row0 = blockIdx.y * kRuRows;
+    const float* __restrict__ cb = (use_h2 ? t.H2 : t.H) + q * t.H_b;
+    const int64_t ldc = t.ldr;
+    for (int i = threadIdx.x; i < kRuRows * RANK_MAX; i += 256) {
+        const int rr = i / RANK_MAX, k = i - rr * RANK_MAX;
+        cs[rr][k] = (k < rank && row0 + rr < n) ? cb[(int64_t)(row0 + rr) * ldc + k] : 0.f;
+    }
+    __syncthreads();
+    if (col >= dim) return;
+    const int64_t ldr = ((int64_t)dim + 3) / 4 * 4, ldx = t.ldx[slot];
+    float rc[RANK_MAX];
+    const float* __restrict__ rb = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b) + col;
+#pragma unroll
+    for (int k = 0; k < RANK_MAX; ++k) rc[k] = k < rank ? rb[(int64_t)k * ldr] : 0.f;
+    float* __restrict__ xb = t.x[slot] + (int64_t)b * t.x_b[slot] + col;
+    float old[kRuRows];
+#pragma unroll
+    for (int rr = 0; rr < kRuRows; ++rr) old[rr] = row0 + rr < n ? xb[(int64_t)(row0 + rr) * ldx] : 0.f;
+#pragma unroll
+    for (int rr = 0; rr < kRuRows; ++rr) {
+        float acc = 0.f;
+#pragma unroll
+        for (int k = 0; k < RANK_MAX; ++k) acc += cs[rr][k] * rc[k];
+        if (row0 + rr < n) xb[(int64_t)(row0 + rr) * ldx] = old[rr] + sign * acc;
+    }
+}
+
+// Xaug_l[b](r, 0..d) = A_l[b](r, :), Xaug_l[b](r, d) = 1, padding columns 0, for up to kNgSlots / 2 layers
+struct NgAugTable {
+    const float* A[kNgSlots / 2]; int64_t lda[kNgSlots / 2], a_b[kNgSlots / 2];
+    float* X[kNgSlots / 2]; int64_t ldx[kNgSlots / 2], x_b[kNgSlots / 2];
+    int d[kNgSlots / 2];
+    int n;
+};
+__global__ __launch_bounds__(256) void ng_augment_slots_kernel(NgAugTable t) {
+    const int l = blockIdx.y, b = blockIdx.z;
+    const int64_t ldx = t.ldx[l], lda = t.lda[l];
+    const int d = t.d[l];
+    const float* __restrict__ A = t.A[l] + (int64_t)b * t.a_b[l];
+    float* __restrict__ X = t.X[l] + (int64_t)b * t.x_b[l];
+    const int64_t total = (int64_t)t.n * ldx;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int64_t r = e / ldx, c = e - r * ldx;
+        float v = 0.f;
+        if (c < d) v = A[r * lda + c];
+        else if (c == d) v = 1.f;
+        X[e] = v;
+    }
+}
+
 // ---- host orchestration --------------------------------------------------------------------------
 
 struct NgCall {
@@ -685,6 +851,10 @@ namespace {
 struct NgDnnLayout {
     int64_t y_off[2 * 64], y_b[2 * 64];     // slot 2(l-1): input side of layer l, slot 2(l-1)+1: output side
     int64_t scal_off, z_off, wt_off, layer_off, layer_floats, total;
+    // all layers at once: augmented inputs of every layer, then per-(slot, replica) H, H2, coefficients, partial
+    // sums and gamma
+    int64_t xaug_off[64 + 1], ld_in[64 + 1];
+    int64_t ldr, H_b, h_off, h2_off, coef_off, part_off, gamma_off;
 };
 NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     NgDnnLayout y;
@@ -706,7 +876,21 @@ NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
         const int64_t f = ng_layer_ws_floats(d[l - 1], d[l], n, k, rank);
         if (f > y.layer_floats) y.layer_floats = f;
     }
-    y.total = off + y.layer_floats;
+    off += y.layer_floats;
+    for (int l = 1; l <= L; ++l) {
+        y.ld_in[l] = round_up(d[l - 1] + 1, 4);
+        y.xaug_off[l] = off;
+        off += round_up((int64_t)k * n * y.ld_in[l], 64);
+    }
+    const int64_t q = (int64_t)2 * L * k;
+    y.ldr = round_up(rank, 4);
+    y.H_b = round_up((int64_t)n * y.ldr, 64);
+    y.h_off = off;     off += q * y.H_b;
+    y.h2_off = off;    off += q * y.H_b;
+    y.coef_off = off;  off += q * 3 * kMaxRank;
+    y.part_off = off;  off += q * 2 * 256;
+    y.gamma_off = off; off += round_up(q, 64);
+    y.total = off;
     return y;
 }
 }  // namespace
@@ -777,6 +961,130 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
         g.epi.alpha_dev0 = gamma_in; g.epi.alpha_dev1 = gamma_out;
         g.epi.lastcol = a.d_in; g.epi.lastcol_dst = a.b; g.epi.lastcol_bstride = a.theta_stride;
         NG_CHECK(gemm_launch(g, a.gemm_ws, a.gemm_ws_floats, s));
+    }
+    return 0;
+}
+
+
+// The preconditioned update of every layer (steady state: one fold per minibatch), a fixed number of launches
+// whatever the depth: augment, ||X||^2 + coefficients, H, Y, X1, H2, combine, Xh, ||Xh||^2 + gamma, then the weight
+// gradients of all layers as one grouped launch.  The folds stay pending until ng_dnn_finish.
+int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
+    const NgLayerArgs& a0 = layers[0];
+    const int n = a0.n, k = a0.k, rank = a0.rank;
+    const NgDnnLayout lay = ng_dnn_layout(a0.dims, L, n, k, rank);
+    if (a0.ws_floats < lay.total) return (int)hipErrorInvalidValue;
+    float* ws = a0.ws;
+    double* scal = reinterpret_cast<double*>(ws + lay.scal_off);
+    constexpr int kLayersPerPass = kNgSlots / 2;
+    for (int l0 = 0; l0 < L; l0 += kLayersPerPass) {
+        const int nl = (L - l0) < kLayersPerPass ? (L - l0) : kLayersPerPass;
+        const int j0 = 2 * l0;                          // first slot of this pass
+        NgSlots t;
+        NgAugTable au;
+        t.nslots = 2 * nl; t.batch = k; t.n = n; t.rank = rank; t.st_b = a0.state_rstride;
+        t.ldr = lay.ldr; t.H_b = lay.H_b;
+        t.H = ws + lay.h_off + (int64_t)j0 * k * lay.H_b;
+        t.H2 = ws + lay.h2_off + (int64_t)j0 * k * lay.H_b;
+        t.coef = ws + lay.coef_off + (int64_t)j0 * k * 3 * kMaxRank;
+        t.part = reinterpret_cast<double*>(ws + lay.part_off) + (int64_t)j0 * k * 256;
+        t.scal = scal + (int64_t)j0 * k * 2;
+        t.gamma = ws + lay.gamma_off + (int64_t)j0 * k;
+        au.n = n;
+        int maxdim = 0;
+        int64_t max_aug = 0;
+        for (int i = 0; i < nl; ++i) {
+            const NgLayerArgs& a = layers[l0 + i];
+            const int l = a.l;
+            const int64_t ld_in = lay.ld_in[l], aug_b = (int64_t)n * ld_in;
+            float* Xaug = ws + lay.xaug_off[l];
+            au.A[i] = a.A_in; au.lda[i] = a.a_ld; au.a_b[i] = a.a_bstride; au.d[i] = a.d_in;
+            au.X[i] = Xaug; au.ldx[i] = ld_in; au.x_b[i] = aug_b;
+            if (aug_b > max_aug) max_aug = aug_b;
+            t.state[2 * i] = a.state_in;      t.x[2 * i] = Xaug;        t.ldx[2 * i] = ld_in;     t.x_b[2 * i] = aug_b;
+            t.dim[2 * i] = a.d_in + 1;
+            t.state[2 * i + 1] = a.state_out; t.x[2 * i + 1] = a.delta; t.ldx[2 * i + 1] = a.ldd; t.x_b[2 * i + 1] = a.d_bstride;
+            t.dim[2 * i + 1] = a.d_out;
+            if (a.d_in + 1 > maxdim) maxdim = a.d_in + 1;
+            if (a.d_out > maxdim) maxdim = a.d_out;
+        }
+        {
+            int64_t gx = (max_aug + 255) / 256;
+            if (gx > 1024) gx = 1024;
+            hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, nl, k), dim3(256), 0, s, au);
+            NG_LAUNCHED();
+        }
+        auto sumsq = [&](int which) -> int {
+            hipLaunchKernelGGL(ng_sumsq_partial_slots_kernel, dim3(256, t.nslots, k), dim3(256), 0, s, t);
+            NG_LAUNCHED();
+            hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, k), dim3(256), 0, s, t, which, a0.alpha, a0.eta);
+            NG_LAUNCHED();
+            return 0;
+        };
+        auto gemm_H = [&](float* Hout) -> int {          // Hout = X R^T for every slot
+            GemmDesc g[kNgSlots];
+            for (int j = 0; j < t.nslots; ++j) {
+                GemmDesc& q = g[j];
+                q.M = n; q.N = rank; q.K = t.dim[j]; q.batch = k;
+                q.A = t.x[j]; q.lda = t.ldx[j]; q.a_bstride = t.x_b[j]; q.a_kc = true;
+                q.B = reinterpret_cast<const float*>(t.state[j]); q.ldb = round_up(t.dim[j], 4); q.b_bstride = t.st_b / 4; q.b_kc = true;
+                q.C = Hout + (int64_t)j * k * lay.H_b; q.ldc = lay.ldr; q.c_bstride = lay.H_b;
+            }
+            return gemm_launch_grouped(g, t.nslots, s, true);
+        };
+        auto rank_update = [&](int use_h2, float sign) -> int {
+            const dim3 grid((unsigned)((maxdim + 255) / 256), (unsigned)((n + kRuRows - 1) / kRuRows), (unsigned)(t.nslots * k));
+            if (rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<32>, grid, dim3(256), 0, s, t, use_h2, sign);
+            else hipLaunchKernelGGL(ng_rank_update_slots_kernel<kMaxRank>, grid, dim3(256), 0, s, t, use_h2, sign);
+            NG_LAUNCHED();
+            return 0;
+        };
+        NG_CHECK(sumsq(0));
+        NG_CHECK(gemm_H(t.H));
+        {   // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it
+            GemmDesc g[kNgSlots];
+            for (int j = 0; j < t.nslots; ++j) {
+                GemmDesc& q = g[j];
+                const int64_t ld = round_up(t.dim[j], 4);
+                q.M = rank; q.N = t.dim[j]; q.K = n; q.batch = k;
+                q.A = t.H + (int64_t)j * k * lay.H_b; q.lda = lay.ldr; q.a_bstride = lay.H_b; q.a_kc = false;
+                q.a_pad4 = true;        // rows of H are ldr = round_up(rank, 4) floats long
+                q.B = t.x[j]; q.ldb = t.ldx[j]; q.b_bstride = t.x_b[j]; q.b_kc = false;
+                q.b_pad4 = t.ldx[j] >= ld;
+                q.C = ws + lay.y_off[j0 + j]; q.ldc = ld; q.c_bstride = lay.y_b[j0 + j];
+                q.epi.kind = EPI_ROWSCALE_ADD; q.epi.alpha = a0.eta / (float)n;
+                q.epi.rowvec = t.coef + (int64_t)j * k * 3 * kMaxRank + kMaxRank; q.epi.rowvec_bstride = 3 * kMaxRank;
+                q.epi.aux = reinterpret_cast<const float*>(t.state[j]); q.epi.ldaux = ld; q.epi.aux_bstride = t.st_b / 4;
+            }
+            NG_CHECK(gemm_launch_grouped(g, t.nslots, s));
+        }
+        NG_CHECK(rank_update(0, -1.f));                  // X1 = X - H R
+        NG_CHECK(gemm_H(t.H2));                          // H2 = X1 R^T
+        {
+            int64_t gx = ((int64_t)n * lay.ldr + 255) / 256;
+            if (gx > 1024) gx = 1024;
+            hipLaunchKernelGGL(ng_combine_slots_kernel, dim3((unsigned)gx, t.nslots, k), dim3(256), 0, s, t);
+            NG_LAUNCHED();
+        }
+        NG_CHECK(rank_update(1, 1.f));                   // Xh = X1 + (H (I - E) - H2) R
+        NG_CHECK(sumsq(1));
+        {   // [W | b] <- [W | b] - lr g_out g_in Xh_out^T Xh_in for the layers of this pass
+            GemmDesc g[kLayersPerPass];
+            for (int i = 0; i < nl; ++i) {
+                const NgLayerArgs& a = layers[l0 + i];
+                GemmDesc& q = g[i];
+                q.M = a.d_out; q.N = a.d_in + 1; q.K = n; q.batch = k;
+                q.A = a.delta; q.lda = a.ldd; q.a_bstride = a.d_bstride; q.a_kc = false;
+                q.a_pad4 = true;
+                q.B = t.x[2 * i]; q.ldb = t.ldx[2 * i]; q.b_bstride = t.x_b[2 * i]; q.b_kc = false;
+                q.b_pad4 = true;
+                q.C = a.W; q.ldc = a.d_in; q.c_bstride = a.theta_stride;
+                q.epi.kind = EPI_AXPBY; q.epi.alpha = -a.lr; q.epi.beta = 1.f;
+                q.epi.alpha_dev0 = t.gamma + (int64_t)(2 * i) * k; q.epi.alpha_dev1 = t.gamma + (int64_t)(2 * i + 1) * k;
+                q.epi.lastcol = a.d_in; q.epi.lastcol_dst = a.b; q.epi.lastcol_bstride = a.theta_stride;
+            }
+            NG_CHECK(gemm_launch_grouped(g, nl, s));
+        }
     }
     return 0;
 }
