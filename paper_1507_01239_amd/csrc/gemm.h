@@ -72,6 +72,7 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
 // Several independent GEMMs of the same operand layouts and batch count in ONE launch (64x64 tiles, unsplit
 // contraction, no scratch).  `thin`: products with few output columns and a long contraction, both operands
 // k-contiguous (32x32 tiles, the contraction split four ways inside each workgroup).  Returns hipError_t as int.
+constexpr int kThinMaxProblems = 40;    // thin problems one launch takes (more are launched in further launches)
 int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream, bool thin = false);
 
 }  // namespace mavg

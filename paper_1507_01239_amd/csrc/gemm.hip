@@ -695,11 +695,11 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
 // instead of 4 (3 direct loads per wavefront and k-tile instead of 2).
 constexpr int kKGroups = 4;
 
-template <int GW, bool AKC, bool BKC>
+template <int GW, bool AKC, bool BKC, int KG = kKGroups>
 __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int tile, const int bz) {
     // GW wavefronts per k-group: 2 (32x64 tile, one barrier per k-tile) or 1 (32x32 tile: a k-group is a single
     // wavefront with a ring of its own, so the loop needs no barrier at all, only the wavefront's own vmcnt waits)
-    constexpr int BK = kDmaBK, NST = 4, BM = 32, BN = 32 * GW, KG = kKGroups;
+    constexpr int BK = kDmaBK, NST = 4, BM = 32, BN = 32 * GW;
     constexpr int A_LOADS = 2 / GW, LOADS = A_LOADS + 2;
     static_assert(GW == 1 || GW == 2, "one or two wavefronts per k-group");
     constexpr int TILE_A = BM * BK, TILE_B = BN * BK;
@@ -856,7 +856,10 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     if (kg > 0) return;
     static_for<16>([&](auto vc) {
         constexpr int v = decltype(vc)::value;
-        acc[0][0][v] = ((acc[0][0][v] + red[0][gw][v][lane]) + red[1][gw][v][lane]) + red[2][gw][v][lane];
+        float r = acc[0][0][v];
+#pragma unroll
+        for (int g = 0; g < KG - 1; ++g) r += red[g][gw][v][lane];
+        acc[0][0][v] = r;
     });
     const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
     MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0, n0 + wn, lrow, lcol)))
@@ -903,13 +906,45 @@ __global__ __launch_bounds__(256) void gemm_dma_grouped_kernel(GemmGroupParams g
     gemm_dma_body<TM, TN, NST, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
-// Several thin products (few output columns, long contraction) in one launch of the in-workgroup-split kernel.
-template <int GW, bool AKC, bool BKC>
-__global__ __launch_bounds__(64 * kKGroups * GW) void gemm_dma_kg_grouped_kernel(GemmGroupParams gp) {
+// Several thin products C = A B^T (few output columns, long contraction, both operands k-contiguous, plain
+// store) in one launch of the in-workgroup-split kernel with 32x32 tiles and four k-groups of one wavefront.
+// The table is compact so that 40 problems fit the 4 KB of kernel arguments.
+constexpr int kMaxThin = kThinMaxProblems, kThinKGroups = 4;
+struct ThinProblem {
+    const float* A; const float* B; float* C;
+    int64_t lda, ldb, ldc, a_bstride, b_bstride, c_bstride;
+    int M, N, K;
+};
+struct ThinGroupParams {
+    ThinProblem g[kMaxThin];
+    int tile_start[kMaxThin + 1];
+    int ngroups;
+};
+__global__ __launch_bounds__(64 * kThinKGroups) void gemm_thin_grouped_kernel(ThinGroupParams gp) {
+    int gi = 0;
+    static_for<kMaxThin - 1>([&](auto ic) {
+        constexpr int i = decltype(ic)::value + 1;
+        if (i < gp.ngroups && (int)blockIdx.x >= gp.tile_start[i]) gi = i;
+    });
+    ThinProblem t = gp.g[0];
+    int first = 0;
+    static_for<kMaxThin - 1>([&](auto ic) {          // one copy with a compile-time index (see select_group)
+        constexpr int i = decltype(ic)::value + 1;
+        if (gi == i) { t = gp.g[i]; first = gp.tile_start[i]; }
+    });
     GemmKParams p;
-    const int first = select_group(gp, p);
-    gemm_dma_kg_body<GW, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
+    p.A = t.A; p.lda = t.lda; p.a_bstride = t.a_bstride;
+    p.B = t.B; p.ldb = t.ldb; p.b_bstride = t.b_bstride;
+    p.C = t.C; p.ldc = t.ldc; p.c_bstride = t.c_bstride;
+    p.M = t.M; p.N = t.N; p.K = t.K; p.batch = (int)gridDim.z; p.splits = 1;
+    p.kper = (t.K + kDmaBK - 1) / kDmaBK * kDmaBK;
+    p.Mr = t.M; p.Nr = t.N;
+    p.tiles_m = (t.M + 31) / 32; p.tiles_n = (t.N + 31) / 32;
+    p.vecA = 1; p.vecB = 1;
+    p.ws = nullptr;
+    gemm_dma_kg_body<1, true, true, kThinKGroups>(p, (int)blockIdx.x - first, blockIdx.z);
 }
+
 
 // Sum the partial results of a split contraction in split order and apply the epilogue.
 __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
@@ -1155,17 +1190,17 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
 
 constexpr int kGroupedStages = 3;
 
-// Thin products X R^T (both operands k-contiguous) on 32x32 tiles with the contraction split inside the workgroup;
-// a problem that kernel cannot take is launched by itself, unsplit.
+// Thin products X R^T in one launch (see gemm_thin_grouped_kernel); a problem that kernel cannot take is launched by
+// itself, unsplit.
 static int gemm_launch_grouped_thin(const GemmDesc* d, int count, hipStream_t stream) {
-    GemmGroupParams gp;
+    ThinGroupParams gp;
     gp.ngroups = 0;
     int tiles = 0, batch = 0;
     auto flush = [&]() -> int {
         if (gp.ngroups == 0) return 0;
         gp.tile_start[gp.ngroups] = tiles;
-        const dim3 grid((unsigned)tiles, 1, (unsigned)batch), block(64 * kKGroups);
-        hipLaunchKernelGGL((gemm_dma_kg_grouped_kernel<1, true, true>), grid, block, 0, stream, gp);
+        const dim3 grid((unsigned)tiles, 1, (unsigned)batch), block(64 * kThinKGroups);
+        hipLaunchKernelGGL(gemm_thin_grouped_kernel, grid, block, 0, stream, gp);
         gp.ngroups = 0;
         tiles = 0;
         const hipError_t e = hipGetLastError();
@@ -1174,20 +1209,25 @@ static int gemm_launch_grouped_thin(const GemmDesc* d, int count, hipStream_t st
     for (int i = 0; i < count; ++i) {
         const GemmDesc& di = d[i];
         if (di.M <= 0 || di.N <= 0 || di.batch <= 0) continue;
-        if (!di.a_kc || !di.b_kc || di.batch != d[0].batch || di.epi.rowsum_dst != nullptr) return note_hip_error(hipErrorInvalidValue);
+        if (!di.a_kc || !di.b_kc || di.batch != d[0].batch || di.epi.kind != EPI_STORE || di.epi.rowsum_dst != nullptr)
+            return note_hip_error(hipErrorInvalidValue);
         const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, 14, 1);
         const GemmKParams q = fill_params(di, pl, nullptr);
-        if (!dma_eligible(di, q) || di.K / kDmaBK < kKGroups) {
+        if (!dma_eligible(di, q) || di.K / kDmaBK < kThinKGroups) {
             GemmDesc one = di;
             one.force_cfg = -1; one.force_splits = 1;
             if (gemm_launch(one, nullptr, 0, stream) != 0) return -1;
             continue;
         }
         batch = di.batch;
-        gp.g[gp.ngroups] = q;
+        ThinProblem& t = gp.g[gp.ngroups];
+        t.A = di.A; t.B = di.B; t.C = di.C;
+        t.lda = di.lda; t.ldb = di.ldb; t.ldc = di.ldc;
+        t.a_bstride = di.a_bstride; t.b_bstride = di.b_bstride; t.c_bstride = di.c_bstride;
+        t.M = di.M; t.N = di.N; t.K = di.K;
         gp.tile_start[gp.ngroups] = tiles;
         tiles += q.tiles_m * q.tiles_n;
-        if (++gp.ngroups == kMaxGroups && flush() != 0) return -1;
+        if (++gp.ngroups == kMaxThin && flush() != 0) return -1;
     }
     return flush();
 }

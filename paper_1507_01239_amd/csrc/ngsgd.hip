@@ -91,6 +91,17 @@ __device__ __forceinline__ double block_sum_d(double v, double* sh) {
     return r;
 }
 
+// the eigen-solver runs 512 threads: 16 groups of 32 lanes, one group per rotation pair up to rank 32
+constexpr int kEigThreads = 512;
+__device__ __forceinline__ double block_sum_eig(double v, double* sh) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const double r = ((sh[0] + sh[1]) + (sh[2] + sh[3])) + ((sh[4] + sh[5]) + (sh[6] + sh[7]));
+    __syncthreads();
+    return r;
+}
+
 // Table of independent folds finished by one launch of each of ng_z_kernel / ng_eig_kernel / ng_newr_kernel:
 // slot = one preconditioned matrix (a layer's input or output side), times `batch` replicas.
 constexpr int kNgSlots = 32;
@@ -271,27 +282,29 @@ __global__ __launch_bounds__(256) void ng_z_kernel(NgFoldTable tb, int rank, dou
 }
 
 // Symmetric eigen-decomposition of the rank x rank matrix Z by cyclic Jacobi rotations in a round-robin
-// (tournament) order, so that the rank/2 disjoint rotations of a round are applied in parallel; then the
+// (tournament) order, so that the rank/2 disjoint rotations of a round are applied in parallel, rows and
+// columns in one pass (the column partner's entries come from a neighbouring lane); then the
 // new d, rho, t and the matrix Wt = diag(c)^-1/2 U^T (rows in descending order of c).
-__global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, int n, float eta, const double* __restrict__ Zg,
+__global__ __launch_bounds__(kEigThreads) void ng_eig_kernel(NgFoldTable tb, int rank, int n, float eta, const double* __restrict__ Zg,
                                                      double* __restrict__ Wt, int bump_t) {
     extern __shared__ double smem[];
     const int r = rank;
     const int rs = r | 1;            // odd row stride: column walks spread over the LDS banks
     double* Zs = smem;               // r x rs
     double* Us = Zs + r * rs;        // r x rs, holds U TRANSPOSED (row k = eigenvector k), so its update is a row rotation
-    double* cs = Us + r * rs;        // 32 cos
-    double* sn = cs + 32;            // 32 sin
-    double* red = sn + 32;           // 8
+    double* al = Us + r * rs;        // 64: a round turns row (and column) i into al[i] row_i + be[i] row_partner(i)
+    double* be = al + 64;            // 64
+    double* red = be + 64;           // 8
     int* pp = reinterpret_cast<int*>(red + 8);   // 32 + 32 pair indices
     int* qq = pp + 32;
     int* order = qq + 32;            // 64
+    int* partner = order + 64;       // 64
     const int slot = blockIdx.x / tb.batch, b = blockIdx.x - slot * tb.batch, tid = threadIdx.x;
     const int dim = tb.dim[slot];
     const int64_t zi = (int64_t)(tb.first + slot) * tb.batch + b;
     const double* __restrict__ Zb = Zg + zi * kMaxRank * kMaxRank;
-    // thread = (lane: an index along a row or column, grp: which rotation pair / which row)
-    const int lw = r <= 32 ? 32 : 64, ngrp = 256 / lw;
+    // thread = (lane: an index along a row, grp: which rotation pair / which row); a group never straddles a wavefront
+    const int lw = r <= 32 ? 32 : 64, ngrp = kEigThreads / lw;
     const int lane = tid & (lw - 1), grp = tid / lw;
     for (int i = grp; i < r; i += ngrp)
         if (lane < r) {
@@ -309,50 +322,57 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
                 const double v = Zs[i * rs + lane];
                 if (i == lane) dg += v * v; else off += v * v;
             }
-        off = block_sum_d(off, red);
-        dg = block_sum_d(dg, red);
+        off = block_sum_eig(off, red);
+        dg = block_sum_eig(dg, red);
         if (off <= 1e-26 * dg) break;       // off-diagonal norm below 1e-13 of the diagonal
         for (int round = 0; round < m - 1; ++round) {
+            // Z <- J^T Z J, U^T <- J^T U^T with, for every pair (p, q) of the round,
+            // row_p <- c row_p - s row_q,  row_q <- s row_p + c row_q  (and the same for the columns of Z)
             if (tid < half) {
                 int p, q;
                 if (tid == 0) { p = m - 1; q = round; }
                 else { p = (round + tid) % (m - 1); q = (round - tid + (m - 1)) % (m - 1); }
                 if (p > q) { const int t = p; p = q; q = t; }
-                double c = 1.0, s = 0.0;
                 if (q < r) {
+                    double c = 1.0, s = 0.0;
                     const double apq = Zs[p * rs + q];
                     if (apq != 0.0) {
-                        const double tau = (Zs[q * rs + q] - Zs[p * rs + p]) / (2.0 * apq);
-                        const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
-                        c = 1.0 / sqrt(1.0 + t * t);
+                        // t = sgn(tau) / (|tau| + sqrt(1 + tau^2)) with tau = (aqq - app) / (2 apq), written with one
+                        // square root, one division and one reciprocal square root
+                        const double d = Zs[q * rs + q] - Zs[p * rs + p], b2 = 2.0 * apq;
+                        const double t = (d >= 0.0 ? b2 : -b2) / (fabs(d) + sqrt(d * d + b2 * b2));
+                        c = rsqrt(1.0 + t * t);
                         s = t * c;
                     }
-                } else { q = -1; }
-                pp[tid] = p; qq[tid] = q; cs[tid] = c; sn[tid] = s;
-            }
-            __syncthreads();
-            // rows of Z and of U^T:  row_p <- c row_p - s row_q ;  row_q <- s row_p + c row_q
-            for (int k = grp; k < half; k += ngrp) {
-                const int p = pp[k], q = qq[k];
-                if (q >= 0 && lane < r) {
-                    const double c = cs[k], s = sn[k];
-                    const double zp = Zs[p * rs + lane], zq = Zs[q * rs + lane];
-                    Zs[p * rs + lane] = c * zp - s * zq;
-                    Zs[q * rs + lane] = s * zp + c * zq;
-                    const double up = Us[p * rs + lane], uq = Us[q * rs + lane];
-                    Us[p * rs + lane] = c * up - s * uq;
-                    Us[q * rs + lane] = s * up + c * uq;
+                    al[p] = c; be[p] = -s; partner[p] = q;
+                    al[q] = c; be[q] = s;  partner[q] = p;
+                } else {          // the bye of an odd rank: row and column p stay
+                    al[p] = 1.0; be[p] = 0.0; partner[p] = p;
+                    q = -1;
                 }
+                pp[tid] = p; qq[tid] = q;
             }
             __syncthreads();
-            // columns of Z
+            // One pass: the group of pair k holds rows p and q; lane l rotates the rows (in registers), fetches the
+            // rotated entries of column partner(l) from the lane that holds them and rotates the columns.
             for (int k = grp; k < half; k += ngrp) {
                 const int p = pp[k], q = qq[k];
-                if (q >= 0 && lane < r) {
-                    const double c = cs[k], s = sn[k];
-                    const double zp = Zs[lane * rs + p], zq = Zs[lane * rs + q];
-                    Zs[lane * rs + p] = c * zp - s * zq;
-                    Zs[lane * rs + q] = s * zp + c * zq;
+                const bool on = lane < r, two = q >= 0;
+                const double c = al[p], s = two ? be[q] : 0.0;
+                const int qr = two ? q : p;
+                const double zp = on ? Zs[p * rs + lane] : 0.0, zq = (on && two) ? Zs[qr * rs + lane] : 0.0;
+                const double up = on ? Us[p * rs + lane] : 0.0, uq = (on && two) ? Us[qr * rs + lane] : 0.0;
+                const double wp = c * zp - s * zq, wq = s * zp + c * zq;
+                const int pl = on ? partner[lane] : lane;
+                const double a = on ? al[lane] : 1.0, bb = on ? be[lane] : 0.0;
+                const double wpo = __shfl(wp, pl, lw), wqo = __shfl(wq, pl, lw);
+                if (on) {
+                    Zs[p * rs + lane] = a * wp + bb * wpo;
+                    Us[p * rs + lane] = c * up - s * uq;
+                    if (two) {
+                        Zs[q * rs + lane] = a * wq + bb * wqo;
+                        Us[q * rs + lane] = s * up + c * uq;
+                    }
                 }
             }
             __syncthreads();
@@ -398,7 +418,7 @@ __global__ __launch_bounds__(256) void ng_eig_kernel(NgFoldTable tb, int rank, i
     }
     __syncthreads();
     double* __restrict__ Wb = Wt + zi * kMaxRank * kMaxRank;
-    for (int w = tid; w < r * r; w += 256) {
+    for (int w = tid; w < r * r; w += kEigThreads) {
         const int i = w / r, k = w - i * r;
         const int col = order[i];
         Wb[w] = Us[col * rs + k] / Zs[col * rs + col];
@@ -605,6 +625,25 @@ __global__ __launch_bounds__(256) void ng_sumsq_final_slots_kernel(NgSlots t, in
     }
 }
 
+// Hout of every slot = sum of the slot's partial products (one per chunk of the contraction), in chunk order
+struct NgChunkTable { int first[kNgSlots], count[kNgSlots]; };
+__global__ __launch_bounds__(256) void ng_sum_chunks_slots_kernel(NgSlots t, NgChunkTable ct, const float* __restrict__ P,
+                                                                  float* __restrict__ Hout) {
+    const int slot = blockIdx.y, b = blockIdx.z;
+    const int64_t q = (int64_t)slot * t.batch + b;
+    const int64_t total4 = (int64_t)t.n * t.ldr / 4;            // ldr is a multiple of 4
+    const int first = ct.first[slot], count = ct.count[slot];
+    float4* __restrict__ out = reinterpret_cast<float4*>(Hout + q * t.H_b);
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total4; e += (int64_t)gridDim.x * 256) {
+        float4 a = reinterpret_cast<const float4*>(P + ((int64_t)first * t.batch + b) * t.H_b)[e];
+        for (int c = 1; c < count; ++c) {
+            const float4 v = reinterpret_cast<const float4*>(P + ((int64_t)(first + c) * t.batch + b) * t.H_b)[e];
+            a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+        }
+        out[e] = a;
+    }
+}
+
 // H2 <- H (I - E) - H2 for every slot
 __global__ __launch_bounds__(256) void ng_combine_slots_kernel(NgSlots t) {
     const int slot = blockIdx.y, b = blockIdx.z;
@@ -619,38 +658,66 @@ __global__ __launch_bounds__(256) void ng_combine_slots_kernel(NgSlots t) {
     }
 }
 
-// X <- X + sign * Cm R for every slot (Cm = H or H2 of the slot); see ng_rank_update_kernel
-template <int RANK_MAX>
-__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign) {
-    __shared__ float cs[kRuRows][RANK_MAX];
+// X <- X + sign * Cm R for every slot (Cm = H or H2 of the slot) on the matrix cores: a wavefront owns 32
+// columns, keeps its 32 (x KH) x 32 block of R in registers as MFMA B operands and walks down `rows` rows in tiles
+// of 32; per tile it reads 32 x rank of Cm (16 contiguous floats per lane) and 32 x 32 of X, multiplies with
+// 16 KH v_mfma_f32_32x32x2_f32 and adds the product to X.  Contraction index of MFMA step s: k = 32 kh + s in
+// lanes 0-31 and 32 kh + 16 + s in lanes 32-63, zero operands beyond `rank`.  No LDS, no barrier.
+typedef float ng_floatx16 __attribute__((ext_vector_type(16)));
+template <int KH>
+__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows) {
     const int slot = blockIdx.z / t.batch, b = blockIdx.z - slot * t.batch;
     const int dim = t.dim[slot], n = t.n, rank = t.rank;
-    if ((int)blockIdx.x * 256 >= dim) return;          // the grid is as wide as the widest slot
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, lc = lane & 31;
+    const int c0 = (blockIdx.x * 4 + wave) * 32;
+    if (c0 >= dim) return;                              // the grid is as wide as the widest slot
+    const int col = c0 + lc;
+    const bool col_ok = col < dim;
     const int64_t q = (int64_t)slot * t.batch + b;
-    const int col = blockIdx.x * 256 + threadIdx.x, row0 = blockIdx.y * kRuRows;
-    const float* __restrict__ cb = (use_h2 ? t.H2 : t.H) + q * t.H_b;
-    const int64_t ldc = t.ldr;
-    for (int i = threadIdx.x; i < kRuRows * RANK_MAX; i += 256) {
-        const int rr = i / RANK_MAX, k = i - rr * RANK_MAX;
-        cs[rr][k] = (k < rank && row0 + rr < n) ? cb[(int64_t)(row0 + rr) * ldc + k] : 0.f;
-    }
-    __syncthreads();
-    if (col >= dim) return;
-    const int64_t ldr = ((int64_t)dim + 3) / 4 * 4, ldx = t.ldx[slot];
-    float rc[RANK_MAX];
-    const float* __restrict__ rb = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b) + col;
+    const int64_t ldR = ((int64_t)dim + 3) / 4 * 4, ldx = t.ldx[slot], ldc = t.ldr;
+    const float* __restrict__ R = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b);
+    const float* __restrict__ C = (use_h2 ? t.H2 : t.H) + q * t.H_b;
+    float* __restrict__ X = t.x[slot] + (int64_t)b * t.x_b[slot];
+    float bf[KH][16];
 #pragma unroll
-    for (int k = 0; k < RANK_MAX; ++k) rc[k] = k < rank ? rb[(int64_t)k * ldr] : 0.f;
-    float* __restrict__ xb = t.x[slot] + (int64_t)b * t.x_b[slot] + col;
-    float old[kRuRows];
+    for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
-    for (int rr = 0; rr < kRuRows; ++rr) old[rr] = row0 + rr < n ? xb[(int64_t)(row0 + rr) * ldx] : 0.f;
+        for (int s = 0; s < 16; ++s) {
+            const int k = 32 * kh + 16 * h + s;
+            bf[kh][s] = (k < rank && col_ok) ? R[(int64_t)k * ldR + col] : 0.f;
+        }
+    const int rbeg = blockIdx.y * rows, rend = min(n, rbeg + rows);
+    for (int r0 = rbeg; r0 < rend; r0 += 32) {
+        const int row = r0 + lc;
+        float af[KH][16];
 #pragma unroll
-    for (int rr = 0; rr < kRuRows; ++rr) {
-        float acc = 0.f;
+        for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
-        for (int k = 0; k < RANK_MAX; ++k) acc += cs[rr][k] * rc[k];
-        if (row0 + rr < n) xb[(int64_t)(row0 + rr) * ldx] = old[rr] + sign * acc;
+            for (int j = 0; j < 4; ++j) {
+                const int k4 = 32 * kh + 16 * h + 4 * j;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (row < rend && k4 < ldc) v = *reinterpret_cast<const float4*>(C + (int64_t)row * ldc + k4);   // ldc is a multiple of 4
+                af[kh][4 * j + 0] = (k4 + 0 < rank) ? v.x : 0.f;
+                af[kh][4 * j + 1] = (k4 + 1 < rank) ? v.y : 0.f;
+                af[kh][4 * j + 2] = (k4 + 2 < rank) ? v.z : 0.f;
+                af[kh][4 * j + 3] = (k4 + 3 < rank) ? v.w : 0.f;
+            }
+        float old[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+            old[v] = (rr < rend && col_ok) ? X[(int64_t)rr * ldx + col] : 0.f;
+        }
+        ng_floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+            for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[kh][s], bf[kh][s], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (rr < rend && col_ok) X[(int64_t)rr * ldx + col] = old[v] + sign * acc[v];
+        }
     }
 }
 
@@ -702,7 +769,7 @@ struct NgCall {
     } while (0)
 #define NG_LAUNCHED() NG_CHECK(note_hip_error(hipGetLastError()))
 
-int ng_eig_smem_bytes(int rank) { return (2 * rank * (rank | 1) + 32 + 32 + 8) * 8 + (32 + 32 + 64) * 4; }
+int ng_eig_smem_bytes(int rank) { return (2 * rank * (rank | 1) + 64 + 64 + 8) * 8 + (32 + 32 + 64 + 64) * 4; }
 
 // Z = Y Y^T, eigen-decomposition, new (R, d, rho, t) for every (slot, replica) of the table: three launches.
 int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, double* Wt, int bump, hipStream_t s) {
@@ -721,7 +788,7 @@ int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, d
     if (y64) hipLaunchKernelGGL(ng_z_kernel<double>, gz, dim3(256), 0, s, tb, rank, Z);
     else hipLaunchKernelGGL(ng_z_kernel<float>, gz, dim3(256), 0, s, tb, rank, Z);
     NG_LAUNCHED();
-    hipLaunchKernelGGL(ng_eig_kernel, dim3(tb.nslots * tb.batch), dim3(256), smem, s, tb, rank, n, eta, Z, Wt, bump);
+    hipLaunchKernelGGL(ng_eig_kernel, dim3(tb.nslots * tb.batch), dim3(kEigThreads), smem, s, tb, rank, n, eta, Z, Wt, bump);
     NG_LAUNCHED();
     const dim3 gr((unsigned)((maxdim + 3 + 31) / 32), tb.nslots, tb.batch);
     if (y64) hipLaunchKernelGGL(ng_newr_kernel<double>, gr, dim3(256), 0, s, tb, rank, Wt);
@@ -854,8 +921,16 @@ struct NgDnnLayout {
     // all layers at once: augmented inputs of every layer, then per-(slot, replica) H, H2, coefficients, partial
     // sums and gamma
     int64_t xaug_off[64 + 1], ld_in[64 + 1];
-    int64_t ldr, H_b, h_off, h2_off, coef_off, part_off, gamma_off;
+    int64_t ldr, H_b, h_off, h2_off, coef_off, part_off, gamma_off, hp_off;
 };
+// The thin products H = X R^T run as one launch of 32-row tiles; to occupy the whole chip the contraction of each
+// is cut into chunks of about 1024 (multiples of 16) whose partial products are summed afterwards.
+inline int ng_chunk_len(int dim) {
+    int nch = (dim + 512) / 1024;
+    if (nch < 1) nch = 1;
+    return (int)round_up((dim + nch - 1) / nch, 16);
+}
+inline int ng_chunk_count(int dim) { const int kc = ng_chunk_len(dim); return (dim + kc - 1) / kc; }
 NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     NgDnnLayout y;
     int64_t off = 0;
@@ -890,6 +965,9 @@ NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     y.coef_off = off;  off += q * 3 * kMaxRank;
     y.part_off = off;  off += q * 2 * 256;
     y.gamma_off = off; off += round_up(q, 64);
+    int64_t nprob = 0;
+    for (int l = 1; l <= L; ++l) nprob += ng_chunk_count(d[l - 1] + 1) + ng_chunk_count(d[l]);
+    y.hp_off = off;    off += nprob * k * y.H_b;
     y.total = off;
     return y;
 }
@@ -1021,21 +1099,40 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
             NG_LAUNCHED();
             return 0;
         };
+        float* P = ws + lay.hp_off;                      // partial products [problem][replica][n x ldr]
+        NgChunkTable ct;
         auto gemm_H = [&](float* Hout) -> int {          // Hout = X R^T for every slot
-            GemmDesc g[kNgSlots];
+            GemmDesc g[kThinMaxProblems];
+            int np = 0, pi = 0;                           // descriptors pending, problems so far
             for (int j = 0; j < t.nslots; ++j) {
-                GemmDesc& q = g[j];
-                q.M = n; q.N = rank; q.K = t.dim[j]; q.batch = k;
-                q.A = t.x[j]; q.lda = t.ldx[j]; q.a_bstride = t.x_b[j]; q.a_kc = true;
-                q.B = reinterpret_cast<const float*>(t.state[j]); q.ldb = round_up(t.dim[j], 4); q.b_bstride = t.st_b / 4; q.b_kc = true;
-                q.C = Hout + (int64_t)j * k * lay.H_b; q.ldc = lay.ldr; q.c_bstride = lay.H_b;
+                const int dim = t.dim[j], kc = ng_chunk_len(dim), nch = ng_chunk_count(dim);
+                ct.first[j] = pi; ct.count[j] = nch;
+                for (int c = 0; c < nch; ++c, ++pi) {
+                    GemmDesc& q = g[np];
+                    q = GemmDesc();
+                    q.M = n; q.N = rank; q.K = (c + 1 < nch) ? kc : dim - c * kc; q.batch = k;
+                    q.A = t.x[j] + (int64_t)c * kc; q.lda = t.ldx[j]; q.a_bstride = t.x_b[j]; q.a_kc = true;
+                    q.B = reinterpret_cast<const float*>(t.state[j]) + (int64_t)c * kc; q.ldb = round_up(dim, 4);
+                    q.b_bstride = t.st_b / 4; q.b_kc = true;
+                    q.C = P + (int64_t)pi * k * lay.H_b; q.ldc = lay.ldr; q.c_bstride = lay.H_b;
+                    if (++np == kThinMaxProblems) {
+                        NG_CHECK(gemm_launch_grouped(g, np, s, true));
+                        np = 0;
+                    }
+                }
             }
-            return gemm_launch_grouped(g, t.nslots, s, true);
+            if (np > 0) NG_CHECK(gemm_launch_grouped(g, np, s, true));
+            int64_t gx = ((int64_t)n * lay.ldr / 4 + 255) / 256;
+            if (gx > 64) gx = 64;
+            hipLaunchKernelGGL(ng_sum_chunks_slots_kernel, dim3((unsigned)gx, t.nslots, k), dim3(256), 0, s, t, ct, P, Hout);
+            NG_LAUNCHED();
+            return 0;
         };
         auto rank_update = [&](int use_h2, float sign) -> int {
-            const dim3 grid((unsigned)((maxdim + 255) / 256), (unsigned)((n + kRuRows - 1) / kRuRows), (unsigned)(t.nslots * k));
-            if (rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<32>, grid, dim3(256), 0, s, t, use_h2, sign);
-            else hipLaunchKernelGGL(ng_rank_update_slots_kernel<kMaxRank>, grid, dim3(256), 0, s, t, use_h2, sign);
+            constexpr int kRows = 128;                   // rows a wavefront walks with its block of R in registers
+            const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((n + kRows - 1) / kRows), (unsigned)(t.nslots * k));
+            if (rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<1>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
+            else hipLaunchKernelGGL(ng_rank_update_slots_kernel<2>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
             NG_LAUNCHED();
             return 0;
         };
