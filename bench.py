@@ -40,6 +40,8 @@ def main():
     ap.add_argument("--minibatch", type=int, default=256)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-extras", action="store_true", help="skip the averaging / CD-1 side measurements")
+    ap.add_argument("--extras", default="all",
+                    help="comma list of the side measurements to run: averaging, cd1, sweep, paper, ngsgd (default all)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="bound on the oracle leg")
     ap.add_argument("--no-warm", action="store_true",
                     help="skip the clock warm-up bursts (for hardware-counter runs, where every launch is serialised)")
@@ -153,7 +155,10 @@ def main():
               "step_mfma_frac": round(frames_per_s * flop_per_frame / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4),
               "flop_per_frame": flop_per_frame, "final_mean_loss": round(final_loss, 4)}
 
-    if not args.no_extras:
+    def want(name):
+        return not args.no_extras and (args.extras == "all" or name in args.extras.split(","))
+
+    if want("averaging"):
         # replica averaging: 8 replicas of the same network resident in HBM (2*K*P*4 bytes per call)
         Kr = 8
         reps_t = torch.randn(Kr, P, device="cuda") * 0.05
@@ -172,6 +177,7 @@ def main():
         log(f"averaging: {extras['averaging']}")
         del reps_t
 
+    if want("cd1"):
         # RBM CD-1 steps (10*n*V*H FLOP each): Gaussian 440 -> 2048, then Bernoulli 2048 -> 2048 with sampled visibles
         def cd1(V, H, vis, flags, lr_r, v0):
             w_, a_, c_ = [torch.from_numpy(t).cuda() for t in gen.rbm_params(V, H, seed, 0)]
@@ -194,6 +200,7 @@ def main():
         extras["cd1_bernoulli_2048x2048"] = cd1(2048, 2048, B.VIS_BERNOULLI, B.SAMPLE_V1, 0.4, torch.rand(n, 2048, device="cuda"))
         log(f"cd1: {extras['cd1_gaussian_440x2048']} {extras['cd1_bernoulli_2048x2048']}")
 
+    if not args.no_extras:
         # NG-SGD step against the plain SGD step at minibatch 512, rank 30 (one replica)
         def train_ms(nb, use_ng):
             xb = torch.from_numpy(gen.features_speech_like(nb, dims[0], seed, 1, 0)).cuda()
@@ -292,16 +299,18 @@ def main():
                                               "mfma_frac": round(Kr * nb / ms * 1e3 * pflop / 1e12 / PEAK_FP32_MFMA_TFLOPS, 4)}
                 del th, xb, yb, ac, wp
             return out
-        extras["averaging_sweep_8_replicas"] = sweep()
-        extras["paper_shape_440_6x2048_8806_mb1024"] = paper_shape()
-        log(f"paper shape: {extras['paper_shape_440_6x2048_8806_mb1024']}")
-        log(f"sweep: {extras['averaging_sweep_8_replicas']}")
-
-        sgd_ms, ng_ms = train_ms(512, False), train_ms(512, True)
-        extras["ngsgd_mb512_rank30"] = {"sgd_ms": round(sgd_ms, 4), "ngsgd_ms": round(ng_ms, 4),
-                                        "overhead": round(ng_ms / sgd_ms - 1.0, 4),
-                                        "ngsgd_frames/s": round(512 / ng_ms * 1e3, 1)}
-        log(f"ngsgd: {extras['ngsgd_mb512_rank30']}")
+        if want("sweep"):
+            extras["averaging_sweep_8_replicas"] = sweep()
+            log(f"sweep: {extras['averaging_sweep_8_replicas']}")
+        if want("paper"):
+            extras["paper_shape_440_6x2048_8806_mb1024"] = paper_shape()
+            log(f"paper shape: {extras['paper_shape_440_6x2048_8806_mb1024']}")
+        if want("ngsgd"):
+            sgd_ms, ng_ms = train_ms(512, False), train_ms(512, True)
+            extras["ngsgd_mb512_rank30"] = {"sgd_ms": round(sgd_ms, 4), "ngsgd_ms": round(ng_ms, 4),
+                                            "overhead": round(ng_ms / sgd_ms - 1.0, 4),
+                                            "ngsgd_frames/s": round(512 / ng_ms * 1e3, 1)}
+            log(f"ngsgd: {extras['ngsgd_mb512_rank30']}")
 
     cpu_baseline = None
     if not args.no_cpu:
