@@ -12,6 +12,8 @@
 // leaves the small remainder with a large relative error.
 // The N x D and R x D work runs in float32 on the MFMA GEMM; the R x R work (Z, its Jacobi eigen-decomposition,
 // d, rho) runs in float64 in one workgroup.  Every kernel takes a batch index (one state per replica).
+// Two drivers: ng_run preconditions one matrix, a launch per step of the recipe; ng_dnn_update takes all layer
+// sides of a backward pass through each step in one launch (kernels named *_slots_kernel).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
