@@ -176,6 +176,31 @@ def test_ng_training_step_tiny_two_replicas():
             check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, ref[k][2][l - 1], tol=5e-3)
 
 
+def test_ng_training_step_mixed_widths_rank_above_32():
+    # Layer sides of very different widths in the same launches: 1601 (its thin product cut into two chunks of the
+    # contraction), 91 / 200 / 201 / 1600 (one chunk, ragged tails), 48 (too short for the in-workgroup split: launched
+    # by itself); rank 36 takes the two-half path of the rank update and 64-lane groups in the eigen-solver;
+    # 96 rows = 3 row tiles; two replicas.
+    dims, K, T, n, lr, rank, eta, seed = [90, 200, 1600, 48], 2, 3, 96, 0.05, 36, 0.2, 9
+    theta0 = gen.init_theta(dims, seed, 0.1)
+    shards = [[(gen.features_iid(n, dims[0], seed, k, t), gen.labels_uniform(n, dims[-1], seed, k, t)) for t in range(T)]
+              for k in range(K)]
+    ref = _oracle_ng_run(dims, theta0, shards, lr, rank, eta)
+    g = NgGpu(dims, K, n, theta0, rank)
+    for t in range(T):
+        g.step(np.stack([shards[k][t][0] for k in range(K)]), np.stack([shards[k][t][1] for k in range(K)]), lr, eta)
+        th = g.params()
+        for k in range(K):
+            prev = theta0.astype(np.float64) if t == 0 else ref[k][0][t - 1]
+            assert rel_err(th[k] - prev, ref[k][0][t] - prev) < 5e-4, (t, k)
+            assert rel_err(th[k], ref[k][0][t]) < 1e-5
+    L = len(dims) - 1
+    for k in range(K):
+        for l in range(1, L + 1):
+            check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, ref[k][1][l - 1], tol=5e-3)
+            check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, ref[k][2][l - 1], tol=5e-3)
+
+
 def test_config5_ng_full_size_two_steps():
     # 440-6x2048-8000, minibatch 512, rank 30, one replica, two minibatches
     dims, n, lr, rank, seed = gen.CONFIG_FULL_DIMS, 512, 0.008, 30, 41
