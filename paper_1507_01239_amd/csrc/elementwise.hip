@@ -148,23 +148,26 @@ __global__ __launch_bounds__(kThreads) void colsum_axpby_kernel(const float* __r
         const float* __restrict__ x = X + (int64_t)b * x_bstride + j;
         const float* __restrict__ y = Y ? Y + (int64_t)b * y_bstride + j : nullptr;
         const float* __restrict__ w = ex.roww ? ex.roww + (int64_t)b * ex.roww_bstride : nullptr;
-        // eight rows per trip: their loads are issued together, the additions keep the row order
+        // sixteen (then eight) rows per trip: their loads are issued together, the additions keep the row order
         int n = ty;
-        for (; n + 56 < rows; n += 64) {
-            float v[8];
+        auto trip = [&](auto nc) {
+            constexpr int NQ = decltype(nc)::value;
+            float v[NQ];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) v[q] = x[(int64_t)(n + 8 * q) * ldx];
+            for (int q = 0; q < NQ; ++q) v[q] = x[(int64_t)(n + 8 * q) * ldx];
             if (y) {
 #pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] -= y[(int64_t)(n + 8 * q) * ldy];
+                for (int q = 0; q < NQ; ++q) v[q] -= y[(int64_t)(n + 8 * q) * ldy];
             }
             if (w) {
 #pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] *= w[(int64_t)(n + 8 * q) * ex.roww_ld];
+                for (int q = 0; q < NQ; ++q) v[q] *= w[(int64_t)(n + 8 * q) * ex.roww_ld];
             }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) s += v[q];
-        }
+            for (int q = 0; q < NQ; ++q) s += v[q];
+        };
+        for (; n + 120 < rows; n += 128) trip(std::integral_constant<int, 16>{});
+        for (; n + 56 < rows; n += 64) trip(std::integral_constant<int, 8>{});
         for (; n < rows; n += 8) {
             float v = x[(int64_t)n * ldx];
             if (y) v -= y[(int64_t)n * ldy];

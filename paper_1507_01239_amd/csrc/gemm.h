@@ -39,7 +39,9 @@ struct Epilogue {
     int lastcol = -1; float* lastcol_dst = nullptr; int64_t lastcol_bstride = 0;
     // optional, only for an m-contiguous A operand (forces an unsplit contraction):
     //   rowsum_dst[b][m] = rowsum_beta * rowsum_dst[b][m] + rowsum_alpha * sum_k A(m,k)
+    //   if rowsum_dst2: rowsum_dst2[b][m] += rowsum_dst[b][m]   (a bias next to its momentum vector)
     float* rowsum_dst = nullptr; int64_t rowsum_bstride = 0; float rowsum_alpha = 1.f, rowsum_beta = 0.f;
+    float* rowsum_dst2 = nullptr; int64_t rowsum2_bstride = 0;
     uint32_t key0 = 0, key1 = 0, step = 0, layer = 0, phase = 0;   // Philox stream of the sampling epilogue
 };
 

@@ -390,6 +390,7 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
         float r = p.epi.rowsum_alpha * rowsum;
         if (p.epi.rowsum_beta != 0.f) r += p.epi.rowsum_beta * *d;
         *d = r;
+        if (p.epi.rowsum_dst2) p.epi.rowsum_dst2[(int64_t)b * p.epi.rowsum2_bstride + m0 + tid] += r;
     }
     if (p.splits > 1) {
         // split contraction: store the partial tile; gemm_reduce_kernel adds the partials in split order
@@ -665,6 +666,7 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         float r = p.epi.rowsum_alpha * rowsum;
         if (p.epi.rowsum_beta != 0.f) r += p.epi.rowsum_beta * *d;
         *d = r;
+        if (p.epi.rowsum_dst2) p.epi.rowsum_dst2[(int64_t)b * p.epi.rowsum2_bstride + m0 + tid] += r;
     }
     if (p.splits > 1) {
         Epilogue raw;

@@ -142,6 +142,8 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
         g.B = v0; g.ldb = V; g.b_kc = false;
         g.C = mw; g.ldc = V;
         g.epi.kind = EPI_AXPBY; g.epi.alpha = lr * invn; g.epi.beta = momentum;
+        // Mc <- momentum Mc + (lr/n) colsum(P_h0): the row sums of this product's first operand (P_h0^T)
+        g.epi.rowsum_dst = mc; g.epi.rowsum_alpha = lr * invn; g.epi.rowsum_beta = momentum;
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
     {   // MW <- MW - (lr/n) P_h1^T V1 ;  W <- W + MW
@@ -152,10 +154,12 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
         g.C = mw; g.ldc = V;
         g.epi.kind = EPI_AXPBY; g.epi.alpha = -lr * invn; g.epi.beta = 1.f;
         g.epi.C2 = w; g.epi.ldc2 = V;
+        // Mc <- Mc - (lr/n) colsum(P_h1) ;  c <- c + Mc
+        g.epi.rowsum_dst = mc; g.epi.rowsum_alpha = -lr * invn; g.epi.rowsum_beta = 1.f;
+        g.epi.rowsum_dst2 = c;
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
-    // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma      (and the same for c with P_h0 - P_h1)
+    // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma
     if (colsum_axpby_launch(v0, V, 0, v1, lay.ldv, 0, ma, 0, a, 0, n, V, 1, lr * invn, momentum, s) != 0) return MAVG_E_LAUNCH;
-    if (colsum_axpby_launch(ph0, lay.ldh, 0, ph1, lay.ldh, 0, mc, 0, c, 0, n, H, 1, lr * invn, momentum, s) != 0) return MAVG_E_LAUNCH;
     return MAVG_OK;
 }
