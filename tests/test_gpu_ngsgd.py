@@ -50,7 +50,8 @@ def _data(n, dim, seed, t, lowrank=8):
     return (rng.standard_normal((n, dim)) * scales[None, :] * 0.3 + rng.standard_normal((n, lowrank)) @ mix).astype(np.float32)
 
 
-@pytest.mark.parametrize("n,dim,rank", [(37, 45, 5), (64, 130, 30), (100, 51, 7), (512, 441, 30), (512, 2049, 30), (512, 8000, 30)])
+@pytest.mark.parametrize("n,dim,rank", [(37, 45, 5), (64, 130, 30), (100, 51, 7), (512, 441, 30), (512, 2049, 30), (512, 8000, 30),
+                                        (96, 150, 33), (128, 200, 64)])    # odd rank above 32; the largest rank
 def test_precondition_sequence_matches_oracle(n, dim, rank):
     import torch
     from paper_1507_01239_amd import binding as B
