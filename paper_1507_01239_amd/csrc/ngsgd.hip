@@ -12,8 +12,8 @@
 // leaves the small remainder with a large relative error.
 // The N x D and R x D work runs in float32 on the MFMA GEMM; the R x R work (Z, its Jacobi eigen-decomposition,
 // d, rho) runs in float64 in one workgroup.  Every kernel takes a batch index (one state per replica).
-// Two drivers: ng_run preconditions one matrix, a launch per step of the recipe; ng_dnn_update takes all layer
-// sides of a backward pass through each step in one launch (kernels named *_slots_kernel).
+// Every step of the apply is a kernel over a table of matrices (*_slots_kernel): ng_dnn_update takes all layer
+// sides of a backward pass through each step in one launch, ng_run is the same recipe for a table of one.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -45,12 +45,22 @@ __host__ __device__ inline StateView state_view(char* st, int dim, int rank) {
     return v;
 }
 
+// The thin products H = X R^T run as one launch of 32-row tiles; to occupy the whole chip the contraction of each
+// is cut into chunks of about 1024 (multiples of 16) whose partial products are summed afterwards.
+inline int ng_chunk_len(int dim) {
+    int nch = (dim + 512) / 1024;
+    if (nch < 1) nch = 1;
+    return (int)round_up((dim + nch - 1) / nch, 16);
+}
+inline int ng_chunk_count(int dim) { const int kc = ng_chunk_len(dim); return (dim + kc - 1) / kc; }
+
 // scratch carve-up (offsets in floats from a 256-byte aligned base)
 struct NgWs {
     int64_t ldr, ld;
     int64_t off_H, off_H2, H_b, off_Y, RY_b, off_coef, coef_b, off_gamma;
     int64_t off_scal, off_part, off_Z, off_Wt;       // float64 regions (offsets still in floats)
     int64_t off_H64, H64_b, off_Y64, Y64_b;          // float64 copies used by the initial folds
+    int64_t off_P;                                   // partial products of the chunked thin GEMM
     int64_t off_gemm, gemm_floats, total;
 };
 
@@ -61,10 +71,7 @@ NgWs ng_ws(int dim, int rank, int n, int batch) {
     w.H_b = round_up((int64_t)n * w.ldr, 64);
     w.RY_b = round_up((int64_t)rank * w.ld, 64);
     w.coef_b = 3 * kMaxRank;
-    int64_t g = gemm_ws_floats(n, rank, dim, batch), f;
-    f = gemm_ws_floats(rank, dim, n, batch); if (f > g) g = f;
-    f = gemm_ws_floats(n, dim, rank, batch, -1, 1); if (f > g) g = f;
-    w.gemm_floats = round_up(g, 64);
+    w.gemm_floats = round_up(gemm_ws_floats(rank, dim, n, batch), 64);       // Y = H^T X
     int64_t off = 0;
     w.off_H = off;     off += w.H_b * batch;
     w.off_H2 = off;    off += w.H_b * batch;
@@ -79,6 +86,7 @@ NgWs ng_ws(int dim, int rank, int n, int batch) {
     w.Y64_b = 2 * round_up((int64_t)rank * w.ld, 64);
     w.off_H64 = off;   off += w.H64_b * batch;
     w.off_Y64 = off;   off += w.Y64_b * batch;
+    w.off_P = off;     off += (int64_t)ng_chunk_count(dim) * batch * w.H_b;
     w.off_gemm = off;  off += w.gemm_floats;
     w.total = off;
     return w;
@@ -129,124 +137,6 @@ __global__ __launch_bounds__(256) void ng_init_kernel(char* state, int dim, int 
     if (blockIdx.x == 0) {
         if (threadIdx.x < rank) v.d[threadIdx.x] = kEps;
         if (threadIdx.x == 0) { *v.rho = kEps; *v.t = 0; }
-    }
-}
-
-// coef[b] = [ e_i | (1-eta)(d_i+rho) | 1 - e_i ]
-__global__ __launch_bounds__(64) void ng_coeff_kernel(char* state, int64_t st_b, int dim, int rank, float alpha, float eta,
-                                                      float* coef, int64_t coef_b) {
-    const int b = blockIdx.x;
-    const StateView v = state_view(state + (int64_t)b * st_b, dim, rank);
-    double sumd = 0.0;
-    for (int j = 0; j < rank; ++j) sumd += v.d[j];
-    const double rho = *v.rho;
-    const double beta = rho * (1.0 + (double)alpha) + (double)alpha * sumd / (double)dim;
-    if (threadIdx.x < rank) {
-        const double di = v.d[threadIdx.x];
-        coef[(int64_t)b * coef_b + threadIdx.x] = (float)(di / (di + beta));
-        coef[(int64_t)b * coef_b + kMaxRank + threadIdx.x] = (float)((1.0 - (double)eta) * (di + rho));
-        coef[(int64_t)b * coef_b + 2 * kMaxRank + threadIdx.x] = (float)(beta / (di + beta));
-    }
-}
-
-// H2 <- H (I - E) - H2   (n x rank, row stride ldr)
-__global__ __launch_bounds__(256) void ng_combine_kernel(const float* __restrict__ H, float* __restrict__ H2, int64_t h_b, int64_t ldr,
-                                                         int n, int rank, const float* __restrict__ coef, int64_t coef_b) {
-    const int b = blockIdx.y;
-    const float* __restrict__ ome = coef + (int64_t)b * coef_b + 2 * kMaxRank;
-    const int64_t total = (int64_t)n * ldr;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int i = (int)(e % ldr);
-        if (i < rank) H2[(int64_t)b * h_b + e] = H[(int64_t)b * h_b + e] * ome[i] - H2[(int64_t)b * h_b + e];
-    }
-}
-
-// partial sums of squares of an n x dim matrix: part[b][blockIdx.x]
-__global__ __launch_bounds__(256) void ng_sumsq_partial_kernel(const float* __restrict__ x, int64_t ldx, int64_t x_b, int n, int dim,
-                                                               double* __restrict__ part) {
-    __shared__ double sh[4];
-    const int b = blockIdx.y;
-    const float* __restrict__ xb = x + (int64_t)b * x_b;
-    double s = 0.0;
-    const bool vec = (ldx & 3) == 0 && (x_b & 3) == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0;
-    for (int r = blockIdx.x; r < n; r += gridDim.x) {
-        const float* __restrict__ row = xb + (int64_t)r * ldx;
-        float a = 0.f;
-        if (vec) {      // 16-byte loads, four in flight per thread; the tail of the row one element at a time
-            const int nq = dim >> 2;
-            int q = threadIdx.x;
-            for (; q + 768 < nq; q += 1024) {
-                const float4 v0 = *reinterpret_cast<const float4*>(row + 4 * q);
-                const float4 v1 = *reinterpret_cast<const float4*>(row + 4 * (q + 256));
-                const float4 v2 = *reinterpret_cast<const float4*>(row + 4 * (q + 512));
-                const float4 v3 = *reinterpret_cast<const float4*>(row + 4 * (q + 768));
-                a += (v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w);
-                a += (v1.x * v1.x + v1.y * v1.y) + (v1.z * v1.z + v1.w * v1.w);
-                a += (v2.x * v2.x + v2.y * v2.y) + (v2.z * v2.z + v2.w * v2.w);
-                a += (v3.x * v3.x + v3.y * v3.y) + (v3.z * v3.z + v3.w * v3.w);
-            }
-            for (; q < nq; q += 256) {
-                const float4 v0 = *reinterpret_cast<const float4*>(row + 4 * q);
-                a += (v0.x * v0.x + v0.y * v0.y) + (v0.z * v0.z + v0.w * v0.w);
-            }
-            for (int c = 4 * nq + threadIdx.x; c < dim; c += 256) { const float e = row[c]; a += e * e; }
-        } else {
-            for (int c = threadIdx.x; c < dim; c += 256) { const float e = row[c]; a += e * e; }
-        }
-        s += (double)a;
-    }
-    s = block_sum_d(s, sh);
-    if (threadIdx.x == 0) part[(int64_t)b * 256 + blockIdx.x] = s;
-}
-
-// scal[b][which] = sum of the 256 partials; which == 1 also sets gamma[b] = sqrt(scal[0]/scal[1]) (1 if either is 0)
-__global__ __launch_bounds__(256) void ng_sumsq_final_kernel(const double* __restrict__ part, double* __restrict__ scal, int which,
-                                                             float* __restrict__ gamma) {
-    __shared__ double sh[4];
-    const int b = blockIdx.x;
-    double s = part[(int64_t)b * 256 + threadIdx.x];
-    s = block_sum_d(s, sh);
-    if (threadIdx.x == 0) {
-        scal[b * 2 + which] = s;
-        if (which == 1) {
-            const double nx = scal[b * 2 + 0];
-            gamma[b] = (nx > 0.0 && s > 0.0) ? (float)sqrt(nx / s) : 1.f;
-        }
-    }
-}
-
-// X <- X + sign * Cm R  for a thin Cm (n x rank) and R (rank x dim): a rank-`rank` update of an n x dim matrix,
-// bound by reading and writing X.  One thread per column keeps that column of R in registers and walks 16 rows;
-// the 16 x rank block of Cm sits in LDS.  (As an MFMA GEMM with a contraction of 30 it took 10 us per call.)
-constexpr int kRuRows = 16;
-template <int RANK_MAX>
-__global__ __launch_bounds__(256) void ng_rank_update_kernel(float* __restrict__ x, int64_t ldx, int64_t x_b,
-                                                             const float* __restrict__ cm, int64_t ldc, int64_t c_b,
-                                                             const float* __restrict__ r, int64_t ldr, int64_t r_b,
-                                                             int n, int dim, int rank, float sign) {
-    __shared__ float cs[kRuRows][RANK_MAX];
-    const int b = blockIdx.z, col = blockIdx.x * 256 + threadIdx.x, row0 = blockIdx.y * kRuRows;
-    const float* __restrict__ cb = cm + (int64_t)b * c_b;
-    for (int i = threadIdx.x; i < kRuRows * RANK_MAX; i += 256) {       // zero beyond `rank` and beyond the last row
-        const int rr = i / RANK_MAX, k = i - rr * RANK_MAX;
-        cs[rr][k] = (k < rank && row0 + rr < n) ? cb[(int64_t)(row0 + rr) * ldc + k] : 0.f;
-    }
-    __syncthreads();
-    if (col >= dim) return;
-    float rc[RANK_MAX];
-    const float* __restrict__ rb = r + (int64_t)b * r_b + col;
-#pragma unroll
-    for (int k = 0; k < RANK_MAX; ++k) rc[k] = k < rank ? rb[(int64_t)k * ldr] : 0.f;
-    float* __restrict__ xb = x + (int64_t)b * x_b + col;
-    float old[kRuRows];
-#pragma unroll
-    for (int rr = 0; rr < kRuRows; ++rr) old[rr] = row0 + rr < n ? xb[(int64_t)(row0 + rr) * ldx] : 0.f;
-#pragma unroll
-    for (int rr = 0; rr < kRuRows; ++rr) {
-        float acc = 0.f;
-#pragma unroll
-        for (int k = 0; k < RANK_MAX; ++k) acc += cs[rr][k] * rc[k];       // both factors are 0 beyond `rank`
-        if (row0 + rr < n) xb[(int64_t)(row0 + rr) * ldx] = old[rr] + sign * acc;
     }
 }
 
@@ -519,28 +409,15 @@ __global__ __launch_bounds__(256) void ng_y64_kernel(char* state, int64_t st_b, 
     }
 }
 
-// Xaug[b](r, 0..d) = A[b](r, :), Xaug[b](r, d) = 1, padding columns 0
-__global__ __launch_bounds__(256) void ng_augment_kernel(const float* __restrict__ A, int64_t lda, int64_t a_b, int n, int d,
-                                                         float* __restrict__ X, int64_t ldx, int64_t x_b) {
-    const int b = blockIdx.y;
-    const int64_t total = (int64_t)n * ldx;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int64_t r = e / ldx, c = e - r * ldx;
-        float v = 0.f;
-        if (c < d) v = A[(int64_t)b * a_b + r * lda + c];
-        else if (c == d) v = 1.f;
-        X[(int64_t)b * x_b + e] = v;
-    }
-}
 
-
-// ---- every layer side of a backward pass at once ---------------------------------------------------
+// ---- the steps of the apply, for a table of matrices ------------------------------------------------
 //
 // Between the end of the back-propagation chain and the weight updates the 2 L preconditioned matrices of a
 // network (input and output side of every layer) are independent of each other.  One preconditioning is a dozen
 // small launches, each a few microseconds of mostly latency; the kernels below take a table of slots (one slot =
 // one matrix, times `batch` replicas) so that a whole backward pass needs one launch per step of the recipe
-// instead of one per step and matrix.  Same arithmetic per element as the single-matrix kernels above.
+// instead of one per step and matrix.  A single matrix (ngsgd_precondition, the first minibatch of a network) is
+// a table of one slot.
 struct NgSlots {
     char* state[kNgSlots];          // state of (slot, replica 0); replica b at + b * st_b bytes
     float* x[kNgSlots];             // matrix of (slot, replica 0), n x dim, preconditioned in place
@@ -799,64 +676,98 @@ int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, d
     return 0;
 }
 
+// Host side of the steps of the apply for a table of slots.
+int ng_slots_norms(const NgSlots& t, int which, float alpha, float eta, hipStream_t s) {
+    hipLaunchKernelGGL(ng_sumsq_partial_slots_kernel, dim3(256, t.nslots, t.batch), dim3(256), 0, s, t);
+    NG_LAUNCHED();
+    hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, which, alpha, eta);
+    NG_LAUNCHED();
+    return 0;
+}
+
+// Hout = X R^T for every slot: one launch over the chunks of all contractions (P: [chunk][replica][n x ldr]
+// partial products), then their sums
+int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s) {
+    GemmDesc g[kThinMaxProblems];
+    NgChunkTable ct;
+    int np = 0, pi = 0;                               // descriptors pending, problems so far
+    for (int j = 0; j < t.nslots; ++j) {
+        const int dim = t.dim[j], kc = ng_chunk_len(dim), nch = ng_chunk_count(dim);
+        ct.first[j] = pi; ct.count[j] = nch;
+        for (int c = 0; c < nch; ++c, ++pi) {
+            GemmDesc& q = g[np];
+            q = GemmDesc();
+            q.M = t.n; q.N = t.rank; q.K = (c + 1 < nch) ? kc : dim - c * kc; q.batch = t.batch;
+            q.A = t.x[j] + (int64_t)c * kc; q.lda = t.ldx[j]; q.a_bstride = t.x_b[j]; q.a_kc = true;
+            q.B = reinterpret_cast<const float*>(t.state[j]) + (int64_t)c * kc; q.ldb = round_up(dim, 4);
+            q.b_bstride = t.st_b / 4; q.b_kc = true;
+            q.C = P + (int64_t)pi * t.batch * t.H_b; q.ldc = t.ldr; q.c_bstride = t.H_b;
+            if (++np == kThinMaxProblems) {
+                NG_CHECK(gemm_launch_grouped(g, np, s, true));
+                np = 0;
+            }
+        }
+    }
+    if (np > 0) NG_CHECK(gemm_launch_grouped(g, np, s, true));
+    int64_t gx = ((int64_t)t.n * t.ldr / 4 + 255) / 256;
+    if (gx > 64) gx = 64;
+    hipLaunchKernelGGL(ng_sum_chunks_slots_kernel, dim3((unsigned)gx, t.nslots, t.batch), dim3(256), 0, s, t, ct, P, Hout);
+    NG_LAUNCHED();
+    return 0;
+}
+
+// X <- X + sign * (H or H2) R for every slot
+int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s) {
+    constexpr int kRows = 128;                       // rows a wavefront walks with its block of R in registers
+    int maxdim = 0;
+    for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
+    const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((t.n + kRows - 1) / kRows), (unsigned)(t.nslots * t.batch));
+    if (t.rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<1>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
+    else hipLaunchKernelGGL(ng_rank_update_slots_kernel<2>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
+    NG_LAUNCHED();
+    return 0;
+}
+
+int ng_slots_combine(const NgSlots& t, hipStream_t s) {
+    int64_t gx = ((int64_t)t.n * t.ldr + 255) / 256;
+    if (gx > 1024) gx = 1024;
+    hipLaunchKernelGGL(ng_combine_slots_kernel, dim3((unsigned)gx, t.nslots, t.batch), dim3(256), 0, s, t);
+    NG_LAUNCHED();
+    return 0;
+}
+
 int ng_run(const NgCall& c, hipStream_t s) {
     const NgWs w = ng_ws(c.dim, c.rank, c.n, c.batch);
-    float* H = c.ws + w.off_H;
-    float* H2 = c.ws + w.off_H2;
     float* Y = c.defer_Y ? c.defer_Y : c.ws + w.off_Y;
-    float* coef = c.ws + w.off_coef;
-    float* gamma = c.gamma;
     double* scal = c.defer_scal ? c.defer_scal : reinterpret_cast<double*>(c.ws + w.off_scal);
-    double* part = reinterpret_cast<double*>(c.ws + w.off_part);
     double* Z = reinterpret_cast<double*>(c.ws + w.off_Z);
     double* Wt = reinterpret_cast<double*>(c.ws + w.off_Wt);
     double* H64 = reinterpret_cast<double*>(c.ws + w.off_H64);
     double* Y64 = reinterpret_cast<double*>(c.ws + w.off_Y64);
     float* gws = c.ws + w.off_gemm;
+    float* P = c.ws + w.off_P;
     const float* Rm = reinterpret_cast<const float*>(c.state);
     const int64_t st_bf = c.st_b / 4;
-    auto sumsq = [&](int which) -> int {
-        hipLaunchKernelGGL(ng_sumsq_partial_kernel, dim3(256, c.batch), dim3(256), 0, s, c.x, c.ldx, c.x_b, c.n, c.dim, part);
-        NG_LAUNCHED();
-        hipLaunchKernelGGL(ng_sumsq_final_kernel, dim3(c.batch), dim3(256), 0, s, part, scal, which, gamma);
-        NG_LAUNCHED();
-        return 0;
-    };
-    auto coeff = [&]() -> int {
-        hipLaunchKernelGGL(ng_coeff_kernel, dim3(c.batch), dim3(64), 0, s, c.state, c.st_b, c.dim, c.rank, c.alpha, c.eta, coef,
-                           w.coef_b);
-        NG_LAUNCHED();
-        return 0;
-    };
-    auto gemm_H = [&](float* Hout) -> int {         // Hout = X R^T
-        GemmDesc g;
-        g.M = c.n; g.N = c.rank; g.K = c.dim; g.batch = c.batch;
-        g.A = c.x; g.lda = c.ldx; g.a_bstride = c.x_b; g.a_kc = true;
-        g.B = Rm; g.ldb = w.ld; g.b_bstride = st_bf; g.b_kc = true;
-        g.C = Hout; g.ldc = w.ldr; g.c_bstride = w.H_b;
-        return gemm_launch(g, gws, w.gemm_floats, s);
-    };
+    NgSlots t;                                       // a table of one slot
+    t.state[0] = c.state; t.x[0] = c.x; t.ldx[0] = c.ldx; t.x_b[0] = c.x_b; t.dim[0] = c.dim;
+    t.st_b = c.st_b; t.nslots = 1; t.batch = c.batch; t.n = c.n; t.rank = c.rank;
+    t.H = c.ws + w.off_H; t.H2 = c.ws + w.off_H2; t.ldr = w.ldr; t.H_b = w.H_b;
+    t.coef = c.ws + w.off_coef;
+    t.part = reinterpret_cast<double*>(c.ws + w.off_part);
+    t.scal = scal;
+    t.gamma = c.gamma;
     auto gemm_Y = [&]() -> int {         // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R
         GemmDesc g;
         g.M = c.rank; g.N = c.dim; g.K = c.n; g.batch = c.batch;
-        g.A = H; g.lda = w.ldr; g.a_bstride = w.H_b; g.a_kc = false;
+        g.A = t.H; g.lda = w.ldr; g.a_bstride = w.H_b; g.a_kc = false;
+        g.a_pad4 = true;                 // rows of H are ldr = round_up(rank, 4) floats long
         g.B = c.x; g.ldb = c.ldx; g.b_bstride = c.x_b; g.b_kc = false;
+        g.b_pad4 = c.ldx >= w.ld;
         g.C = Y; g.ldc = w.ld; g.c_bstride = w.RY_b;
         g.epi.kind = EPI_ROWSCALE_ADD; g.epi.alpha = c.eta / (float)c.n;
-        g.epi.rowvec = coef + kMaxRank; g.epi.rowvec_bstride = w.coef_b;
+        g.epi.rowvec = t.coef + kMaxRank; g.epi.rowvec_bstride = w.coef_b;
         g.epi.aux = Rm; g.epi.ldaux = w.ld; g.epi.aux_bstride = st_bf;
         return gemm_launch(g, gws, w.gemm_floats, s);
-    };
-    auto gemm_XR = [&](const float* coefmat, float sign) -> int {     // X <- X + sign * coefmat R
-        const dim3 grid((unsigned)((c.dim + 255) / 256), (unsigned)((c.n + kRuRows - 1) / kRuRows), (unsigned)c.batch);
-        if (c.rank <= 32)
-            hipLaunchKernelGGL(ng_rank_update_kernel<32>, grid, dim3(256), 0, s, c.x, c.ldx, c.x_b, coefmat, (int64_t)w.ldr, w.H_b,
-                               Rm, (int64_t)w.ld, st_bf, c.n, c.dim, c.rank, sign);
-        else
-            hipLaunchKernelGGL(ng_rank_update_kernel<kMaxRank>, grid, dim3(256), 0, s, c.x, c.ldx, c.x_b, coefmat, (int64_t)w.ldr, w.H_b,
-                               Rm, (int64_t)w.ld, st_bf, c.n, c.dim, c.rank, sign);
-        NG_LAUNCHED();
-        return 0;
     };
     auto finish_fold = [&](int bump, bool y64) -> int {     // from Y: Z, eigen-decomposition, new state
         NgFoldTable tb;
@@ -866,7 +777,7 @@ int ng_run(const NgCall& c, hipStream_t s) {
         tb.nslots = 1; tb.batch = c.batch; tb.first = 0;
         return ng_finish(tb, c.rank, c.n, c.eta, y64, Z, Wt, bump, s);
     };
-    NG_CHECK(sumsq(0));
+    NG_CHECK(ng_slots_norms(t, 0, c.alpha, c.eta, s));              // ||X||^2 and the coefficients of the state
     if (c.mode == 2) {
         for (int f = 0; f < kInitFolds; ++f) {      // in float64: see ng_h64_kernel
             hipLaunchKernelGGL(ng_h64_kernel, dim3(c.n, c.batch), dim3(256), 0, s, c.state, c.st_b, c.dim, c.rank, c.x, c.ldx, c.x_b,
@@ -877,25 +788,21 @@ int ng_run(const NgCall& c, hipStream_t s) {
             NG_LAUNCHED();
             NG_CHECK(finish_fold(0, true));
         }
-    }
-    NG_CHECK(coeff());
-    NG_CHECK(gemm_H(H));
-    if (c.mode >= 1) NG_CHECK(gemm_Y());
-    NG_CHECK(gemm_XR(H, -1.f));                 // X1 = X - H R
-    NG_CHECK(gemm_H(H2));                       // H2 = X1 R^T  (what the first pass left inside the subspace)
-    {
-        int64_t gx = ((int64_t)c.n * w.ldr + 255) / 256;
-        if (gx > 1024) gx = 1024;
-        hipLaunchKernelGGL(ng_combine_kernel, dim3((unsigned)gx, c.batch), dim3(256), 0, s, H, H2, w.H_b, w.ldr, c.n, c.rank, coef,
-                           w.coef_b);
+        // the coefficients again, from the folded state (the partial sums of ||X||^2 are still in place)
+        hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(1, c.batch), dim3(256), 0, s, t, 0, c.alpha, c.eta);
         NG_LAUNCHED();
     }
-    NG_CHECK(gemm_XR(H2, 1.f));                 // Xh = X1 + (H (I - E) - H2) R
-    NG_CHECK(sumsq(1));
+    NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
+    if (c.mode >= 1) NG_CHECK(gemm_Y());
+    NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s));      // X1 = X - H R
+    NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s));           // H2 = X1 R^T  (what the first pass left inside the subspace)
+    NG_CHECK(ng_slots_combine(t, s));
+    NG_CHECK(ng_slots_rank_update(t, 1, 1.f, s));       // Xh = X1 + (H (I - E) - H2) R
+    NG_CHECK(ng_slots_norms(t, 1, c.alpha, c.eta, s));  // ||Xh||^2, gamma
     if (c.scale) {
         int64_t gx = ((int64_t)c.n * c.dim + 255) / 256;
         if (gx > 2048) gx = 2048;
-        hipLaunchKernelGGL(ng_scale_kernel, dim3((unsigned)gx, c.batch), dim3(256), 0, s, c.x, c.ldx, c.x_b, c.n, c.dim, gamma);
+        hipLaunchKernelGGL(ng_scale_kernel, dim3((unsigned)gx, c.batch), dim3(256), 0, s, c.x, c.ldx, c.x_b, c.n, c.dim, c.gamma);
         NG_LAUNCHED();
     }
     if (c.mode >= 1 && !c.defer_Y) NG_CHECK(finish_fold(1, false));
@@ -925,14 +832,6 @@ struct NgDnnLayout {
     int64_t xaug_off[64 + 1], ld_in[64 + 1];
     int64_t ldr, H_b, h_off, h2_off, coef_off, part_off, gamma_off, hp_off;
 };
-// The thin products H = X R^T run as one launch of 32-row tiles; to occupy the whole chip the contraction of each
-// is cut into chunks of about 1024 (multiples of 16) whose partial products are summed afterwards.
-inline int ng_chunk_len(int dim) {
-    int nch = (dim + 512) / 1024;
-    if (nch < 1) nch = 1;
-    return (int)round_up((dim + nch - 1) / nch, 16);
-}
-inline int ng_chunk_count(int dim) { const int kc = ng_chunk_len(dim); return (dim + kc - 1) / kc; }
 NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     NgDnnLayout y;
     int64_t off = 0;
@@ -1016,8 +915,10 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
     {
         int64_t gx = (aug_b + 255) / 256;
         if (gx > 2048) gx = 2048;
-        hipLaunchKernelGGL(ng_augment_kernel, dim3((unsigned)gx, a.k), dim3(256), 0, s, a.A_in, a.a_ld, a.a_bstride, a.n, a.d_in,
-                           Xaug, ld_in, aug_b);
+        NgAugTable au;
+        au.A[0] = a.A_in; au.lda[0] = a.a_ld; au.a_b[0] = a.a_bstride; au.d[0] = a.d_in;
+        au.X[0] = Xaug; au.ldx[0] = ld_in; au.x_b[0] = aug_b; au.n = a.n;
+        hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, 1, a.k), dim3(256), 0, s, au);
         NG_LAUNCHED();
     }
     NgCall c;
@@ -1071,7 +972,6 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
         t.scal = scal + (int64_t)j0 * k * 2;
         t.gamma = ws + lay.gamma_off + (int64_t)j0 * k;
         au.n = n;
-        int maxdim = 0;
         int64_t max_aug = 0;
         for (int i = 0; i < nl; ++i) {
             const NgLayerArgs& a = layers[l0 + i];
@@ -1085,8 +985,6 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
             t.dim[2 * i] = a.d_in + 1;
             t.state[2 * i + 1] = a.state_out; t.x[2 * i + 1] = a.delta; t.ldx[2 * i + 1] = a.ldd; t.x_b[2 * i + 1] = a.d_bstride;
             t.dim[2 * i + 1] = a.d_out;
-            if (a.d_in + 1 > maxdim) maxdim = a.d_in + 1;
-            if (a.d_out > maxdim) maxdim = a.d_out;
         }
         {
             int64_t gx = (max_aug + 255) / 256;
@@ -1094,52 +992,9 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
             hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, nl, k), dim3(256), 0, s, au);
             NG_LAUNCHED();
         }
-        auto sumsq = [&](int which) -> int {
-            hipLaunchKernelGGL(ng_sumsq_partial_slots_kernel, dim3(256, t.nslots, k), dim3(256), 0, s, t);
-            NG_LAUNCHED();
-            hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, k), dim3(256), 0, s, t, which, a0.alpha, a0.eta);
-            NG_LAUNCHED();
-            return 0;
-        };
         float* P = ws + lay.hp_off;                      // partial products [problem][replica][n x ldr]
-        NgChunkTable ct;
-        auto gemm_H = [&](float* Hout) -> int {          // Hout = X R^T for every slot
-            GemmDesc g[kThinMaxProblems];
-            int np = 0, pi = 0;                           // descriptors pending, problems so far
-            for (int j = 0; j < t.nslots; ++j) {
-                const int dim = t.dim[j], kc = ng_chunk_len(dim), nch = ng_chunk_count(dim);
-                ct.first[j] = pi; ct.count[j] = nch;
-                for (int c = 0; c < nch; ++c, ++pi) {
-                    GemmDesc& q = g[np];
-                    q = GemmDesc();
-                    q.M = n; q.N = rank; q.K = (c + 1 < nch) ? kc : dim - c * kc; q.batch = k;
-                    q.A = t.x[j] + (int64_t)c * kc; q.lda = t.ldx[j]; q.a_bstride = t.x_b[j]; q.a_kc = true;
-                    q.B = reinterpret_cast<const float*>(t.state[j]) + (int64_t)c * kc; q.ldb = round_up(dim, 4);
-                    q.b_bstride = t.st_b / 4; q.b_kc = true;
-                    q.C = P + (int64_t)pi * k * lay.H_b; q.ldc = lay.ldr; q.c_bstride = lay.H_b;
-                    if (++np == kThinMaxProblems) {
-                        NG_CHECK(gemm_launch_grouped(g, np, s, true));
-                        np = 0;
-                    }
-                }
-            }
-            if (np > 0) NG_CHECK(gemm_launch_grouped(g, np, s, true));
-            int64_t gx = ((int64_t)n * lay.ldr / 4 + 255) / 256;
-            if (gx > 64) gx = 64;
-            hipLaunchKernelGGL(ng_sum_chunks_slots_kernel, dim3((unsigned)gx, t.nslots, k), dim3(256), 0, s, t, ct, P, Hout);
-            NG_LAUNCHED();
-            return 0;
-        };
-        auto rank_update = [&](int use_h2, float sign) -> int {
-            constexpr int kRows = 128;                   // rows a wavefront walks with its block of R in registers
-            const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((n + kRows - 1) / kRows), (unsigned)(t.nslots * k));
-            if (rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<1>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
-            else hipLaunchKernelGGL(ng_rank_update_slots_kernel<2>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
-            NG_LAUNCHED();
-            return 0;
-        };
-        NG_CHECK(sumsq(0));
-        NG_CHECK(gemm_H(t.H));
+        NG_CHECK(ng_slots_norms(t, 0, a0.alpha, a0.eta, s));
+        NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
         {   // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it
             GemmDesc g[kNgSlots];
             for (int j = 0; j < t.nslots; ++j) {
@@ -1157,16 +1012,11 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
             }
             NG_CHECK(gemm_launch_grouped(g, t.nslots, s));
         }
-        NG_CHECK(rank_update(0, -1.f));                  // X1 = X - H R
-        NG_CHECK(gemm_H(t.H2));                          // H2 = X1 R^T
-        {
-            int64_t gx = ((int64_t)n * lay.ldr + 255) / 256;
-            if (gx > 1024) gx = 1024;
-            hipLaunchKernelGGL(ng_combine_slots_kernel, dim3((unsigned)gx, t.nslots, k), dim3(256), 0, s, t);
-            NG_LAUNCHED();
-        }
-        NG_CHECK(rank_update(1, 1.f));                   // Xh = X1 + (H (I - E) - H2) R
-        NG_CHECK(sumsq(1));
+        NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s));       // X1 = X - H R
+        NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s));            // H2 = X1 R^T
+        NG_CHECK(ng_slots_combine(t, s));
+        NG_CHECK(ng_slots_rank_update(t, 1, 1.f, s));        // Xh = X1 + (H (I - E) - H2) R
+        NG_CHECK(ng_slots_norms(t, 1, a0.alpha, a0.eta, s));
         {   // [W | b] <- [W | b] - lr g_out g_in Xh_out^T Xh_in for the layers of this pass
             GemmDesc g[kLayersPerPass];
             for (int i = 0; i < nl; ++i) {
