@@ -113,60 +113,74 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
     static_for<TM * TN>([&](auto bc) {
         constexpr int t = decltype(bc)::value;
         constexpr int i = t / TN, j = t % TN;
-        const int n = nbase + j * 32 + lcol;
-        const bool n_ok = n < N;
-        const uint32_t offC = (uint32_t)(((int64_t)(4 * lrow) * ldc + n) * 4);
-        const uint32_t offAux = kReadsAux ? (uint32_t)(((int64_t)(4 * lrow) * e.ldaux + n) * 4) : 0u;
-        const uint32_t offC2 = (KIND == EPI_AXPBY || KIND == EPI_BIAS_SIGMOID_SAMPLE) ? (uint32_t)(((int64_t)(4 * lrow) * e.ldc2 + n) * 4) : 0u;
-        const bool lastcol = KIND == EPI_AXPBY && c.lastcol_dst != nullptr && n == e.lastcol;
-        float bias_n = 0.f;
-        if (kBias && n_ok) bias_n = c.bias[n];
-        float old[16];
-        if constexpr (kReadsC || kReadsAux) {
-            // read-modify-write epilogues: issue the 16 loads of a 32x32 block back to back, then combine and
-            // store, so that their latencies overlap instead of adding up
-            const bool need_old = kReadsAux || e.beta != 0.f;
+        // Does this 32-column block hold the column that goes to a separate vector (uniform over the wavefront)?
+        // Only then do the accesses need a per-lane choice of destination.
+        bool has_lastcol = false;
+        if constexpr (KIND == EPI_AXPBY)
+            has_lastcol = c.lastcol_dst != nullptr && e.lastcol >= nbase + j * 32 && e.lastcol < nbase + j * 32 + 32;
+        auto block = [&](auto lcc) {
+            constexpr bool LC = decltype(lcc)::value;
+            const int n = nbase + j * 32 + lcol;
+            const bool n_ok = n < N;
+            const uint32_t offC = (uint32_t)(((int64_t)(4 * lrow) * ldc + n) * 4);
+            const uint32_t offAux = kReadsAux ? (uint32_t)(((int64_t)(4 * lrow) * e.ldaux + n) * 4) : 0u;
+            const uint32_t offC2 = (KIND == EPI_AXPBY || KIND == EPI_BIAS_SIGMOID_SAMPLE) ? (uint32_t)(((int64_t)(4 * lrow) * e.ldc2 + n) * 4) : 0u;
+            const bool lastcol = LC && n == e.lastcol;
+            float bias_n = 0.f;
+            if (kBias && n_ok) bias_n = c.bias[n];
+            float old[16];
+            if constexpr (kReadsC || kReadsAux) {
+                // read-modify-write epilogues: issue the 16 loads of a 32x32 block back to back, then combine and
+                // store, so that their latencies overlap instead of adding up
+                const bool need_old = kReadsAux || e.beta != 0.f;
+                static_for<16>([&](auto vc) {
+                    constexpr int v = decltype(vc)::value;
+                    const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
+                    const int m = mu + 4 * lrow;
+                    old[v] = 0.f;
+                    if (need_old && m < M && n_ok) {
+                        if constexpr (kReadsC) old[v] = lastcol ? c.lastcol_dst[m] : *at_off(c.C + (int64_t)mu * ldc, offC);
+                        else old[v] = *at_off(c.aux + (int64_t)mu * e.ldaux, offAux);
+                    }
+                });
+            }
             static_for<16>([&](auto vc) {
                 constexpr int v = decltype(vc)::value;
                 const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
                 const int m = mu + 4 * lrow;
-                old[v] = 0.f;
-                if (need_old && m < M && n_ok) {
-                    if constexpr (kReadsC) old[v] = lastcol ? c.lastcol_dst[m] : *at_off(c.C + (int64_t)mu * ldc, offC);
-                    else old[v] = *at_off(c.aux + (int64_t)mu * e.ldaux, offAux);
+                if (m < M && n_ok) {
+                    const float a = acc[i][j][v];
+                    float* dst = at_off(c.C + (int64_t)mu * ldc, offC);
+                    if constexpr (KIND == EPI_STORE) {
+                        *dst = a;
+                    } else if constexpr (KIND == EPI_BIAS) {
+                        *dst = a + bias_n;
+                    } else if constexpr (KIND == EPI_BIAS_SIGMOID) {
+                        *dst = e.act_tanh ? tanhf(a + bias_n) : sigmoidf_dev(a + bias_n);
+                    } else if constexpr (KIND == EPI_MUL_DSIGMOID) {
+                        *dst = e.act_tanh ? a * (1.f - old[v] * old[v]) : a * old[v] * (1.f - old[v]);
+                    } else if constexpr (KIND == EPI_AXPBY) {
+                        const float r = c.alpha * a + e.beta * old[v];
+                        if (lastcol) c.lastcol_dst[m] = r;
+                        else *dst = r;
+                        if (c.C2) *at_off(c.C2 + (int64_t)mu * e.ldc2, offC2) += r;
+                    } else if constexpr (KIND == EPI_BIAS_SIGMOID_SAMPLE) {
+                        const float pr = sigmoidf_dev(a + bias_n);
+                        if (c.C) *dst = pr;
+                        const float u = philox_uniform((uint64_t)m * (uint64_t)N + (uint64_t)n, e.key0, e.key1, e.step, e.layer, e.phase);
+                        *at_off(c.C2 + (int64_t)mu * e.ldc2, offC2) = (u < pr) ? 1.f : 0.f;
+                    } else {      // EPI_ROWSCALE_ADD
+                        *dst = c.alpha * a + c.rowvec[m] * old[v];
+                    }
                 }
             });
+        };
+        if constexpr (KIND == EPI_AXPBY) {
+            if (has_lastcol) block(std::true_type{});
+            else block(std::false_type{});
+        } else {
+            block(std::false_type{});
         }
-        static_for<16>([&](auto vc) {
-            constexpr int v = decltype(vc)::value;
-            const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
-            const int m = mu + 4 * lrow;
-            if (m < M && n_ok) {
-                const float a = acc[i][j][v];
-                float* dst = at_off(c.C + (int64_t)mu * ldc, offC);
-                if constexpr (KIND == EPI_STORE) {
-                    *dst = a;
-                } else if constexpr (KIND == EPI_BIAS) {
-                    *dst = a + bias_n;
-                } else if constexpr (KIND == EPI_BIAS_SIGMOID) {
-                    *dst = e.act_tanh ? tanhf(a + bias_n) : sigmoidf_dev(a + bias_n);
-                } else if constexpr (KIND == EPI_MUL_DSIGMOID) {
-                    *dst = e.act_tanh ? a * (1.f - old[v] * old[v]) : a * old[v] * (1.f - old[v]);
-                } else if constexpr (KIND == EPI_AXPBY) {
-                    const float r = c.alpha * a + e.beta * old[v];
-                    if (lastcol) c.lastcol_dst[m] = r;
-                    else *dst = r;
-                    if (c.C2) *at_off(c.C2 + (int64_t)mu * e.ldc2, offC2) += r;
-                } else if constexpr (KIND == EPI_BIAS_SIGMOID_SAMPLE) {
-                    const float pr = sigmoidf_dev(a + bias_n);
-                    if (c.C) *dst = pr;
-                    const float u = philox_uniform((uint64_t)m * (uint64_t)N + (uint64_t)n, e.key0, e.key1, e.step, e.layer, e.phase);
-                    *at_off(c.C2 + (int64_t)mu * e.ldc2, offC2) = (u < pr) ? 1.f : 0.f;
-                } else {      // EPI_ROWSCALE_ADD
-                    *dst = c.alpha * a + c.rowvec[m] * old[v];
-                }
-            }
-        });
     });
 }
 
