@@ -11,6 +11,7 @@
 #include "gemm.h"
 #include "../../include/mavg.h"
 #include "device_math.h"
+#include <cstddef>
 #include <utility>
 #include <type_traits>
 
@@ -118,10 +119,12 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
         bool has_lastcol = false;
         if constexpr (KIND == EPI_AXPBY)
             has_lastcol = c.lastcol_dst != nullptr && e.lastcol >= nbase + j * 32 && e.lastcol < nbase + j * 32 + 32;
-        auto block = [&](auto lcc) {
-            constexpr bool LC = decltype(lcc)::value;
+        // A block that lies wholly inside the matrix needs no per-element bounds checks (uniform over the wavefront).
+        const bool interior = mb + i * 32 + 32 <= M && nbase + j * 32 + 32 <= N;
+        auto block = [&](auto lcc, auto inc) {
+            constexpr bool LC = decltype(lcc)::value, IN = decltype(inc)::value;
             const int n = nbase + j * 32 + lcol;
-            const bool n_ok = n < N;
+            const bool n_ok = IN || n < N;
             const uint32_t offC = (uint32_t)(((int64_t)(4 * lrow) * ldc + n) * 4);
             const uint32_t offAux = kReadsAux ? (uint32_t)(((int64_t)(4 * lrow) * e.ldaux + n) * 4) : 0u;
             const uint32_t offC2 = (KIND == EPI_AXPBY || KIND == EPI_BIAS_SIGMOID_SAMPLE) ? (uint32_t)(((int64_t)(4 * lrow) * e.ldc2 + n) * 4) : 0u;
@@ -138,7 +141,7 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                     const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
                     const int m = mu + 4 * lrow;
                     old[v] = 0.f;
-                    if (need_old && m < M && n_ok) {
+                    if (need_old && (IN || m < M) && n_ok) {
                         if constexpr (kReadsC) old[v] = lastcol ? c.lastcol_dst[m] : *at_off(c.C + (int64_t)mu * ldc, offC);
                         else old[v] = *at_off(c.aux + (int64_t)mu * e.ldaux, offAux);
                     }
@@ -148,7 +151,7 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                 constexpr int v = decltype(vc)::value;
                 const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
                 const int m = mu + 4 * lrow;
-                if (m < M && n_ok) {
+                if ((IN || m < M) && n_ok) {
                     const float a = acc[i][j][v];
                     float* dst = at_off(c.C + (int64_t)mu * ldc, offC);
                     if constexpr (KIND == EPI_STORE) {
@@ -175,11 +178,12 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                 }
             });
         };
-        if constexpr (KIND == EPI_AXPBY) {
-            if (has_lastcol) block(std::true_type{});
-            else block(std::false_type{});
+        if (has_lastcol) {
+            if constexpr (KIND == EPI_AXPBY) block(std::true_type{}, std::false_type{});
+        } else if (interior) {
+            block(std::false_type{}, std::true_type{});
         } else {
-            block(std::false_type{});
+            block(std::false_type{}, std::false_type{});
         }
     });
 }
@@ -895,30 +899,38 @@ struct GemmGroupParams {
     int ngroups;
 };
 
-// Copy the parameters of the group this workgroup belongs to and return the group's first workgroup id.
-// Every index is a compile-time constant (a run-time index into the by-value kernel argument would send the
-// whole array through private memory); the selects are scalar, the condition being workgroup-uniform.
-__device__ __forceinline__ int select_group(const GemmGroupParams& gp, GemmKParams& p) {
-    p = gp.g[0];
-    int first = 0;
+// The group's parameters where they already are: in the kernel-argument segment (constant memory), read through
+// a pointer computed from the group's index, so that fields are fetched by scalar loads when they are needed
+// instead of the whole 336-byte record sitting in scalar registers through the main loop (a copy selected with
+// compile-time indices did: the loop then ran with spilled scalars, 435 of them in the weight-gradient kernel;
+// a run-time index into the by-value argument sends the whole array through private memory).  The table is the
+// kernel's first (only) argument, i.e. at offset 0 of the segment.
+__device__ __forceinline__ const GemmKParams& group_params(const GemmGroupParams& gp, int& first) {
+    int gi = 0;
+    first = 0;
     static_for<kMaxGroups - 1>([&](auto ic) {
         constexpr int i = decltype(ic)::value + 1;
-        if (i < gp.ngroups && (int)blockIdx.x >= gp.tile_start[i]) { p = gp.g[i]; first = gp.tile_start[i]; }
+        if (i < gp.ngroups && (int)blockIdx.x >= gp.tile_start[i]) { gi = i; first = gp.tile_start[i]; }
     });
-    return first;
+    gi = __builtin_amdgcn_readfirstlane(gi);
+    typedef const __attribute__((address_space(4))) char* ConstBytes;
+    ConstBytes base = (ConstBytes)__builtin_amdgcn_kernarg_segment_ptr();
+    typedef const __attribute__((address_space(4))) GemmKParams* ConstParams;
+    ConstParams q = (ConstParams)(base + offsetof(GemmGroupParams, g) + (size_t)gi * sizeof(GemmKParams));
+    return *(const GemmKParams*)q;
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int PF, bool AKC, bool BKC>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_grouped_kernel(GemmGroupParams gp) {
-    GemmKParams p;
-    const int first = select_group(gp, p);
+    int first;
+    const GemmKParams& p = group_params(gp, first);
     gemm_body<BM, BN, BK, WM, WN, PF, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
 template <int TM, int TN, int NST, bool AKC, bool BKC>
 __global__ __launch_bounds__(256) void gemm_dma_grouped_kernel(GemmGroupParams gp) {
-    GemmKParams p;
-    const int first = select_group(gp, p);
+    int first;
+    const GemmKParams& p = group_params(gp, first);
     gemm_dma_body<TM, TN, NST, AKC, BKC>(p, (int)blockIdx.x - first, blockIdx.z);
 }
 
@@ -944,7 +956,7 @@ __global__ __launch_bounds__(64 * kThinKGroups) void gemm_thin_grouped_kernel(Th
     });
     ThinProblem t = gp.g[0];
     int first = 0;
-    static_for<kMaxThin - 1>([&](auto ic) {          // one copy with a compile-time index (see select_group)
+    static_for<kMaxThin - 1>([&](auto ic) {          // one copy of the 84-byte record, with a compile-time index
         constexpr int i = decltype(ic)::value + 1;
         if (gi == i) { t = gp.g[i]; first = gp.tile_start[i]; }
     });
