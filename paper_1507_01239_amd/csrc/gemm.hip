@@ -949,17 +949,17 @@ struct ThinGroupParams {
     int ngroups;
 };
 __global__ __launch_bounds__(64 * kThinKGroups) void gemm_thin_grouped_kernel(ThinGroupParams gp) {
-    int gi = 0;
+    int gi = 0, first = 0;
     static_for<kMaxThin - 1>([&](auto ic) {
         constexpr int i = decltype(ic)::value + 1;
-        if (i < gp.ngroups && (int)blockIdx.x >= gp.tile_start[i]) gi = i;
+        if (i < gp.ngroups && (int)blockIdx.x >= gp.tile_start[i]) { gi = i; first = gp.tile_start[i]; }
     });
-    ThinProblem t = gp.g[0];
-    int first = 0;
-    static_for<kMaxThin - 1>([&](auto ic) {          // one copy of the 84-byte record, with a compile-time index
-        constexpr int i = decltype(ic)::value + 1;
-        if (gi == i) { t = gp.g[i]; first = gp.tile_start[i]; }
-    });
+    gi = __builtin_amdgcn_readfirstlane(gi);
+    // the problem's record straight from the kernel-argument segment (see group_params)
+    typedef const __attribute__((address_space(4))) char* ConstBytes;
+    typedef const __attribute__((address_space(4))) ThinProblem* ConstProblem;
+    const ThinProblem& t = *(const ThinProblem*)(ConstProblem)((ConstBytes)__builtin_amdgcn_kernarg_segment_ptr() +
+                                                              offsetof(ThinGroupParams, g) + (size_t)gi * sizeof(ThinProblem));
     GemmKParams p;
     p.A = t.A; p.lda = t.lda; p.a_bstride = t.a_bstride;
     p.B = t.B; p.ldb = t.ldb; p.b_bstride = t.b_bstride;
