@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmavg.so")
-SOURCES = ["gemm.hip", "elementwise.hip", "average.hip", "dnn.hip", "rbm.hip", "ngsgd.hip"]
+SOURCES = ["gemm_dma64.hip", "gemm_dma128.hip", "gemm_kg.hip", "gemm_legacy.hip", "gemm.hip", "elementwise.hip", "average.hip",
+           "dnn.hip", "rbm.hip", "ngsgd.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-std=c++17", "-O3", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
