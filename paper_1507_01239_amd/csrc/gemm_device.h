@@ -709,11 +709,11 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
 // instead of 4 (3 direct loads per wavefront and k-tile instead of 2).
 constexpr int kKGroups = 4;
 
-template <int GW, bool AKC, bool BKC, int KG = kKGroups>
+template <int GW, bool AKC, bool BKC, int KG = kKGroups, int NST = 4>
 __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int tile, const int bz) {
     // GW wavefronts per k-group: 2 (32x64 tile, one barrier per k-tile) or 1 (32x32 tile: a k-group is a single
     // wavefront with a ring of its own, so the loop needs no barrier at all, only the wavefront's own vmcnt waits)
-    constexpr int BK = kDmaBK, NST = 4, BM = 32, BN = 32 * GW;
+    constexpr int BK = kDmaBK, BM = 32, BN = 32 * GW;
     constexpr int A_LOADS = 2 / GW, LOADS = A_LOADS + 2;
     static_assert(GW == 1 || GW == 2, "one or two wavefronts per k-group");
     constexpr int TILE_A = BM * BK, TILE_B = BN * BK;
@@ -802,9 +802,12 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
 #pragma unroll
     for (int t = 0; t < NST - 1; ++t)
         if (t < nkt) issue(t, t);
-    auto wait_next = [&]() {       // two younger k-tiles of LOADS loads each may stay in flight
-        if constexpr (LOADS == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    auto wait_next = [&]() {       // NST - 2 younger k-tiles of LOADS loads each may stay in flight
+        constexpr int OUT = LOADS * (NST - 2);
+        if constexpr (OUT == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else if constexpr (OUT == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if constexpr (OUT == 9) asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+        else { static_assert(OUT == 12, "unexpected number of loads in flight"); asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); }
     };
     auto group_barrier = [&]() {   // publish the landed tile to the other wavefront of the k-group, if there is one
         if constexpr (GW > 1) __syncthreads();
@@ -814,8 +817,8 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     group_barrier();
     if (nkt > 0) read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     auto step = [&](auto uc, const int t) {
-        constexpr int u = decltype(uc)::value;
-        constexpr int set = u & 1;
+        constexpr int u = decltype(uc)::value % NST;      // stage of tile t
+        constexpr int set = decltype(uc)::value & 1;      // register set of tile t
         if (t < nkt) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][0][c], fb[set][0][c], acc[0][0], 0, 0, 0);
@@ -836,8 +839,9 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    for (int t = 0; t < nloop; t += NST) {
-        static_for<NST>([&](auto uc) {
+    constexpr int PERIOD = (NST % 2 == 0) ? NST : 2 * NST;      // stages and register sets repeat together
+    for (int t = 0; t < nloop; t += PERIOD) {
+        static_for<PERIOD>([&](auto uc) {
             if (t + decltype(uc)::value < nloop) step(uc, t + decltype(uc)::value);
         });
     }
@@ -879,9 +883,11 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0, n0 + wn, lrow, lcol)))
 }
 
+// Ring of four stages: a fifth (the 32x64 variant has the LDS for it: 144 KB with the reduction buffer) changed
+// nothing measurable, so the loop is not waiting on the depth of its prefetch.
 template <int GW, bool AKC, bool BKC>
 __global__ __launch_bounds__(64 * kKGroups * GW) void gemm_dma_kg_kernel(GemmKParams p) {
-    gemm_dma_kg_body<GW, AKC, BKC>(p, blockIdx.x, blockIdx.z);
+    gemm_dma_kg_body<GW, AKC, BKC, kKGroups, 4>(p, blockIdx.x, blockIdx.z);
 }
 
 // Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
