@@ -216,7 +216,9 @@ __global__ __launch_bounds__(kEigThreads) void ng_eig_kernel(NgFoldTable tb, int
             }
         off = block_sum_eig(off, red);
         dg = block_sum_eig(dg, red);
-        if (off <= 1e-26 * dg) break;       // off-diagonal norm below 1e-13 of the diagonal
+        // off-diagonal norm below 1e-13 of the diagonal: Z spans many orders of magnitude, and a looser stop (1e-10)
+        // leaves its small eigenvalues, hence the weak rows of R, outside the parity tolerance
+        if (off <= 1e-26 * dg) break;
         for (int round = 0; round < m - 1; ++round) {
             // Z <- J^T Z J, U^T <- J^T U^T with, for every pair (p, q) of the round,
             // row_p <- c row_p - s row_q,  row_q <- s row_p + c row_q  (and the same for the columns of Z)
