@@ -227,7 +227,7 @@ int32_t ngsgd_precondition(void* state, int32_t dim, int32_t rank,
  * C(m,n) = epilogue( sum_{kk<k} A(m,kk) B(kk,n) ), float32 operands, float32 MFMA accumulation.
  *   a_kc != 0: A(m,kk) = a[m*lda + kk], else a[kk*lda + m];   b_kc != 0: B(kk,n) = b[n*ldb + kk], else b[kk*ldb + n]
  *   C(m,n) = c[m*ldc + n]
- *   epi: 0  C = v            1  C = v + bias[n]          2  C = sigmoid(v + bias[n])
+ *   epi: 0  C = v            1  C = v + bias[n]          2  C = alpha*sigmoid(v + bias[n])
  *        3  C = v * aux(m,n) * (1 - aux(m,n))            4  C = beta*C + alpha*v
  *   cfg: -1 = choose the kernel, else its index:
  *        1  64x64 tiles, operands loaded global -> LDS directly when they allow it (16-byte aligned rows, k a

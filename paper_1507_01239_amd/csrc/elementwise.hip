@@ -244,6 +244,24 @@ int copy_bcast_launch(const float* src, int64_t count, float* dst, int64_t dst_b
     return note_hip_error(hipGetLastError());
 }
 
+// ---- copy of a rows x cols matrix between two row strides ---------------------------------------------
+__global__ __launch_bounds__(kThreads) void copy2d_kernel(const float* __restrict__ src, int64_t lds, float* __restrict__ dst,
+                                                          int64_t ldd, int rows, int cols) {
+    const int64_t total = (int64_t)rows * cols;
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kThreads) {
+        const int64_t r = e / cols, c = e - r * cols;
+        dst[r * ldd + c] = src[r * lds + c];
+    }
+}
+
+int copy2d_launch(const float* src, int64_t lds, float* dst, int64_t ldd, int rows, int cols, hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return 0;
+    int64_t gx = ((int64_t)rows * cols + kThreads - 1) / kThreads;
+    if (gx > 4096) gx = 4096;
+    hipLaunchKernelGGL(copy2d_kernel, dim3((unsigned)gx), dim3(kThreads), 0, s, src, lds, dst, ldd, rows, cols);
+    return note_hip_error(hipGetLastError());
+}
+
 // ---- frames whose largest posterior is the label's ---------------------------------------------------
 __global__ void zero_i32_kernel(int32_t* p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;

@@ -16,7 +16,7 @@ constexpr int kNumXCD = 8;
 enum EpiKind : int {
     EPI_STORE = 0,            // C = v
     EPI_BIAS = 1,             // C = v + bias[n]
-    EPI_BIAS_SIGMOID = 2,     // C = sigmoid(v + bias[n])
+    EPI_BIAS_SIGMOID = 2,     // C = alpha * sigmoid(v + bias[n])
     EPI_MUL_DSIGMOID = 3,     // C = v * a * (1 - a),  a = aux[m, n]
     EPI_AXPBY = 4,            // C = beta*C + alpha*v ;  if C2: C2 += C
     EPI_BIAS_SIGMOID_SAMPLE = 5,  // p = sigmoid(v + bias[n]); if C: C = p;  C2 = [u(m*N+n) < p]

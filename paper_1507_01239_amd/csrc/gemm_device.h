@@ -64,7 +64,7 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
     } else if (KIND == EPI_BIAS) {
         c.C[(int64_t)m * ldc + n] = v + c.bias[n];
     } else if (KIND == EPI_BIAS_SIGMOID) {
-        c.C[(int64_t)m * ldc + n] = e.act_tanh ? tanhf(v + c.bias[n]) : sigmoidf_dev(v + c.bias[n]);
+        c.C[(int64_t)m * ldc + n] = c.alpha * (e.act_tanh ? tanhf(v + c.bias[n]) : sigmoidf_dev(v + c.bias[n]));
     } else if (KIND == EPI_MUL_DSIGMOID) {
         const float a = c.aux[(int64_t)m * e.ldaux + n];
         c.C[(int64_t)m * ldc + n] = e.act_tanh ? v * (1.f - a * a) : v * a * (1.f - a);
@@ -153,7 +153,7 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                     } else if constexpr (KIND == EPI_BIAS) {
                         *dst = a + bias_n;
                     } else if constexpr (KIND == EPI_BIAS_SIGMOID) {
-                        *dst = e.act_tanh ? tanhf(a + bias_n) : sigmoidf_dev(a + bias_n);
+                        *dst = c.alpha * (e.act_tanh ? tanhf(a + bias_n) : sigmoidf_dev(a + bias_n));
                     } else if constexpr (KIND == EPI_MUL_DSIGMOID) {
                         *dst = e.act_tanh ? a * (1.f - old[v] * old[v]) : a * old[v] * (1.f - old[v]);
                     } else if constexpr (KIND == EPI_AXPBY) {

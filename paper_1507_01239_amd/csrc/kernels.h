@@ -38,6 +38,8 @@ int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, 
 
 // dst[b*dst_bstride + i] = src[i], i < count, b < batch.
 int copy_bcast_launch(const float* src, int64_t count, float* dst, int64_t dst_bstride, int batch, hipStream_t s);
+// dst(r, c) = src(r, c) for a rows x cols matrix (row strides lds, ldd)
+int copy2d_launch(const float* src, int64_t lds, float* dst, int64_t ldd, int rows, int cols, hipStream_t s);
 
 // correct[b] = number of rows n < rows whose arg max over p[b](n, :) (lowest index among equal maxima) equals
 // labels[b*label_bstride + n].

@@ -1,7 +1,8 @@
 // rbm_cd1_step: one CD-1 minibatch update of an RBM.  Three affine GEMMs (hidden probabilities with
 // the Bernoulli sampling fused into the epilogue, reconstruction, hidden probabilities of the
-// reconstruction), two statistics GEMMs fused with the momentum update, two column-sum kernels for the
-// biases, and a fixed-order reduction for the reconstruction error.
+// reconstruction), ONE statistics GEMM fused with the momentum updates of W and of the hidden bias
+// (positive minus negative phase as one contraction over the stacked rows [P_h0; -P_h1] and [V0; V1]), a
+// column-sum kernel for the visible bias, and a fixed-order reduction for the reconstruction error.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -18,7 +19,7 @@ inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 struct RbmWs {
     int64_t ldh, ldv;
-    int64_t off_ph0, off_h0, off_v1, off_ph1, off_part, off_gemm, gemm_floats, total;
+    int64_t off_ph, off_h0, off_vv, off_part, off_gemm, gemm_floats, total;     // ph: [P_h0; -P_h1], vv: [V0; V1], 2n rows each
 };
 
 RbmWs rbm_ws(int V, int H, int n) {
@@ -27,13 +28,11 @@ RbmWs rbm_ws(int V, int H, int n) {
     w.ldv = round_up(V, 4);
     int64_t g = gemm_ws_floats(n, H, V, 1), f;
     f = gemm_ws_floats(n, V, H, 1); if (f > g) g = f;
-    f = gemm_ws_floats(H, V, n, 1); if (f > g) g = f;
     w.gemm_floats = round_up(g, 64);
     int64_t off = 0;
-    w.off_ph0 = off; off += round_up((int64_t)n * w.ldh, 64);
+    w.off_ph = off;  off += round_up((int64_t)2 * n * w.ldh, 64);
     w.off_h0 = off;  off += round_up((int64_t)n * w.ldh, 64);
-    w.off_ph1 = off; off += round_up((int64_t)n * w.ldh, 64);
-    w.off_v1 = off;  off += round_up((int64_t)n * w.ldv, 64);
+    w.off_vv = off;  off += round_up((int64_t)2 * n * w.ldv, 64);
     w.off_part = off; off += round_up(sqdiff_partials(), 64);
     w.off_gemm = off; off += w.gemm_floats;
     w.total = off;
@@ -86,10 +85,11 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
     if (!workspace || workspace_bytes < lay.total * 4 + 256) return MAVG_E_WORKSPACE;
     float* ws = ws_base(workspace);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    float* ph0 = ws + lay.off_ph0;
+    float* ph0 = ws + lay.off_ph;                       // rows 0..n-1 of the stacked hidden statistics
+    float* ph1 = ph0 + (int64_t)n * lay.ldh;            // rows n..2n-1, stored NEGATED
     float* h0 = ws + lay.off_h0;
-    float* ph1 = ws + lay.off_ph1;
-    float* v1 = ws + lay.off_v1;
+    float* vv = ws + lay.off_vv;                        // rows 0..n-1: copy of V0; rows n..2n-1: V1
+    float* v1 = vv + (int64_t)n * lay.ldv;
     float* gws = ws + lay.off_gemm;
     const uint32_t k0 = (uint32_t)(seed & 0xFFFFFFFFu), k1 = (uint32_t)(seed >> 32);
     const float invn = 1.0f / (float)n;
@@ -122,40 +122,32 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
         }
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
-    {   // P_h1 = sigmoid(V1 W^T + c)
+    {   // -P_h1 = -sigmoid(V1 W^T + c)
         GemmDesc g;
         g.M = n; g.N = H; g.K = V;
         g.A = v1; g.lda = lay.ldv; g.a_kc = true;
         g.B = w; g.ldb = V; g.b_kc = true;
         g.C = ph1; g.ldc = lay.ldh;
-        g.epi.kind = EPI_BIAS_SIGMOID; g.epi.bias = c;
+        g.epi.kind = EPI_BIAS_SIGMOID; g.epi.bias = c; g.epi.alpha = -1.f;
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
     if (dbg_ph0 && note_hip_error(hipMemcpy2DAsync(dbg_ph0, (size_t)H * 4, ph0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (dbg_h0 && note_hip_error(hipMemcpy2DAsync(dbg_h0, (size_t)H * 4, h0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (dbg_v1 && note_hip_error(hipMemcpy2DAsync(dbg_v1, (size_t)V * 4, v1, (size_t)lay.ldv * 4, (size_t)V * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (recon_err && sqdiff_sum_launch(v0, V, v1, lay.ldv, n, V, ws + lay.off_part, recon_err, s) != 0) return MAVG_E_LAUNCH;
-    {   // MW <- momentum MW + (lr/n) P_h0^T V0
+    if (copy2d_launch(v0, V, vv, lay.ldv, n, V, s) != 0) return MAVG_E_LAUNCH;
+    {   // MW <- momentum MW + (lr/n) (P_h0^T V0 - P_h1^T V1) = momentum MW + (lr/n) [P_h0; -P_h1]^T [V0; V1];  W <- W + MW
         GemmDesc g;
-        g.M = H; g.N = V; g.K = n;
+        g.M = H; g.N = V; g.K = 2 * n;
         g.A = ph0; g.lda = lay.ldh; g.a_kc = false;
-        g.B = v0; g.ldb = V; g.b_kc = false;
+        g.a_pad4 = true;        // rows of the stacked statistics are ldh = round_up(H, 4) floats long
+        g.B = vv; g.ldb = lay.ldv; g.b_kc = false;
+        g.b_pad4 = true;
         g.C = mw; g.ldc = V;
         g.epi.kind = EPI_AXPBY; g.epi.alpha = lr * invn; g.epi.beta = momentum;
-        // Mc <- momentum Mc + (lr/n) colsum(P_h0): the row sums of this product's first operand (P_h0^T)
-        g.epi.rowsum_dst = mc; g.epi.rowsum_alpha = lr * invn; g.epi.rowsum_beta = momentum;
-        if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
-    }
-    {   // MW <- MW - (lr/n) P_h1^T V1 ;  W <- W + MW
-        GemmDesc g;
-        g.M = H; g.N = V; g.K = n;
-        g.A = ph1; g.lda = lay.ldh; g.a_kc = false;
-        g.B = v1; g.ldb = lay.ldv; g.b_kc = false;
-        g.C = mw; g.ldc = V;
-        g.epi.kind = EPI_AXPBY; g.epi.alpha = -lr * invn; g.epi.beta = 1.f;
         g.epi.C2 = w; g.epi.ldc2 = V;
-        // Mc <- Mc - (lr/n) colsum(P_h1) ;  c <- c + Mc
-        g.epi.rowsum_dst = mc; g.epi.rowsum_alpha = -lr * invn; g.epi.rowsum_beta = 1.f;
+        // Mc <- momentum Mc + (lr/n) colsum(P_h0 - P_h1), the row sums of this product's first operand;  c <- c + Mc
+        g.epi.rowsum_dst = mc; g.epi.rowsum_alpha = lr * invn; g.epi.rowsum_beta = momentum;
         g.epi.rowsum_dst2 = c;
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }

@@ -34,7 +34,7 @@ def _run(m, n, k, a_kc, b_kc, epi=0, cfg=-1, splits=0, seed=0, pad=0, alpha=1.0,
     got = host(c)
     v = A.astype(np.float64) @ Bm.astype(np.float64)
     if epi == 1: ref = v + bias
-    elif epi == 2: ref = 1 / (1 + np.exp(-(v + bias)))
+    elif epi == 2: ref = alpha / (1 + np.exp(-(v + bias)))
     elif epi == 3: ref = v * aux * (1.0 - aux)
     elif epi == 4: ref = beta * c0[:, :n].astype(np.float64) + alpha * v
     else: ref = v
