@@ -131,74 +131,64 @@ int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_
 }
 
 // ---- column sums with fused update ---------------------------------------------------------------
-// A workgroup owns 32 columns: 256 threads = 32 columns x 8 row groups; row group g sums rows g, g+8, ...
-// top to bottom (a wavefront reads two 128-byte row segments per step), then the 8 partial sums of a
-// column are combined in a fixed order through LDS.
-__global__ __launch_bounds__(kThreads) void colsum_axpby_kernel(const float* __restrict__ X, int64_t ldx, int64_t x_bstride,
-                                                                const float* __restrict__ Y, int64_t ldy, int64_t y_bstride,
-                                                                float* __restrict__ dst, int64_t dst_bstride,
-                                                                float* __restrict__ dst2, int64_t dst2_bstride,
-                                                                int rows, int cols, float alpha, float beta, ColsumExtras ex) {
-    __shared__ float sh[8][33];
-    const int b = blockIdx.y;
+// dst[j] = beta dst[j] + alpha sum_r (X(r, j) - Y(r, j));  dst2[j] += dst[j];  optionally Xcopy(r, j) = X(r, j).
+// A workgroup owns 32 columns: 1024 threads = 32 columns x 32 row groups; row group g sums rows g, g+32, ...
+// top to bottom, eight rows per trip with their loads issued together (a wavefront reads two 128-byte row
+// segments per load), then the 32 partial sums of a column are combined in a fixed order through LDS.
+constexpr int kColsumGroups = 32;
+__global__ __launch_bounds__(32 * kColsumGroups) void colsum_axpby_kernel(const float* __restrict__ X, int64_t ldx,
+                                                                         const float* __restrict__ Y, int64_t ldy,
+                                                                         float* __restrict__ dst, float* __restrict__ dst2,
+                                                                         float* __restrict__ xcopy, int64_t ldc,
+                                                                         int rows, int cols, float alpha, float beta) {
+    __shared__ float sh[kColsumGroups][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int j = blockIdx.x * 32 + tx;
     float s = 0.f;
     if (j < cols) {
-        const float* __restrict__ x = X + (int64_t)b * x_bstride + j;
-        const float* __restrict__ y = Y ? Y + (int64_t)b * y_bstride + j : nullptr;
-        const float* __restrict__ w = ex.roww ? ex.roww + (int64_t)b * ex.roww_bstride : nullptr;
-        // sixteen (then eight) rows per trip: their loads are issued together, the additions keep the row order
+        const float* __restrict__ x = X + j;
+        const float* __restrict__ y = Y ? Y + j : nullptr;
         int n = ty;
-        auto trip = [&](auto nc) {
-            constexpr int NQ = decltype(nc)::value;
-            float v[NQ];
+        for (; n + 7 * kColsumGroups < rows; n += 8 * kColsumGroups) {
+            float v[8];
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) v[q] = x[(int64_t)(n + 8 * q) * ldx];
+            for (int q = 0; q < 8; ++q) v[q] = x[(int64_t)(n + kColsumGroups * q) * ldx];
+            if (xcopy) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) xcopy[(int64_t)(n + kColsumGroups * q) * ldc + j] = v[q];
+            }
             if (y) {
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) v[q] -= y[(int64_t)(n + 8 * q) * ldy];
-            }
-            if (w) {
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) v[q] *= w[(int64_t)(n + 8 * q) * ex.roww_ld];
+                for (int q = 0; q < 8; ++q) v[q] -= y[(int64_t)(n + kColsumGroups * q) * ldy];
             }
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) s += v[q];
-        };
-        for (; n + 120 < rows; n += 128) trip(std::integral_constant<int, 16>{});
-        for (; n + 56 < rows; n += 64) trip(std::integral_constant<int, 8>{});
-        for (; n < rows; n += 8) {
+            for (int q = 0; q < 8; ++q) s += v[q];
+        }
+        for (; n < rows; n += kColsumGroups) {
             float v = x[(int64_t)n * ldx];
+            if (xcopy) xcopy[(int64_t)n * ldc + j] = v;
             if (y) v -= y[(int64_t)n * ldy];
-            if (w) v *= w[(int64_t)n * ex.roww_ld];
             s += v;
         }
     }
     sh[ty][tx] = s;
     __syncthreads();
     if (ty == 0 && j < cols) {
-        const float tot = ((sh[0][tx] + sh[1][tx]) + (sh[2][tx] + sh[3][tx])) + ((sh[4][tx] + sh[5][tx]) + (sh[6][tx] + sh[7][tx]));
-        float a = alpha;
-        if (ex.alpha_dev0) a *= ex.alpha_dev0[b];
-        if (ex.alpha_dev1) a *= ex.alpha_dev1[b];
-        float* d = dst + (int64_t)b * dst_bstride + j;
-        float r = a * tot;
-        if (beta != 0.f) r += beta * *d;
-        *d = r;
-        if (dst2) dst2[(int64_t)b * dst2_bstride + j] += r;
+        float tot = 0.f;
+#pragma unroll
+        for (int g = 0; g < kColsumGroups; ++g) tot += sh[g][tx];
+        float r = alpha * tot;
+        if (beta != 0.f) r += beta * dst[j];
+        dst[j] = r;
+        if (dst2) dst2[j] += r;
     }
 }
 
-int colsum_axpby_launch(const float* X, int64_t ldx, int64_t x_bstride, const float* Y, int64_t ldy, int64_t y_bstride,
-                        float* dst, int64_t dst_bstride, float* dst2, int64_t dst2_bstride, int rows, int cols, int batch,
-                        float alpha, float beta, hipStream_t s, const ColsumExtras* extras) {
-    if (cols <= 0 || batch <= 0) return 0;
-    dim3 grid((unsigned)((cols + 31) / 32), (unsigned)batch);
-    ColsumExtras ex;
-    if (extras) ex = *extras;
-    hipLaunchKernelGGL(colsum_axpby_kernel, grid, dim3(kThreads), 0, s, X, ldx, x_bstride, Y, ldy, y_bstride, dst, dst_bstride,
-                       dst2, dst2_bstride, rows, cols, alpha, beta, ex);
+int colsum_axpby_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, float* dst, float* dst2, float* xcopy,
+                        int64_t ldc, int rows, int cols, float alpha, float beta, hipStream_t s) {
+    if (cols <= 0) return 0;
+    hipLaunchKernelGGL(colsum_axpby_kernel, dim3((unsigned)((cols + 31) / 32)), dim3(32 * kColsumGroups), 0, s, X, ldx, Y, ldy, dst,
+                       dst2, xcopy, ldc, rows, cols, alpha, beta);
     return note_hip_error(hipGetLastError());
 }
 
@@ -241,24 +231,6 @@ int copy_bcast_launch(const float* src, int64_t count, float* dst, int64_t dst_b
     int64_t gx = (count + kThreads - 1) / kThreads;
     if (gx > 8192) gx = 8192;
     hipLaunchKernelGGL(copy_bcast_kernel, dim3((unsigned)gx, (unsigned)batch), dim3(kThreads), 0, s, src, count, dst, dst_bstride);
-    return note_hip_error(hipGetLastError());
-}
-
-// ---- copy of a rows x cols matrix between two row strides ---------------------------------------------
-__global__ __launch_bounds__(kThreads) void copy2d_kernel(const float* __restrict__ src, int64_t lds, float* __restrict__ dst,
-                                                          int64_t ldd, int rows, int cols) {
-    const int64_t total = (int64_t)rows * cols;
-    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kThreads) {
-        const int64_t r = e / cols, c = e - r * cols;
-        dst[r * ldd + c] = src[r * lds + c];
-    }
-}
-
-int copy2d_launch(const float* src, int64_t lds, float* dst, int64_t ldd, int rows, int cols, hipStream_t s) {
-    if (rows <= 0 || cols <= 0) return 0;
-    int64_t gx = ((int64_t)rows * cols + kThreads - 1) / kThreads;
-    if (gx > 4096) gx = 4096;
-    hipLaunchKernelGGL(copy2d_kernel, dim3((unsigned)gx), dim3(kThreads), 0, s, src, lds, dst, ldd, rows, cols);
     return note_hip_error(hipGetLastError());
 }
 

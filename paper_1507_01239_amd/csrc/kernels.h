@@ -17,19 +17,10 @@ int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride,
 // out[b] = sum_{i<n} v[b*n + i], summed in a fixed order (one workgroup per b).
 int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s);
 
-// dst[b][j] = beta*dst[b][j] + alpha * sum_{n<rows} w[b][n] * (X[b](n,j) - Y[b](n,j))   (Y may be null);
-// if dst2: dst2[b][j] += dst[b][j].
-// Optional extras (null = absent): row weights w[b][n] = roww[b*roww_bstride + n*roww_ld]; device-side factors
-// of alpha, alpha_eff = alpha * alpha_dev0[b] * alpha_dev1[b].
-struct ColsumExtras {
-    const float* roww = nullptr; int64_t roww_ld = 0, roww_bstride = 0;
-    const float* alpha_dev0 = nullptr; const float* alpha_dev1 = nullptr;
-};
-int colsum_axpby_launch(const float* X, int64_t ldx, int64_t x_bstride,
-                        const float* Y, int64_t ldy, int64_t y_bstride,
-                        float* dst, int64_t dst_bstride, float* dst2, int64_t dst2_bstride,
-                        int rows, int cols, int batch, float alpha, float beta, hipStream_t s,
-                        const ColsumExtras* extras = nullptr);
+// dst[j] = beta dst[j] + alpha colsum_j(X - Y) over `rows` rows (Y may be null);  dst2[j] += dst[j] (dst2 may be null);
+// xcopy (may be null): receives a copy of X with row stride ldc.
+int colsum_axpby_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, float* dst, float* dst2, float* xcopy,
+                        int64_t ldc, int rows, int cols, float alpha, float beta, hipStream_t s);
 
 // out[0] = sum over rows x cols of (X - Y)^2, fixed order; partial: scratch of >= sqdiff_partials() floats.
 int sqdiff_partials();
@@ -38,8 +29,6 @@ int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, 
 
 // dst[b*dst_bstride + i] = src[i], i < count, b < batch.
 int copy_bcast_launch(const float* src, int64_t count, float* dst, int64_t dst_bstride, int batch, hipStream_t s);
-// dst(r, c) = src(r, c) for a rows x cols matrix (row strides lds, ldd)
-int copy2d_launch(const float* src, int64_t lds, float* dst, int64_t ldd, int rows, int cols, hipStream_t s);
 
 // correct[b] = number of rows n < rows whose arg max over p[b](n, :) (lowest index among equal maxima) equals
 // labels[b*label_bstride + n].

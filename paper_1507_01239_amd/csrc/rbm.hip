@@ -2,7 +2,7 @@
 // the Bernoulli sampling fused into the epilogue, reconstruction, hidden probabilities of the
 // reconstruction), ONE statistics GEMM fused with the momentum updates of W and of the hidden bias
 // (positive minus negative phase as one contraction over the stacked rows [P_h0; -P_h1] and [V0; V1]), a
-// column-sum kernel for the visible bias, and a fixed-order reduction for the reconstruction error.
+// column-sum kernel for the visible bias that also stacks V0, and a fixed-order reduction for the reconstruction error.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -135,7 +135,8 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
     if (dbg_h0 && note_hip_error(hipMemcpy2DAsync(dbg_h0, (size_t)H * 4, h0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (dbg_v1 && note_hip_error(hipMemcpy2DAsync(dbg_v1, (size_t)V * 4, v1, (size_t)lay.ldv * 4, (size_t)V * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (recon_err && sqdiff_sum_launch(v0, V, v1, lay.ldv, n, V, ws + lay.off_part, recon_err, s) != 0) return MAVG_E_LAUNCH;
-    if (copy2d_launch(v0, V, vv, lay.ldv, n, V, s) != 0) return MAVG_E_LAUNCH;
+    // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma;  the same pass copies V0 under V1's rows' stride
+    if (colsum_axpby_launch(v0, V, v1, lay.ldv, ma, a, vv, lay.ldv, n, V, lr * invn, momentum, s) != 0) return MAVG_E_LAUNCH;
     {   // MW <- momentum MW + (lr/n) (P_h0^T V0 - P_h1^T V1) = momentum MW + (lr/n) [P_h0; -P_h1]^T [V0; V1];  W <- W + MW
         GemmDesc g;
         g.M = H; g.N = V; g.K = 2 * n;
@@ -151,7 +152,5 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
         g.epi.rowsum_dst2 = c;
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
-    // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma
-    if (colsum_axpby_launch(v0, V, 0, v1, lay.ldv, 0, ma, 0, a, 0, n, V, 1, lr * invn, momentum, s) != 0) return MAVG_E_LAUNCH;
     return MAVG_OK;
 }
