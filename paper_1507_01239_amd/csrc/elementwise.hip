@@ -131,7 +131,8 @@ int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_
 }
 
 // ---- column sums with fused update ---------------------------------------------------------------
-// dst[j] = beta dst[j] + alpha sum_r (X(r, j) - Y(r, j));  dst2[j] += dst[j];  optionally Xcopy(r, j) = X(r, j).
+// dst[j] = beta dst[j] + alpha sum_r (X(r, j) - Y(r, j));  dst2[j] += dst[j];  optionally Xcopy(r, j) = X(r, j) and
+// sq_partial[workgroup] = sum over the workgroup's 32 columns of (X - Y)^2 (fixed order; the caller adds them up).
 // A workgroup owns 32 columns: 1024 threads = 32 columns x 32 row groups; row group g sums rows g, g+32, ...
 // top to bottom, eight rows per trip with their loads issued together (a wavefront reads two 128-byte row
 // segments per load), then the 32 partial sums of a column are combined in a fixed order through LDS.
@@ -140,11 +141,13 @@ __global__ __launch_bounds__(32 * kColsumGroups) void colsum_axpby_kernel(const 
                                                                          const float* __restrict__ Y, int64_t ldy,
                                                                          float* __restrict__ dst, float* __restrict__ dst2,
                                                                          float* __restrict__ xcopy, int64_t ldc,
+                                                                         float* __restrict__ sq_partial,
                                                                          int rows, int cols, float alpha, float beta) {
     __shared__ float sh[kColsumGroups][33];
+    __shared__ float sq[kColsumGroups][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int j = blockIdx.x * 32 + tx;
-    float s = 0.f;
+    float s = 0.f, s2 = 0.f;
     if (j < cols) {
         const float* __restrict__ x = X + j;
         const float* __restrict__ y = Y ? Y + j : nullptr;
@@ -162,17 +165,31 @@ __global__ __launch_bounds__(32 * kColsumGroups) void colsum_axpby_kernel(const 
                 for (int q = 0; q < 8; ++q) v[q] -= y[(int64_t)(n + kColsumGroups * q) * ldy];
             }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) s += v[q];
+            for (int q = 0; q < 8; ++q) { s += v[q]; s2 += v[q] * v[q]; }
         }
         for (; n < rows; n += kColsumGroups) {
             float v = x[(int64_t)n * ldx];
             if (xcopy) xcopy[(int64_t)n * ldc + j] = v;
             if (y) v -= y[(int64_t)n * ldy];
             s += v;
+            s2 += v * v;
         }
     }
     sh[ty][tx] = s;
+    sq[ty][tx] = s2;
     __syncthreads();
+    if (sq_partial && ty == 1) {          // one wavefront-half: column totals, then across the 32 columns, fixed order
+        float c2 = 0.f;
+#pragma unroll
+        for (int g = 0; g < kColsumGroups; ++g) c2 += sq[g][tx];
+        sq[0][tx] = c2;                   // row 0 is read by these same 32 threads only
+        __builtin_amdgcn_wave_barrier();
+        if (tx == 0) {
+            float t2 = 0.f;
+            for (int c = 0; c < 32; ++c) t2 += sq[0][c];
+            sq_partial[blockIdx.x] = t2;
+        }
+    }
     if (ty == 0 && j < cols) {
         float tot = 0.f;
 #pragma unroll
@@ -184,39 +201,14 @@ __global__ __launch_bounds__(32 * kColsumGroups) void colsum_axpby_kernel(const 
     }
 }
 
+int colsum_blocks(int cols) { return (cols + 31) / 32; }
+
 int colsum_axpby_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, float* dst, float* dst2, float* xcopy,
-                        int64_t ldc, int rows, int cols, float alpha, float beta, hipStream_t s) {
+                        int64_t ldc, float* sq_partial, int rows, int cols, float alpha, float beta, hipStream_t s) {
     if (cols <= 0) return 0;
-    hipLaunchKernelGGL(colsum_axpby_kernel, dim3((unsigned)((cols + 31) / 32)), dim3(32 * kColsumGroups), 0, s, X, ldx, Y, ldy, dst,
-                       dst2, xcopy, ldc, rows, cols, alpha, beta);
+    hipLaunchKernelGGL(colsum_axpby_kernel, dim3((unsigned)colsum_blocks(cols)), dim3(32 * kColsumGroups), 0, s, X, ldx, Y, ldy, dst,
+                       dst2, xcopy, ldc, sq_partial, rows, cols, alpha, beta);
     return note_hip_error(hipGetLastError());
-}
-
-// ---- sum of squared differences ------------------------------------------------------------------
-constexpr int kSqBlocks = 256;
-int sqdiff_partials() { return kSqBlocks; }
-
-__global__ __launch_bounds__(kThreads) void sqdiff_partial_kernel(const float* __restrict__ X, int64_t ldx,
-                                                                  const float* __restrict__ Y, int64_t ldy, int rows, int cols,
-                                                                  float* __restrict__ partial) {
-    __shared__ float sh[4];
-    const int64_t total = (int64_t)rows * cols;
-    float s = 0.f;
-    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kThreads) {
-        const int64_t n = e / cols, j = e - n * cols;
-        const float d = X[n * ldx + j] - Y[n * ldy + j];
-        s += d * d;
-    }
-    s = block_sum(s, sh);
-    if (threadIdx.x == 0) partial[blockIdx.x] = s;
-}
-
-int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, int rows, int cols, float* partial,
-                      float* out, hipStream_t s) {
-    hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(kThreads), 0, s, X, ldx, Y, ldy, rows, cols, partial);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return note_hip_error(e);
-    return sum_segments_launch(partial, kSqBlocks, 1, out, s);
 }
 
 // ---- broadcast copy: dst[b*dst_bstride + i] = src[i] -------------------------------------------------

@@ -18,14 +18,11 @@ int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride,
 int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s);
 
 // dst[j] = beta dst[j] + alpha colsum_j(X - Y) over `rows` rows (Y may be null);  dst2[j] += dst[j] (dst2 may be null);
-// xcopy (may be null): receives a copy of X with row stride ldc.
+// xcopy (may be null): receives a copy of X with row stride ldc;  sq_partial (may be null): colsum_blocks(cols)
+// floats, entry w = sum of (X - Y)^2 over the 32 columns of workgroup w (their sum is the squared distance).
+int colsum_blocks(int cols);
 int colsum_axpby_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, float* dst, float* dst2, float* xcopy,
-                        int64_t ldc, int rows, int cols, float alpha, float beta, hipStream_t s);
-
-// out[0] = sum over rows x cols of (X - Y)^2, fixed order; partial: scratch of >= sqdiff_partials() floats.
-int sqdiff_partials();
-int sqdiff_sum_launch(const float* X, int64_t ldx, const float* Y, int64_t ldy, int rows, int cols,
-                      float* partial, float* out, hipStream_t s);
+                        int64_t ldc, float* sq_partial, int rows, int cols, float alpha, float beta, hipStream_t s);
 
 // dst[b*dst_bstride + i] = src[i], i < count, b < batch.
 int copy_bcast_launch(const float* src, int64_t count, float* dst, int64_t dst_bstride, int batch, hipStream_t s);

@@ -2,7 +2,8 @@
 // the Bernoulli sampling fused into the epilogue, reconstruction, hidden probabilities of the
 // reconstruction), ONE statistics GEMM fused with the momentum updates of W and of the hidden bias
 // (positive minus negative phase as one contraction over the stacked rows [P_h0; -P_h1] and [V0; V1]), a
-// column-sum kernel for the visible bias that also stacks V0, and a fixed-order reduction for the reconstruction error.
+// column-sum kernel for the visible bias that also stacks V0 and sums the squared reconstruction error per block of
+// columns, and a fixed-order sum of those.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -33,7 +34,7 @@ RbmWs rbm_ws(int V, int H, int n) {
     w.off_ph = off;  off += round_up((int64_t)2 * n * w.ldh, 64);
     w.off_h0 = off;  off += round_up((int64_t)n * w.ldh, 64);
     w.off_vv = off;  off += round_up((int64_t)2 * n * w.ldv, 64);
-    w.off_part = off; off += round_up(sqdiff_partials(), 64);
+    w.off_part = off; off += round_up(colsum_blocks(V), 64);
     w.off_gemm = off; off += w.gemm_floats;
     w.total = off;
     return w;
@@ -134,9 +135,11 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
     if (dbg_ph0 && note_hip_error(hipMemcpy2DAsync(dbg_ph0, (size_t)H * 4, ph0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (dbg_h0 && note_hip_error(hipMemcpy2DAsync(dbg_h0, (size_t)H * 4, h0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     if (dbg_v1 && note_hip_error(hipMemcpy2DAsync(dbg_v1, (size_t)V * 4, v1, (size_t)lay.ldv * 4, (size_t)V * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
-    if (recon_err && sqdiff_sum_launch(v0, V, v1, lay.ldv, n, V, ws + lay.off_part, recon_err, s) != 0) return MAVG_E_LAUNCH;
     // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma;  the same pass copies V0 under V1's rows' stride
-    if (colsum_axpby_launch(v0, V, v1, lay.ldv, ma, a, vv, lay.ldv, n, V, lr * invn, momentum, s) != 0) return MAVG_E_LAUNCH;
+    // and leaves the squared reconstruction error of each block of 32 columns, summed afterwards in block order
+    if (colsum_axpby_launch(v0, V, v1, lay.ldv, ma, a, vv, lay.ldv, recon_err ? ws + lay.off_part : nullptr, n, V, lr * invn,
+                            momentum, s) != 0) return MAVG_E_LAUNCH;
+    if (recon_err && sum_segments_launch(ws + lay.off_part, colsum_blocks(V), 1, recon_err, s) != 0) return MAVG_E_LAUNCH;
     {   // MW <- momentum MW + (lr/n) (P_h0^T V0 - P_h1^T V1) = momentum MW + (lr/n) [P_h0; -P_h1]^T [V0; V1];  W <- W + MW
         GemmDesc g;
         g.M = H; g.N = V; g.K = 2 * n;
