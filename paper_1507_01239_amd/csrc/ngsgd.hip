@@ -720,7 +720,7 @@ int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s) {
 
 // X <- X + sign * (H or H2) R for every slot
 int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s) {
-    constexpr int kRows = 128;                       // rows a wavefront walks with its block of R in registers
+    constexpr int kRows = 64;                        // rows a wavefront walks with its block of R in registers
     int maxdim = 0;
     for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
     const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((t.n + kRows - 1) / kRows), (unsigned)(t.nslots * t.batch));
