@@ -193,7 +193,8 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
     GemmKParams p = fill_params(d, pl, ws);
     const bool kg_cfg = pl.cfg == 13 || pl.cfg == 14;
-    if (pl.cfg >= 9 && pl.cfg != 12 && !(dma_eligible(d, p) && (!kg_cfg || (!rowsum && d.K / kDmaBK >= kKGroups)))) {
+    if (pl.cfg >= 9 && pl.cfg != 12 &&
+        !(dma_eligible(d, p) && (!kg_cfg || (!rowsum && d.K / (pl.cfg == 13 ? kKgWideBK : kDmaBK) >= kKGroups)))) {
         pl = gemm_plan(d.M, d.N, d.K, d.batch, 8, rowsum ? 1 : d.force_splits);
         p = fill_params(d, pl, ws);
     }

@@ -709,17 +709,28 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(GemmKParams p) {
 // instead of 4 (3 direct loads per wavefront and k-tile instead of 2).
 constexpr int kKGroups = 4;
 
-template <int GW, bool AKC, bool BKC, int KG = kKGroups, int NST = 4>
+// 16-byte chunk q of row r of a k-contiguous tile with BK contraction steps per row sits at chunk position
+// q ^ kc_swizzle<BK>(r).  A ds_read_b128 serves 16 lanes = 16 rows per cycle from 64 banks: with 64-byte rows
+// (BK = 16) rows r, r+4, r+8, r+12 start at the same bank and need four different chunk positions; with 128-byte
+// rows (BK = 32) rows of equal parity do, eight of them.
+template <int BK>
+__device__ __forceinline__ constexpr int kc_swizzle(int r) { return BK == 16 ? (r >> 2) & 3 : (r >> 1) & 7; }
+
+template <int GW, bool AKC, bool BKC, int KG = kKGroups, int NST = 4, int BK = kDmaBK>
 __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int tile, const int bz) {
     // GW wavefronts per k-group: 2 (32x64 tile, one barrier per k-tile) or 1 (32x32 tile: a k-group is a single
-    // wavefront with a ring of its own, so the loop needs no barrier at all, only the wavefront's own vmcnt waits)
-    constexpr int BK = kDmaBK, BM = 32, BN = 32 * GW;
-    constexpr int A_LOADS = 2 / GW, LOADS = A_LOADS + 2;
+    // wavefront with a ring of its own, so the loop needs no barrier at all, only the wavefront's own vmcnt waits).
+    // BK contraction steps per k-tile: 16, or 32 (twice the MFMAs per barrier and per round of loads, waits and
+    // operand reads: the fixed cost of a k-tile, about 160 cycles against 512 of MFMAs at BK = 16, is paid half as often).
+    constexpr int BM = 32, BN = 32 * GW;
     static_assert(GW == 1 || GW == 2, "one or two wavefronts per k-group");
+    static_assert(BK == 16 || BK == 32, "16 or 32 contraction steps per k-tile");
     constexpr int TILE_A = BM * BK, TILE_B = BN * BK;
+    constexpr int A_LOADS = TILE_A / 256 / GW, B_LOADS = TILE_B / 256 / GW, LOADS = A_LOADS + B_LOADS;   // 1 KB each
+    constexpr int NPR = BK / 8;                           // pairs of 16-byte chunks (8 contraction steps) per k-tile
     __shared__ __attribute__((aligned(1024))) float As[KG][NST][TILE_A];
     __shared__ __attribute__((aligned(1024))) float Bs[KG][NST][TILE_B];
-    __shared__ float red[KG - 1][GW][16][64];
+    static_assert(NST * TILE_B >= GW * 1024, "a k-group's B ring must hold its accumulators for the final sum");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kg = wave / GW, gw = wave % GW;
     const int lrow = lane >> 5, lcol = lane & 31;
@@ -728,17 +739,21 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     int tm_i, tn_i;
     tile_coords(p, tile, tm_i, tn_i);
     const int m0 = tm_i * BM, n0 = tn_i * BN;
-    // k-tiles of this k-group: a contiguous share of the K / 16 tiles
+    // k-tiles of this k-group: a contiguous share of the K / BK tiles
     const int nkt_all = p.K / BK, base = nkt_all / KG, rem = nkt_all % KG;
     const int nkt = __builtin_amdgcn_readfirstlane(base + (kg < rem ? 1 : 0));
     const int first = kg * base + min(kg, rem);
     const int nloop = base + (rem > 0 ? 1 : 0);        // every wavefront takes part in this many barriers
     const int kbeg = first * BK;
 
-    // direct loads of this wavefront: unit gw of the A stage (2 units of 256 floats), units gw and gw + 2 of B
+    // Direct loads, in units of 256 floats (1 KB, one load of a wavefront).  k-contiguous operand ([row][BK]): a unit
+    // is 256 / BK rows, lane -> row lane / (BK/4), chunk position lane % (BK/4).  m/n-contiguous operand ([k][BR]): a
+    // unit is 256 / BR k-rows.  The A stage has TILE_A / 256 units, the B stage TILE_B / 256; a wavefront takes units
+    // gw, gw + GW, ...
     auto lane_offset = [&](bool kc, int unit, int BR, int r0, int R, int64_t ld) -> uint32_t {
         if (kc) {
-            const int r = unit * 16 + (lane >> 2), q = (lane & 3) ^ chunk_swizzle(r);
+            constexpr int CPR = BK / 4;                   // chunks per row
+            const int r = unit * (256 / BK) + lane / CPR, q = (lane % CPR) ^ kc_swizzle<BK>(r);
             const int row = min(r0 + r, R - 1);
             return (uint32_t)(((int64_t)row * ld + q * 4) * 4);
         }
@@ -746,13 +761,11 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         const int k = unit * (256 / BR) + lane / per, col = min(r0 + (lane % per) * 4, R - 4);
         return (uint32_t)(((int64_t)k * ld + col) * 4);
     };
-    // units of 256 floats: the A stage has 2 (a wavefront takes unit gw, or both when it is alone in its k-group),
-    // the B stage 2 GW (a wavefront takes units gw and gw + GW)
-    uint32_t voa[A_LOADS];
+    uint32_t voa[A_LOADS], vob[B_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) voa[i] = lane_offset(AKC, gw + i * GW, BM, m0, AKC ? p.M : p.Mr, p.lda);
-    const uint32_t vob0 = lane_offset(BKC, gw, BN, n0, BKC ? p.N : p.Nr, p.ldb);
-    const uint32_t vob1 = lane_offset(BKC, gw + GW, BN, n0, BKC ? p.N : p.Nr, p.ldb);
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) vob[i] = lane_offset(BKC, gw + i * GW, BN, n0, BKC ? p.N : p.Nr, p.ldb);
     const float* sa = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
         p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda))));
     const float* sb = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
@@ -764,22 +777,23 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     auto issue = [&](int t, int stage) {
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i) dma16(voa[i], sa + t * stepa, la + stage * (TILE_A * 4) + i * GW * 1024);
-        dma16(vob0, sb + t * stepb, lb + stage * (TILE_B * 4));
-        dma16(vob1, sb + t * stepb, lb + stage * (TILE_B * 4) + GW * 1024);
+#pragma unroll
+        for (int i = 0; i < B_LOADS; ++i) dma16(vob[i], sb + t * stepb, lb + stage * (TILE_B * 4) + i * GW * 1024);
     };
 
-    int offa[2], offb[2];
+    // operand reads: MFMA step c (0..3) of pair pr multiplies k = 8 pr + c in lanes 0-31 and k = 8 pr + 4 + c in lanes 32-63
+    int offa[NPR], offb[NPR];
 #pragma unroll
-    for (int pr = 0; pr < 2; ++pr) {
+    for (int pr = 0; pr < NPR; ++pr) {
         const int ia = lcol, ib = wn + lcol;
-        offa[pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ chunk_swizzle(ia)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
-        offb[pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ chunk_swizzle(ib)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
+        offa[pr] = AKC ? ia * BK + (((2 * pr + lrow) ^ kc_swizzle<BK>(ia)) * 4) : (8 * pr + 4 * lrow) * BM + ia;
+        offb[pr] = BKC ? ib * BK + (((2 * pr + lrow) ^ kc_swizzle<BK>(ib)) * 4) : (8 * pr + 4 * lrow) * BN + ib;
     }
-    float fa[2][2][4], fb[2][2][4];
+    float fa[2][NPR][4], fb[2][NPR][4];
     auto read_frags = [&](auto setc, auto stagec) {
         constexpr int set = decltype(setc)::value, stage = decltype(stagec)::value;
 #pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
+        for (int pr = 0; pr < NPR; ++pr) {
             if (AKC) {
                 const float4 v = *reinterpret_cast<const float4*>(&As[kg][stage][offa[pr]]);
                 fa[set][pr][0] = v.x; fa[set][pr][1] = v.y; fa[set][pr][2] = v.z; fa[set][pr][3] = v.w;
@@ -816,13 +830,17 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     group_barrier();
     if (nkt > 0) read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    auto multiply = [&](auto setc, auto halfc) {       // one half of the k-tile's MFMAs
+        constexpr int set = decltype(setc)::value, half = decltype(halfc)::value;
+#pragma unroll
+        for (int pr = half * (NPR / 2); pr < (half + 1) * (NPR / 2); ++pr)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][pr][c], fb[set][pr][c], acc[0][0], 0, 0, 0);
+    };
     auto step = [&](auto uc, const int t) {
         constexpr int u = decltype(uc)::value % NST;      // stage of tile t
         constexpr int set = decltype(uc)::value & 1;      // register set of tile t
-        if (t < nkt) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][0][c], fb[set][0][c], acc[0][0], 0, 0, 0);
-        }
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{});
         __builtin_amdgcn_sched_barrier(0);
         if (t + NST - 1 < nkt) {
             issue(t + NST - 1, (u + NST - 1) % NST);
@@ -833,10 +851,7 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         group_barrier();
         if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
         __builtin_amdgcn_sched_barrier(0);
-        if (t < nkt) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][1][c], fb[set][1][c], acc[0][0], 0, 0, 0);
-        }
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{});
         __builtin_amdgcn_sched_barrier(0);
     };
     constexpr int PERIOD = (NST % 2 == 0) ? NST : 2 * NST;      // stages and register sets repeat together
@@ -846,29 +861,33 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         });
     }
 
-    // contraction steps past the last whole k-tile (fewer than 16): the last k-group, straight from global memory
+    // contraction steps past the last whole k-tile (fewer than BK): the last k-group, straight from global memory
     if (kg == KG - 1 && nkt_all * BK < p.K) {
         const float* __restrict__ Ab = p.A + (int64_t)b * p.a_bstride;
         const float* __restrict__ Bb = p.B + (int64_t)b * p.b_bstride;
         const int m = min(m0 + lcol, p.M - 1), n = min(n0 + wn + lcol, p.N - 1);
-        static_for<2>([&](auto prc) {
+        static_for<NPR>([&](auto prc) {
             constexpr int pr = decltype(prc)::value;
-            float ta[4], tb[4];
+            if (nkt_all * BK + 8 * pr < p.K) {        // (uniform) pairs wholly past the end are skipped
+                float ta[4], tb[4];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int k = nkt_all * BK + 8 * pr + 4 * lrow + c;
-                const bool ok = k < p.K;
-                ta[c] = ok ? (AKC ? Ab[(int64_t)m * p.lda + k] : Ab[(int64_t)k * p.lda + m]) : 0.f;
-                tb[c] = ok ? (BKC ? Bb[(int64_t)n * p.ldb + k] : Bb[(int64_t)k * p.ldb + n]) : 0.f;
+                for (int c = 0; c < 4; ++c) {
+                    const int k = nkt_all * BK + 8 * pr + 4 * lrow + c;
+                    const bool ok = k < p.K;
+                    ta[c] = ok ? (AKC ? Ab[(int64_t)m * p.lda + k] : Ab[(int64_t)k * p.lda + m]) : 0.f;
+                    tb[c] = ok ? (BKC ? Bb[(int64_t)n * p.ldb + k] : Bb[(int64_t)k * p.ldb + n]) : 0.f;
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ta[c], tb[c], acc[0][0], 0, 0, 0);
             }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ta[c], tb[c], acc[0][0], 0, 0, 0);
         });
     }
 
-    // add the k-groups' accumulators in group order; every LDS read of the rings is behind the last barrier
+    // Add the k-groups' accumulators in group order.  Every read of the rings is behind the last barrier of the loop
+    // and every load has landed, so a k-group parks its accumulators in its own B ring (1024 floats per wavefront).
+    float* red = &Bs[kg][0][0] + gw * 1024;
     if (kg > 0) {
-        static_for<16>([&](auto vc) { red[kg - 1][gw][decltype(vc)::value][lane] = acc[0][0][decltype(vc)::value]; });
+        static_for<16>([&](auto vc) { red[decltype(vc)::value * 64 + lane] = acc[0][0][decltype(vc)::value]; });
     }
     __syncthreads();
     if (kg > 0) return;
@@ -876,18 +895,22 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         constexpr int v = decltype(vc)::value;
         float r = acc[0][0][v];
 #pragma unroll
-        for (int g = 0; g < KG - 1; ++g) r += red[g][gw][v][lane];
+        for (int g = 1; g < KG; ++g) r += (&Bs[g][0][0] + gw * 1024)[v * 64 + lane];
         acc[0][0][v] = r;
     });
     const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
     MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0, n0 + wn, lrow, lcol)))
 }
 
-// Ring of four stages: a fifth (the 32x64 variant has the LDS for it: 144 KB with the reduction buffer) changed
-// nothing measurable, so the loop is not waiting on the depth of its prefetch.
+// The 32x64 variant (one workgroup per compute unit) takes k-tiles of 32 steps in a ring of three stages (144 KB of
+// LDS); the 32x32 variant keeps 16 steps and four stages so that two workgroups share a compute unit.  A deeper ring
+// at 16 steps changed nothing measurable: the loop was not waiting on the depth of its prefetch but paying a fixed
+// cost per k-tile.
+constexpr int kKgWideBK = 32;
 template <int GW, bool AKC, bool BKC>
 __global__ __launch_bounds__(64 * kKGroups * GW) void gemm_dma_kg_kernel(GemmKParams p) {
-    gemm_dma_kg_body<GW, AKC, BKC, kKGroups, 4>(p, blockIdx.x, blockIdx.z);
+    if constexpr (GW == 2) gemm_dma_kg_body<2, AKC, BKC, kKGroups, 3, kKgWideBK>(p, blockIdx.x, blockIdx.z);
+    else gemm_dma_kg_body<1, AKC, BKC, kKGroups, 4, kDmaBK>(p, blockIdx.x, blockIdx.z);
 }
 
 // Several independent problems of the same operand layout in one launch (e.g. the weight gradients of all
