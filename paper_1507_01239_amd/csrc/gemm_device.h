@@ -466,6 +466,23 @@ __device__ __forceinline__ void dma16(uint32_t voff, const float* sbase, uint32_
                  : "memory");
 }
 
+// The same load with the LDS base already in M0 and an immediate offset OFF (0 .. 4095 bytes) that the hardware adds
+// to BOTH the global address and the LDS address: several loads of a k-tile share one M0 value (their LDS
+// destinations OFF apart) and their per-lane offsets are prepared OFF smaller, which takes the M0 traffic (save,
+// set, hazard nop, restore: four scalar instructions per load) out of the loop.
+__device__ __forceinline__ uint32_t m0_swap(uint32_t v) {
+    uint32_t old;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0" : "=&s"(old) : "s"(v) : "memory");
+    return old;
+}
+__device__ __forceinline__ void m0_set(uint32_t v) { asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" ::"s"(v) : "memory"); }
+template <int OFF>
+__device__ __forceinline__ void dma16_m0(uint32_t voff, const float* sbase) {
+    static_assert(OFF >= 0 && OFF < 4096, "immediate offset of a global load");
+    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(voff), "s"(sbase), "n"(OFF) : "memory");
+}
+constexpr int kDmaBias = 4096;      // bytes: per-lane offsets are kept this much larger, the scalar base this much smaller
+
 // Pin a workgroup-uniform 64-bit value to scalar registers (the compiler cannot always prove uniformity, e.g.
 // for fields of a kernel-argument array indexed by the workgroup's group number).
 __device__ __forceinline__ uint64_t uniform_u64(uint64_t x) {
@@ -761,24 +778,38 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         const int k = unit * (256 / BR) + lane / per, col = min(r0 + (lane % per) * 4, R - 4);
         return (uint32_t)(((int64_t)k * ld + col) * 4);
     };
+    // Loads 2j and 2j+1 of an operand share one M0 value: the odd one lands GW KB further on through its immediate
+    // offset, and fetches from an address prepared that much smaller.
+    constexpr int PAIR_OFF = GW * 1024;
+    static_assert(A_LOADS <= 2 && B_LOADS % 2 == 0, "loads are issued in pairs that share an LDS base");
     uint32_t voa[A_LOADS], vob[B_LOADS];
 #pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) voa[i] = lane_offset(AKC, gw + i * GW, BM, m0, AKC ? p.M : p.Mr, p.lda);
+    for (int i = 0; i < A_LOADS; ++i)
+        voa[i] = lane_offset(AKC, gw + i * GW, BM, m0, AKC ? p.M : p.Mr, p.lda) + kDmaBias - (i & 1) * PAIR_OFF;
 #pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) vob[i] = lane_offset(BKC, gw + i * GW, BN, n0, BKC ? p.N : p.Nr, p.ldb);
+    for (int i = 0; i < B_LOADS; ++i)
+        vob[i] = lane_offset(BKC, gw + i * GW, BN, n0, BKC ? p.N : p.Nr, p.ldb) + kDmaBias - (i & 1) * PAIR_OFF;
     const float* sa = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
-        p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda))));
+        p.A + (int64_t)b * p.a_bstride + (AKC ? (int64_t)kbeg : (int64_t)kbeg * p.lda) - kDmaBias / 4)));
     const float* sb = reinterpret_cast<const float*>(uniform_u64(reinterpret_cast<uint64_t>(
-        p.B + (int64_t)b * p.b_bstride + (BKC ? (int64_t)kbeg : (int64_t)kbeg * p.ldb))));
+        p.B + (int64_t)b * p.b_bstride + (BKC ? (int64_t)kbeg : (int64_t)kbeg * p.ldb) - kDmaBias / 4)));
     const int64_t stepa = (int64_t)uniform_u64((uint64_t)(AKC ? BK : BK * p.lda));
     const int64_t stepb = (int64_t)uniform_u64((uint64_t)(BKC ? BK : BK * p.ldb));
     const uint32_t la = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&As[kg][0][gw * 256]);
     const uint32_t lb = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)&Bs[kg][0][gw * 256]);
     auto issue = [&](int t, int stage) {
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) dma16(voa[i], sa + t * stepa, la + stage * (TILE_A * 4) + i * GW * 1024);
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) dma16(vob[i], sb + t * stepb, lb + stage * (TILE_B * 4) + i * GW * 1024);
+        const float* ga = sa + t * stepa;
+        const float* gb = sb + t * stepb;
+        const uint32_t saved_m0 = m0_swap(la + stage * (TILE_A * 4));
+        dma16_m0<0>(voa[0], ga);
+        if constexpr (A_LOADS == 2) dma16_m0<PAIR_OFF>(voa[1], ga);
+        static_for<B_LOADS / 2>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            m0_set(lb + stage * (TILE_B * 4) + j * 2 * PAIR_OFF);
+            dma16_m0<0>(vob[2 * j], gb);
+            dma16_m0<PAIR_OFF>(vob[2 * j + 1], gb);
+        });
+        m0_set(saved_m0);
     };
 
     // operand reads: MFMA step c (0..3) of pair pr multiplies k = 8 pr + c in lanes 0-31 and k = 8 pr + 4 + c in lanes 32-63
