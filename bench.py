@@ -24,8 +24,8 @@ PEAK_FP32_MFMA_TFLOPS = 157.3     # 256 CU x 4 SIMD x 64 FLOP/cycle x 2.4 GHz
 PEAK_HBM_GBPS = 8000.0
 # HBM-side traffic of one launch of the roofline kernel (256 x 8000 x 2048 forward GEMM), from the two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy of known size) summarised in
-# profiles/gemm_output_layer_forward_hbm_counters.md: 98.8 MB fetched + 8.2 MB written.
-ROOFLINE_TRAFFIC_BYTES = {256: 107.0e6}
+# profiles/gemm_output_layer_forward_hbm_counters.md: 99.1 MB fetched + 8.2 MB written.
+ROOFLINE_TRAFFIC_BYTES = {256: 107.3e6}
 
 
 def log(msg):
