@@ -202,7 +202,7 @@ def main():
 
     if not args.no_extras:
         # NG-SGD step against the plain SGD step at minibatch 512, rank 30 (one replica)
-        def train_ms(nb, use_ng):
+        def train_ms(nb, use_ng, fold_every=1):
             xb = torch.from_numpy(gen.features_speech_like(nb, dims[0], seed, 1, 0)).cuda()
             yb = torch.from_numpy(gen.labels_zipf(nb, dims[-1], seed, 1, 0)).cuda()
             th = torch.from_numpy(theta0).cuda()
@@ -218,17 +218,19 @@ def main():
                     B.ngsgd_state_init(st_[2 * (l - 1)], dims[l - 1] + 1, 30)
                     B.ngsgd_state_init(st_[2 * (l - 1) + 1], dims[l], 30)
                 kw = dict(ng_state=st_, ng_state_stride=sb, ng_rank=30, ng_alpha=4.0, ng_eta=1.0 - float(np.exp(-nb / 2000.0)))
-            def one(first):
+            def one(first, i=0):
+                extra = 0
+                if use_ng:
+                    extra = B.NG_FIRST if first else (0 if i % fold_every == 0 else B.NG_APPLY_ONLY)
                 B.dnn_forward(shape, 1, th, P, xb, 0, nb, ac, 0, w2)
-                B.dnn_backward_update(shape, 1, th, P, xb, 0, yb, 0, nb, ac, 0, lr, fl | (B.NG_FIRST if (use_ng and first) else 0),
-                                      None, w2, **kw)
+                B.dnn_backward_update(shape, 1, th, P, xb, 0, yb, 0, nb, ac, 0, lr, fl | extra, None, w2, **kw)
             one(True)
             warm_clocks(0.2)
-            for _ in range(3):
-                one(False)
+            for i in range(3):
+                one(False, i)
             e0.record()
-            for _ in range(20):
-                one(False)
+            for i in range(20):
+                one(False, i)
             e1.record()
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / 20
@@ -306,10 +308,12 @@ def main():
             extras["paper_shape_440_6x2048_8806_mb1024"] = paper_shape()
             log(f"paper shape: {extras['paper_shape_440_6x2048_8806_mb1024']}")
         if want("ngsgd"):
-            sgd_ms, ng_ms = train_ms(512, False), train_ms(512, True)
+            sgd_ms, ng_ms, ng4_ms = train_ms(512, False), train_ms(512, True), train_ms(512, True, 4)
             extras["ngsgd_mb512_rank30"] = {"sgd_ms": round(sgd_ms, 4), "ngsgd_ms": round(ng_ms, 4),
                                             "overhead": round(ng_ms / sgd_ms - 1.0, 4),
-                                            "ngsgd_frames/s": round(512 / ng_ms * 1e3, 1)}
+                                            "ngsgd_frames/s": round(512 / ng_ms * 1e3, 1),
+                                            "ngsgd_fold_every_4th_minibatch_ms": round(ng4_ms, 4),
+                                            "overhead_fold_every_4th": round(ng4_ms / sgd_ms - 1.0, 4)}
             log(f"ngsgd: {extras['ngsgd_mb512_rank30']}")
 
     cpu_baseline = None

@@ -49,6 +49,9 @@ extern "C" {
 #define MAVG_USE_NGSGD    2u    /* precondition each layer's gradient factors (needs ng_state)   */
 #define MAVG_NG_FIRST     4u    /* with MAVG_USE_NGSGD: first minibatch on freshly initialised
                                    states (each state is folded three times before it is applied) */
+#define MAVG_NG_APPLY_ONLY 8u   /* with MAVG_USE_NGSGD: precondition with the states as they are and
+                                   leave them unchanged (a caller that folds only every few
+                                   minibatches sets it on the others); not together with MAVG_NG_FIRST */
 
 /* ngsgd_precondition `update` modes */
 #define MAVG_NG_APPLY        0  /* precondition only                                             */
@@ -112,7 +115,9 @@ int32_t dnn_forward(const mavg_shape* shape, int32_t k,
  *                  W_l <- W_l - lr G_l,  b_l <- b_l - lr g_l
  * With MAVG_USE_NGSGD the two factors [A_{l-1}, 1] and delta_l are passed through
  * ngsgd_precondition (Sec. 4, eq. 4) before they are multiplied; the delta that is propagated
- * downwards is not.
+ * downwards is not.  Every call folds its minibatch into the 2*L states (update mode MAVG_NG_UPDATE;
+ * MAVG_NG_INIT_UPDATE with MAVG_NG_FIRST) unless MAVG_NG_APPLY_ONLY is set (mode MAVG_NG_APPLY: the
+ * states are read and left as they are).
  *   labels    device int32, n per replica, replica r at labels + r*label_stride; each in [0, d_L)
  *             (an out-of-range label contributes no "-1" and no loss; it is not detected)
  *   ng_state  device, required with MAVG_USE_NGSGD: for each replica r, 2*L states laid out as

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libmavg.so")
 
 OK, E_NULL, E_DIM, E_ALIGN, E_FLAG, E_LAUNCH, E_WORKSPACE = 0, -1, -2, -3, -4, -5, -6
 ACT_SIGMOID, ACT_TANH = 0, 1
-MEAN_GRAD, USE_NGSGD, NG_FIRST = 1, 2, 4
+MEAN_GRAD, USE_NGSGD, NG_FIRST, NG_APPLY_ONLY = 1, 2, 4, 8
 VIS_BERNOULLI, VIS_GAUSSIAN = 0, 1
 SAMPLE_V1 = 1
 NG_APPLY, NG_UPDATE, NG_INIT_UPDATE = 0, 1, 2

@@ -110,7 +110,8 @@ extern "C" int64_t mavg_workspace_bytes(const mavg_shape* shape, int32_t n, int3
     const int rc = check_shape(shape);
     if (rc) return rc;
     if (n < 1 || k < 1) return MAVG_E_DIM;
-    if (flags & ~(MAVG_MEAN_GRAD | MAVG_USE_NGSGD | MAVG_NG_FIRST)) return MAVG_E_FLAG;
+    if (flags & ~(MAVG_MEAN_GRAD | MAVG_USE_NGSGD | MAVG_NG_FIRST | MAVG_NG_APPLY_ONLY)) return MAVG_E_FLAG;
+    if ((flags & MAVG_NG_FIRST) && (flags & MAVG_NG_APPLY_ONLY)) return MAVG_E_FLAG;
     if ((flags & MAVG_USE_NGSGD) && (ng_rank < 1 || ng_rank > 64)) return MAVG_E_DIM;
     const Layout y = make_layout(shape, n);
     return make_workspace(y, n, k, flags, ng_rank).total_floats * 4 + 256;
@@ -173,7 +174,8 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
     int rc = check_common(shape, k, theta, theta_stride, x, x_stride, n, acts, act_stride, &y);
     if (rc) return rc;
     if (!labels) return MAVG_E_NULL;
-    if (flags & ~(MAVG_MEAN_GRAD | MAVG_USE_NGSGD | MAVG_NG_FIRST)) return MAVG_E_FLAG;
+    if (flags & ~(MAVG_MEAN_GRAD | MAVG_USE_NGSGD | MAVG_NG_FIRST | MAVG_NG_APPLY_ONLY)) return MAVG_E_FLAG;
+    if ((flags & MAVG_NG_FIRST) && (flags & MAVG_NG_APPLY_ONLY)) return MAVG_E_FLAG;
     if (k > 1 && label_stride != 0 && label_stride < n) return MAVG_E_ALIGN;
     const bool ng = (flags & MAVG_USE_NGSGD) != 0;
     if (ng) {
@@ -246,13 +248,14 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
             a.state_out = static_cast<char*>(ng_state) + (int64_t)(2 * (l - 1) + 1) * ng_state_stride;
             a.state_rstride = (int64_t)2 * y.L * ng_state_stride;
             a.rank = ng_rank; a.alpha = ng_alpha; a.eta = ng_eta; a.lr = lr;
-            a.mode = (flags & MAVG_NG_FIRST) ? 2 : 1;
+            a.mode = (flags & MAVG_NG_FIRST) ? 2 : (flags & MAVG_NG_APPLY_ONLY) ? 0 : 1;
             a.ws = ws + w.off_ng; a.ws_floats = w.ng_floats;
             a.gemm_ws = gws; a.gemm_ws_floats = w.gemm_floats;
             if ((flags & MAVG_NG_FIRST) && ng_layer_update(a, s) != 0) return MAVG_E_LAUNCH;
         }
         if (!(flags & MAVG_NG_FIRST) && ng_dnn_update(la, y.L, s) != 0) return MAVG_E_LAUNCH;
-        if (ng_dnn_finish(y.d, y.L, n, k, ng_rank, ng_eta, static_cast<char*>(ng_state), ng_state_stride, ws + w.off_ng, s) != 0)
+        if (!(flags & MAVG_NG_APPLY_ONLY) &&
+            ng_dnn_finish(y.d, y.L, n, k, ng_rank, ng_eta, static_cast<char*>(ng_state), ng_state_stride, ws + w.off_ng, s) != 0)
             return MAVG_E_LAUNCH;
     }
     return MAVG_OK;

@@ -14,7 +14,7 @@ struct NgLayerArgs {
     float* W; float* b; int64_t theta_stride;          // d_out x d_in weights, d_out biases
     char* state_in; char* state_out; int64_t state_rstride;   // replica r's states at + r*state_rstride bytes
     int rank; float alpha, eta, lr;
-    int mode;                                           // 1 apply + fold, 2 first minibatch (three folds first)
+    int mode;                                           // 0 apply only, 1 apply + fold, 2 first minibatch (three folds first)
     float* ws; int64_t ws_floats;
     float* gemm_ws; int64_t gemm_ws_floats;
 };
@@ -25,7 +25,7 @@ int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank);
 // left pending (their Y matrices stay in the scratch) until ng_dnn_finish.
 int ng_layer_update(const NgLayerArgs& a, hipStream_t s);
 // The same for all layers of the network at once (layers[l - 1] describes layer l; all share k, n, rank, alpha, eta,
-// ws): one launch per step of the recipe instead of one per step and layer side.  Steady state only (mode 1).
+// ws): one launch per step of the recipe instead of one per step and layer side.  Modes 0 and 1.
 int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s);
 // Fold this minibatch into all 2*L*k states (after ng_layer_update has run for every layer).
 int ng_dnn_finish(const int* d, int L, int n, int k, int rank, float eta, char* ng_state, int64_t state_stride, float* ws,

@@ -997,7 +997,7 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
         float* P = ws + lay.hp_off;                      // partial products [problem][replica][n x ldr]
         NG_CHECK(ng_slots_norms(t, 0, a0.alpha, a0.eta, s));
         NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
-        {   // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it
+        if (a0.mode >= 1) {   // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it
             GemmDesc g[kNgSlots];
             for (int j = 0; j < t.nslots; ++j) {
                 GemmDesc& q = g[j];

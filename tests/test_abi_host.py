@@ -55,7 +55,8 @@ def test_bad_shapes_are_rejected():
     assert _rc(B.mavg_param_count, B.Shape((4, 0, 3))) == B.E_DIM
     assert _rc(B.mavg_act_count, B.Shape((4, 3)), 0) == B.E_DIM
     assert _rc(B.mavg_workspace_bytes, B.Shape((4, 3)), 8, 0) == B.E_DIM
-    assert _rc(B.mavg_workspace_bytes, B.Shape((4, 3)), 8, 1, 8) == B.E_FLAG
+    assert _rc(B.mavg_workspace_bytes, B.Shape((4, 3)), 8, 1, 16) == B.E_FLAG
+    assert _rc(B.mavg_workspace_bytes, B.Shape((4, 3)), 8, 1, B.USE_NGSGD | B.NG_FIRST | B.NG_APPLY_ONLY, 2) == B.E_FLAG
     assert _rc(B.mavg_param_count, B.Shape(tuple([3] * 70))) == B.E_DIM  # too many layers
     assert _rc(B.mavg_param_count, B.Shape((4, 3), hidden_act=7)) == B.E_FLAG      # unknown nonlinearity
     assert B.mavg_param_count(B.Shape((4, 3), hidden_act=B.ACT_TANH)) == 15
@@ -78,7 +79,8 @@ def test_dnn_calls_validate_before_touching_the_device():
                           ng_state=kw.get("ng", None), ng_rank=kw.get("rank", 0), ng_state_stride=kw.get("ngs", 0),
                           ng_eta=0.1)
     assert bw(labels=None) == B.E_NULL
-    assert bw(flags=8) == B.E_FLAG
+    assert bw(flags=16) == B.E_FLAG
+    assert bw(flags=B.USE_NGSGD | B.NG_FIRST | B.NG_APPLY_ONLY) == B.E_FLAG     # the first minibatch always folds
     assert bw(ws=None) == B.E_WORKSPACE
     assert bw(wb=16) == B.E_WORKSPACE
     assert bw(flags=3) == B.E_NULL                      # NG-SGD without a state

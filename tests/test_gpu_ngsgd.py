@@ -124,13 +124,15 @@ class NgGpu:
                 B.ngsgd_state_init(self.states[(r * 2 * L) + 2 * (l - 1) + 1], dims[l], rank)
         self.first = True
 
-    def step(self, X, Y, lr, eta):
+    def step(self, X, Y, lr, eta, fold=True):
         B = self.B
         x = dev(X.reshape(self.k, -1))
         y = dev(Y.reshape(self.k, -1).astype(np.int32))
         B.dnn_forward(self.shape, self.k, self.theta, self.stride, x, x.shape[1], self.n, self.acts, self.act_stride, self.ws)
         B.dnn_backward_update(self.shape, self.k, self.theta, self.stride, x, x.shape[1], y, y.shape[1], self.n, self.acts,
-                              self.act_stride, lr, self.flags | (B.NG_FIRST if self.first else 0), self.loss, self.ws,
+                              self.act_stride, lr,
+                              self.flags | (B.NG_FIRST if self.first else 0) | (0 if (fold or self.first) else B.NG_APPLY_ONLY),
+                              self.loss, self.ws,
                               ng_state=self.states, ng_state_stride=self.sb, ng_rank=self.rank, ng_alpha=4.0, ng_eta=eta)
         self.first = False
 
@@ -139,17 +141,20 @@ class NgGpu:
         return host(self.theta[:, :self.P])
 
 
-def _oracle_ng_run(dims, theta0, shards, lr, rank, eta):
+def _oracle_ng_run(dims, theta0, shards, lr, rank, eta, fold=None):
+    # fold[t] False: minibatch t is preconditioned with the states as they are and not folded into them
     K, T = len(shards), len(shards[0])
     out = []
     for k in range(K):
         s_in = [ngsgd.init_state(dims[l - 1] + 1, rank) for l in range(1, len(dims))]
         s_out = [ngsgd.init_state(dims[l], rank) for l in range(1, len(dims))]
         pre = ngsgd.make_layer_preconditioner(s_in, s_out, 4.0, eta)
+        pre_apply = ngsgd.make_layer_preconditioner(s_in, s_out, 4.0, eta, update=False)      # same state lists
         th = theta0.astype(np.float64)
         traj = []
         for t in range(T):
-            th, _, _ = dnn.sgd_step(th, dims, shards[k][t][0], shards[k][t][1], lr, precondition=pre)
+            p_t = pre if (fold is None or fold[t]) else pre_apply
+            th, _, _ = dnn.sgd_step(th, dims, shards[k][t][0], shards[k][t][1], lr, precondition=p_t)
             traj.append(th.copy())
         out.append((traj, s_in, s_out))
     return out
@@ -196,6 +201,33 @@ def test_ng_training_step_mixed_widths_rank_above_32():
             assert rel_err(th[k] - prev, ref[k][0][t] - prev) < 5e-4, (t, k)
             assert rel_err(th[k], ref[k][0][t]) < 1e-5
     L = len(dims) - 1
+    for k in range(K):
+        for l in range(1, L + 1):
+            check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, ref[k][1][l - 1], tol=5e-3)
+            check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, ref[k][2][l - 1], tol=5e-3)
+
+
+def test_ng_training_with_folds_on_some_minibatches_only():
+    # the states are folded on minibatches 0, 1 and 4 only; 2, 3 and 5 are preconditioned with the states as they are
+    dims, K, n, lr, rank, eta, seed = [70, 130, 96, 40], 2, 64, 0.05, 12, 0.2, 13
+    fold = [True, True, False, False, True, False]
+    T = len(fold)
+    theta0 = gen.init_theta(dims, seed, 0.1)
+    shards = [[(gen.features_iid(n, dims[0], seed, k, t), gen.labels_uniform(n, dims[-1], seed, k, t)) for t in range(T)]
+              for k in range(K)]
+    ref = _oracle_ng_run(dims, theta0, shards, lr, rank, eta, fold)
+    g = NgGpu(dims, K, n, theta0, rank)
+    L = len(dims) - 1
+    for t in range(T):
+        before = host(g.states).copy() if not fold[t] else None
+        g.step(np.stack([shards[k][t][0] for k in range(K)]), np.stack([shards[k][t][1] for k in range(K)]), lr, eta, fold=fold[t])
+        th = g.params()
+        if not fold[t]:
+            assert np.array_equal(host(g.states), before)          # apply-only leaves every state bit for bit
+        for k in range(K):
+            prev = theta0.astype(np.float64) if t == 0 else ref[k][0][t - 1]
+            assert rel_err(th[k] - prev, ref[k][0][t] - prev) < 5e-4, (t, k)
+            assert rel_err(th[k], ref[k][0][t]) < 1e-5
     for k in range(K):
         for l in range(1, L + 1):
             check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, ref[k][1][l - 1], tol=5e-3)
