@@ -14,7 +14,8 @@ Modules (each function cites the passage of the paper it follows):
 Pins (tests/test_oracle_*.py, run without a GPU): finite differences, softmax
 identities, closed-form logistic regression, the averaging/gradient-averaging
 identity of Sec. 3, brute-force CD-1 expectation on a 4x3 RBM, Philox known
-answers, and dense-matrix checks of the NG-SGD algebra.  The NG-SGD constants,
-initialisation and flooring follow a reading of the cited algorithm that the
-paper itself does not print: for those details, parity unpinned.
+answers, dense-matrix checks of the NG-SGD algebra, hand-worked examples of its
+floors and a dense replay of its first call.  That the NG-SGD constants,
+initial state and number of initial folds are those of the cited algorithm
+(the paper itself does not print them): parity unpinned.
 """

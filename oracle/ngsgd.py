@@ -4,8 +4,11 @@ The paper (Sec. 4, eq. 4) replaces the scalar learning rate by alpha_t * E_t wit
 positive definite, standing for the inverse Fisher matrix (eq. 5), which is "approximated
 directly"; every detail is left to the cited NG-SGD work.  This module fixes one concrete
 reading of that online scheme, in this build's own notation; the HIP path implements the same
-steps and parity is defined against THIS list.  Constants, initialisation and flooring:
-parity unpinned (the paper does not print them); the algebra is pinned by dense checks.
+steps and parity is defined against THIS list.  That the constants (alpha = 4, the 2000-frame
+forgetting constant, EPS, DELTA, C_FLOOR), the initial state and the three initial folds are those
+of the cited algorithm: parity unpinned (the paper does not print them).  What this module does
+with them is pinned: the algebra by dense checks, the floors by hand-worked examples, the first
+call by three dense subspace iterations written without this module's fold.
 
 Per preconditioned matrix X (N rows of dimension D: a layer's input activations with a 1
 appended, or its output derivatives), rank R < D, the state is
