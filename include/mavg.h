@@ -18,7 +18,9 @@
  *     strides are counted in elements.
  *   - Workspace: the caller passes a device scratch buffer of at least the size the matching
  *     *_workspace_bytes() query returns; its contents are undefined on entry and exit.
- *   - No reduction uses atomics: results are bitwise reproducible run to run on the same device.
+ *   - No floating-point reduction uses atomics (every such sum has one owner and a fixed order), so results are
+ *     bitwise reproducible run to run on the same device.  The only atomic is the integer count of
+ *     dnn_count_correct, whose result does not depend on the order of the additions.
  *
  * Parameter vector ("theta") of a network with widths d_0..d_L:
  *     [ W_1 | b_1 | W_2 | b_2 | ... | W_L | b_L ],   W_l is d_l x d_{l-1} row-major (row = output unit).
@@ -118,7 +120,8 @@ int32_t dnn_forward(const mavg_shape* shape, int32_t k,
  * downwards is not.  Every call folds its minibatch into the 2*L states (update mode MAVG_NG_UPDATE;
  * MAVG_NG_INIT_UPDATE with MAVG_NG_FIRST) unless MAVG_NG_APPLY_ONLY is set (mode MAVG_NG_APPLY: the
  * states are read and left as they are).
- *   labels    device int32, n per replica, replica r at labels + r*label_stride; each in [0, d_L)
+ *   labels    device int32, n per replica, replica r at labels + r*label_stride (label_stride >= n, or 0 to share
+ *             one label vector); each in [0, d_L)
  *             (an out-of-range label contributes no "-1" and no loss; it is not detected)
  *   ng_state  device, required with MAVG_USE_NGSGD: for each replica r, 2*L states laid out as
  *             [in_1, out_1, in_2, out_2, ...], state (r, j) at ng_state + (r*2L + j)*ng_state_stride
@@ -163,15 +166,31 @@ int32_t replicas_average(float* theta, int64_t theta_stride, int64_t count, int3
  *   u = (word >> 8) * 2^-24.
  *   w n_hid x n_vis; a n_vis; c n_hid; mw, ma, mc momentum buffers of the same sizes (all device, in place)
  *   v0 device n x n_vis;  recon_err device float, nullable
- *   dbg_h0 / dbg_v1 device, nullable: receive H0 (n x n_hid) and V1 (n x n_vis) for inspection.
+ * Errors: MAVG_E_NULL, MAVG_E_DIM, MAVG_E_FLAG (unknown vis_type or flag; MAVG_SAMPLE_V1 with Gaussian visibles),
+ * MAVG_E_ALIGN, MAVG_E_WORKSPACE, MAVG_E_LAUNCH.
  */
 int64_t rbm_workspace_bytes(int32_t n_vis, int32_t n_hid, int32_t n);
 int32_t rbm_cd1_step(int32_t n_vis, int32_t n_hid, int32_t vis_type,
                      float* w, float* a, float* c, float* mw, float* ma, float* mc,
                      const float* v0, int32_t n, float lr, float momentum,
                      uint64_t seed, uint32_t step, uint32_t layer, uint32_t flags,
-                     float* recon_err, float* dbg_ph0, float* dbg_h0, float* dbg_v1,
-                     void* workspace, int64_t workspace_bytes, void* stream);
+                     float* recon_err, void* workspace, int64_t workspace_bytes, void* stream);
+/*
+ * Where rbm_cd1_step leaves the intermediate matrices of its last call inside the workspace, for a caller that
+ * wants to look at them afterwards (they stay valid until the workspace is used again).  out: host, 8 entries =
+ * (byte offset from the workspace pointer rounded up to a multiple of 256, row stride in floats) of
+ *   P_h0 (n x n_hid), H0 (n x n_hid, 0.0 / 1.0), V1 (n x n_vis), -P_h1 (n x n_hid, stored negated), in this order.
+ * Host only; MAVG_E_NULL / MAVG_E_DIM on invalid arguments.
+ */
+int32_t rbm_workspace_layout(int32_t n_vis, int32_t n_hid, int32_t n, int64_t* out);
+/*
+ * The generator of the sampler by itself (Sec. 5.1 pretraining draws its Bernoulli decisions from it):
+ * out[4 i .. 4 i + 3] (device, uint32, 16-byte aligned) <- Philox4x32-10 block of counter
+ * (first_block + i mod 2^32, step, layer, phase) under key (seed lo32, seed hi32), for i in [0, nblocks).
+ * Errors: MAVG_E_NULL, MAVG_E_DIM (nblocks < 0 or > 2^32), MAVG_E_ALIGN, MAVG_E_LAUNCH.
+ */
+int32_t mavg_philox_fill(uint32_t* out, int64_t nblocks, uint32_t first_block, uint64_t seed, uint32_t step,
+                         uint32_t layer, uint32_t phase, void* stream);
 /* hidden probabilities sigmoid(V W^T + c) of a trained RBM (the next RBM's input when stacking). */
 int32_t rbm_hidden_prob(int32_t n_vis, int32_t n_hid, const float* w, const float* c,
                         const float* v, int32_t n, float* out,
@@ -195,7 +214,7 @@ int32_t dnn_init_layer_from_rbm(const mavg_shape* shape, int32_t k, float* theta
  * correct[r] (device, int32[k], overwritten) <- number of rows i < n of replica r whose largest posterior
  * acts_L(i, :) (as left by dnn_forward; lowest class index among equal maxima) is labels[r*label_stride + i].
  * The comparison is made on the float32 posteriors.  acts / act_stride / labels / label_stride as in
- * dnn_backward_update.  Asynchronous on `stream`.
+ * dnn_backward_update (label_stride 0: all replicas share one label vector).  Asynchronous on `stream`.
  * Errors: MAVG_E_NULL, MAVG_E_DIM, MAVG_E_ALIGN (strides too small for k > 1), MAVG_E_LAUNCH.
  */
 int32_t dnn_count_correct(const mavg_shape* shape, int32_t k, const float* acts, int64_t act_stride,
@@ -207,7 +226,10 @@ int32_t dnn_count_correct(const mavg_shape* shape, int32_t k, const float* acts,
  * State blob (device, caller-owned, 16-byte aligned), for dimension `dim` and rank `rank` < dim:
  *   float  R[rank][ld]  (ld = dim rounded up to a multiple of 4; rows orthonormal)
  *   double d[rank]; double rho; int64 t          -- Fisher estimate F = R^T diag(d) R + rho I
- * ngsgd_state_init writes R = [I 0], d = rho = 1e-10, t = 0.
+ *   int32 sweeps; int32 unconverged               -- Jacobi sweeps the last fold took; number of folds so far whose
+ *                                                    eigen-decomposition used all 14 sweeps without meeting its stop
+ *                                                    test (off-diagonal norm <= 1e-13 of the diagonal's): 0 is healthy
+ * ngsgd_state_init writes R = [I 0], d = rho = 1e-10, t = 0, sweeps = unconverged = 0.
  *
  * ngsgd_precondition, on x (device, n x dim, row stride ldx >= dim), in place:
  *   update = MAVG_NG_INIT_UPDATE (the caller's first minibatch on a fresh state; the library never reads the
@@ -234,15 +256,15 @@ int32_t ngsgd_precondition(void* state, int32_t dim, int32_t rank,
  *   C(m,n) = c[m*ldc + n]
  *   epi: 0  C = v            1  C = v + bias[n]          2  C = alpha*sigmoid(v + bias[n])
  *        3  C = v * aux(m,n) * (1 - aux(m,n))            4  C = beta*C + alpha*v
- *   cfg: -1 = choose the kernel, else its index:
- *        1  64x64 tiles, operands loaded global -> LDS directly when they allow it (16-byte aligned rows, k a
+ *   cfg: -1 = choose the kernel, else:
+ *        0  64x64 tiles, operands loaded global -> LDS directly when they allow it (16-byte aligned rows, k a
  *           multiple of 16, widths of m/n-contiguous operands multiples of 4), else through registers
- *        8  64x64 tiles, always through registers (guarded loads: any shape and alignment);  2  128x128 likewise
- *        9 / 10 / 11  direct-to-LDS 128x64 / 64x128 / 128x128 tiles;  12  as 1 with a shallower LDS ring
- *        13 / 14  direct-to-LDS 32x64 / 32x32 tiles whose contraction is split four ways inside the workgroup
- *        (9..14 run as 8 when the operands do not allow direct loads; 0 and 3..7 are retired aliases of 2 and 8)
+ *        1  64x64 tiles, always through registers (guarded loads: any shape and alignment);  2  128x128 likewise
+ *        3 / 4 / 5  direct-to-LDS 128x64 / 64x128 / 128x128 tiles;  6  as 0 with a shallower LDS ring
+ *        7 / 8  direct-to-LDS 32x64 / 32x32 tiles whose contraction is split four ways inside the workgroup
+ *        (3, 4, 5, 7, 8 run as 1 when the operands do not allow direct loads)
  *   splits: 0 = choose how many ways the contraction is split across workgroups (partial sums are combined
- *   in split order by a second kernel), else that many; ignored by 13 and 14.
+ *   in split order by a second kernel), else that many; ignored by 7 and 8.
  * All pointers device.  Results are bitwise reproducible for a given (shape, cfg, splits).
  */
 int64_t mavg_gemm_workspace_bytes(int32_t m, int32_t n, int32_t k, int32_t cfg, int32_t splits);

@@ -74,7 +74,9 @@ _SIG = {
     "dnn_count_correct": (_i32, [_p, _i32, _p, _i64, _p, _i64, _i32, _p, _p]),
     "rbm_workspace_bytes": (_i64, [_i32, _i32, _i32]),
     "rbm_cd1_step": (_i32, [_i32, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _i32, _f, _f, _u64, _u32, _u32, _u32,
-                            _p, _p, _p, _p, _p, _i64, _p]),
+                            _p, _p, _i64, _p]),
+    "rbm_workspace_layout": (_i32, [_i32, _i32, _i32, _p]),
+    "mavg_philox_fill": (_i32, [_p, _i64, _u32, _u64, _u32, _u32, _u32, _p]),
     "rbm_hidden_prob": (_i32, [_i32, _i32, _p, _p, _p, _i32, _p, _p, _i64, _p]),
     "ngsgd_state_bytes": (_i64, [_i32, _i32]),
     "ngsgd_workspace_bytes": (_i64, [_i32, _i32, _i32]),
@@ -175,11 +177,23 @@ def rbm_workspace_bytes(n_vis, n_hid, n) -> int:
 
 
 def rbm_cd1_step(n_vis, n_hid, vis_type, w, a, c, mw, ma, mc, v0, n, lr, momentum, seed, step, layer, flags,
-                 recon_err, workspace, dbg_ph0=None, dbg_h0=None, dbg_v1=None, stream=None, workspace_bytes=None):
+                 recon_err, workspace, stream=None, workspace_bytes=None):
     wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     return _check(lib.rbm_cd1_step(n_vis, n_hid, vis_type, ptr(w), ptr(a), ptr(c), ptr(mw), ptr(ma), ptr(mc), ptr(v0), n,
-                                   lr, momentum, seed, step, layer, flags, ptr(recon_err), ptr(dbg_ph0), ptr(dbg_h0),
-                                   ptr(dbg_v1), ptr(workspace), wb, _stream(stream)), "rbm_cd1_step")
+                                   lr, momentum, seed, step, layer, flags, ptr(recon_err), ptr(workspace), wb,
+                                   _stream(stream)), "rbm_cd1_step")
+
+
+def rbm_workspace_layout(n_vis, n_hid, n):
+    """((byte offset, row stride in floats) of P_h0, H0, V1, -P_h1) inside the 256-byte aligned workspace."""
+    out = (C.c_int64 * 8)()
+    _check(lib.rbm_workspace_layout(n_vis, n_hid, n, C.cast(out, C.c_void_p)), "rbm_workspace_layout")
+    return tuple((int(out[2 * i]), int(out[2 * i + 1])) for i in range(4))
+
+
+def mavg_philox_fill(out, nblocks, first_block, seed, step, layer, phase, stream=None):
+    return _check(lib.mavg_philox_fill(ptr(out), nblocks, first_block, seed, step, layer, phase, _stream(stream)),
+                  "mavg_philox_fill")
 
 
 def rbm_hidden_prob(n_vis, n_hid, w, c, v, n, out, workspace, stream=None, workspace_bytes=None):

@@ -282,7 +282,7 @@ extern "C" int32_t dnn_count_correct(const mavg_shape* shape, int32_t k, const f
     if (!acts || !labels || !correct) return MAVG_E_NULL;
     if (k < 1 || n < 1) return MAVG_E_DIM;
     const Layout y = make_layout(shape, n);
-    if (k > 1 && (act_stride < y.acts || label_stride < n)) return MAVG_E_ALIGN;
+    if (k > 1 && (act_stride < y.acts || (label_stride != 0 && label_stride < n))) return MAVG_E_ALIGN;
     if (count_correct_launch(acts + y.a_off[y.L], y.d[y.L], act_stride, labels, label_stride, n, y.d[y.L], k, correct,
                              static_cast<hipStream_t>(stream)) != 0) return MAVG_E_LAUNCH;
     return MAVG_OK;

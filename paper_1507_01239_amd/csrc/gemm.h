@@ -63,6 +63,21 @@ struct GemmDesc {
     int force_splits = 0;   // 0: choose; otherwise number of contraction splits
 };
 
+// Kernel / tile configurations (also the `cfg` argument of the exported mavg_gemm).
+enum GemmCfg : int {
+    CFG_AUTO = -1,
+    CFG_64 = 0,          // 64x64 tiles, 2x2 wavefronts of 32x32: direct-to-LDS (ring of four stages) whenever the operands allow
+    CFG_64_REG = 1,      // 64x64 tiles, always register-staged (guarded loads: any shape, any alignment)
+    CFG_128_REG = 2,     // 128x128 tiles, 2x4 wavefronts of 64x32, register-staged
+    CFG_128x64 = 3,      // direct-to-LDS only from here on (replanned as CFG_64_REG when the operands do not allow it):
+    CFG_64x128 = 4,      //   2x2 wavefronts of 64x32 / 32x64 / 64x64
+    CFG_128 = 5,
+    CFG_64_RING3 = 6,    // as CFG_64 with a ring of three LDS stages
+    CFG_KG_32x64 = 7,    // 32x64 tile, contraction split four ways inside the workgroup
+    CFG_KG_32x32 = 8,    // 32x32 tile, likewise, one wavefront per k-group (no barrier in the loop)
+    CFG_COUNT = 9
+};
+
 struct GemmPlan { int cfg; int splits; int bm, bn; };
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits);

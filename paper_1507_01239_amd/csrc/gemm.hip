@@ -63,27 +63,21 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(GemmKParams p) {
 // ---- host side -----------------------------------------------------------------------------------
 
 struct TileCfg { int bm, bn, bk, threads; };
-// index = the `cfg` argument of the exported test entry point
-static const TileCfg kCfgs[] = {
-    // register-staged kernels (guarded loads: any shape, any alignment)
-    {128, 128, 16, 512},   // 0: = 2 (retired variant)
-    {64, 64, 16, 256},     // 1: 2x2 wavefronts of 32x32; runs as the direct-to-LDS 64x64 kernel whenever the operands allow
-    {128, 128, 16, 512},   // 2: 2x4 wavefronts of 64x32
-    {64, 64, 16, 256},     // 3..7: = 8 (retired variants: 128x64, 64x128, 256x128 tiles, 32 contraction steps per stage)
-    {64, 64, 16, 256},
-    {64, 64, 16, 256},
-    {64, 64, 16, 256},
-    {64, 64, 16, 256},
-    {64, 64, 16, 256},     // 8: as 1, but never the direct-to-LDS variant
-    // direct-to-LDS only; replanned as 8 when the operands do not allow it
-    {128, 64, 16, 256},    // 9: 2x2 wavefronts of 64x32
-    {64, 128, 16, 256},    // 10: 2x2 wavefronts of 32x64
-    {128, 128, 16, 256},   // 11: 2x2 wavefronts of 64x64
-    {64, 64, 16, 256},     // 12: as 1 with a ring of three LDS stages instead of four
-    {32, 64, 16, 512},     // 13: 32x64 tile, contraction split four ways inside the workgroup
-    {32, 32, 16, 256},     // 14: as 13 with one wavefront per k-group (32x32 tile, no barrier in the loop)
+// indexed by GemmCfg
+static const TileCfg kCfgs[CFG_COUNT] = {
+    {64, 64, 16, 256},     // CFG_64
+    {64, 64, 16, 256},     // CFG_64_REG
+    {128, 128, 16, 512},   // CFG_128_REG
+    {128, 64, 16, 256},    // CFG_128x64
+    {64, 128, 16, 256},    // CFG_64x128
+    {128, 128, 16, 256},   // CFG_128
+    {64, 64, 16, 256},     // CFG_64_RING3
+    {32, 64, 16, 512},     // CFG_KG_32x64
+    {32, 32, 16, 256},     // CFG_KG_32x32
 };
-constexpr int kNumCfgs = 15;
+constexpr int kNumCfgs = CFG_COUNT;
+static inline bool cfg_dma_only(int cfg) { return cfg >= CFG_128x64 && cfg != CFG_64_RING3; }
+static inline bool cfg_kg(int cfg) { return cfg == CFG_KG_32x64 || cfg == CFG_KG_32x32; }
 
 GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     GemmPlan pl;
@@ -99,23 +93,23 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
     // (8000x2048x256: 90 against 95 us); the long contractions want the deeper ring (256x8000x2048: 73 against 81).
     if (cfg < 0 || cfg >= kNumCfgs) {
         const int64_t t64 = (int64_t)((M + 63) / 64) * ((N + 63) / 64) * batch;
-        cfg = (M >= 2048 && N >= 2048 && K >= 2048) ? 11 : (K <= 1024 && t64 >= 1024) ? 12 : 1;
+        cfg = (M >= 2048 && N >= 2048 && K >= 2048) ? CFG_128 : (K <= 1024 && t64 >= 1024) ? CFG_64_RING3 : CFG_64;
         // A skinny problem whose 32x64 tiles come to about one per compute unit (the 256 x 2048 x 2048 hidden
         // layers of the minibatch-256 step) does its contraction split inside the workgroup: 24.5 against
         // 26.9 us including the reducer (13.1 against 15.9 us for the 440-wide first layer).  Not at half or
         // twice that many tiles, nor for K = 8000 (measured).
         const int64_t t3264 = (int64_t)((M + 31) / 32) * ((N + 63) / 64) * batch;
-        if (cfg == 1 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU + kNumCU / 8 && K >= 256 && K <= 4096) cfg = 13;
+        if (cfg == CFG_64 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU + kNumCU / 8 && K >= 256 && K <= 4096) cfg = CFG_KG_32x64;
         // Half as many rows again (128 x 2048 x 2048): 32x32 tiles, one wavefront per k-group, no barrier in the
         // loop: 18.0 against 19.8 us.
         const int64_t t3232 = (int64_t)((M + 31) / 32) * ((N + 31) / 32) * batch;
-        if (cfg == 1 && t3232 >= 3 * kNumCU / 4 && t3232 <= kNumCU + kNumCU / 8 && K >= 1024 && K <= 4096) cfg = 14;
+        if (cfg == CFG_64 && t3232 >= 3 * kNumCU / 4 && t3232 <= kNumCU + kNumCU / 8 && K >= 1024 && K <= 4096) cfg = CFG_KG_32x32;
     }
     pl.cfg = cfg;
     pl.bm = kCfgs[cfg].bm; pl.bn = kCfgs[cfg].bn;
     const int bk = kCfgs[cfg].bk;
     const int64_t tiles = (int64_t)((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn) * batch;
-    int splits = (cfg == 13 || cfg == 14) ? 1 : force_splits;      // 13, 14 split the contraction inside the workgroup only
+    int splits = cfg_kg(cfg) ? 1 : force_splits;      // these split the contraction inside the workgroup only
     if (splits <= 0) {
         splits = 1;
         if (tiles <= kNumCU + kNumCU / 2) {                        // (500 tiles measured faster unsplit than split in two)
@@ -138,8 +132,8 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
 int64_t gemm_ws_floats(int M, int N, int K, int batch, int force_cfg, int force_splits) {
     const GemmPlan pl = gemm_plan(M, N, K, batch, force_cfg, force_splits);
     int splits = pl.splits;
-    if (pl.cfg >= 9 && pl.cfg != 12) {      // direct-to-LDS only: also cover what runs if the operands rule it out
-        const GemmPlan fb = gemm_plan(M, N, K, batch, 8, force_splits);
+    if (cfg_dma_only(pl.cfg)) {      // direct-to-LDS only: also cover what runs if the operands rule it out
+        const GemmPlan fb = gemm_plan(M, N, K, batch, CFG_64_REG, force_splits);
         if (fb.splits > splits) splits = fb.splits;
     }
     return splits > 1 ? (int64_t)splits * batch * M * N : 0;
@@ -160,7 +154,7 @@ static bool dma_eligible(const GemmDesc& d, const GemmKParams& p) {
 }
 
 static void launch_dma(int cfg, const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
-    if (cfg == 9 || cfg == 10 || cfg == 11) launch_dma128(cfg, p, a_kc, b_kc, grid, s);
+    if (cfg == CFG_128x64 || cfg == CFG_64x128 || cfg == CFG_128) launch_dma128(cfg, p, a_kc, b_kc, grid, s);
     else launch_dma64(cfg, p, a_kc, b_kc, grid, s);
 }
 
@@ -192,10 +186,10 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
     if (rowsum && d.a_kc) return note_hip_error(hipErrorInvalidValue);
     GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
     GemmKParams p = fill_params(d, pl, ws);
-    const bool kg_cfg = pl.cfg == 13 || pl.cfg == 14;
-    if (pl.cfg >= 9 && pl.cfg != 12 &&
-        !(dma_eligible(d, p) && (!kg_cfg || (!rowsum && d.K / (pl.cfg == 13 ? kKgWideBK : kDmaBK) >= kKGroups)))) {
-        pl = gemm_plan(d.M, d.N, d.K, d.batch, 8, rowsum ? 1 : d.force_splits);
+    const bool kg_cfg = cfg_kg(pl.cfg);
+    if (cfg_dma_only(pl.cfg) &&
+        !(dma_eligible(d, p) && (!kg_cfg || (!rowsum && d.K / (pl.cfg == CFG_KG_32x64 ? kKgWideBK : kDmaBK) >= kKGroups)))) {
+        pl = gemm_plan(d.M, d.N, d.K, d.batch, CFG_64_REG, rowsum ? 1 : d.force_splits);
         p = fill_params(d, pl, ws);
     }
     if (d.force_cfg < 0 && pl.splits == 1 && !dma_eligible(d, p)) {
@@ -203,16 +197,16 @@ int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t str
         // register-staged kernels the 128x128 tile with 8 wavefronts is the fastest from about 3000 64x64 tiles on
         const int64_t t64 = (int64_t)p.tiles_m * p.tiles_n * d.batch;
         if (t64 >= 3072 && d.M >= 512 && d.N >= 512) {
-            pl = gemm_plan(d.M, d.N, d.K, d.batch, 2, 1);
+            pl = gemm_plan(d.M, d.N, d.K, d.batch, CFG_128_REG, 1);
             p = fill_params(d, pl, ws);
         }
     }
     if (pl.splits > 1 && (ws == nullptr || ws_floats < (int64_t)pl.splits * d.batch * d.M * d.N)) return note_hip_error(hipErrorInvalidValue);
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)(d.batch * pl.splits));
-    if (pl.cfg == 13 || pl.cfg == 14) {      // (the plan may have been replaced above)
+    if (cfg_kg(pl.cfg)) {      // (the plan may have been replaced above)
         launch_kg(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
-    } else if ((pl.cfg == 1 || pl.cfg >= 9) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
-    else launch_legacy(pl.cfg == 0 || pl.cfg == 2, p, d.a_kc, d.b_kc, grid, stream);
+    } else if ((pl.cfg == CFG_64 || pl.cfg >= CFG_128x64) && dma_eligible(d, p)) launch_dma(pl.cfg, p, d.a_kc, d.b_kc, grid, stream);
+    else launch_legacy(pl.cfg == CFG_128_REG, p, d.a_kc, d.b_kc, grid, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return note_hip_error(e);
     if (pl.splits > 1) {
@@ -247,7 +241,7 @@ static int gemm_launch_grouped_thin(const GemmDesc* d, int count, hipStream_t st
         if (di.M <= 0 || di.N <= 0 || di.batch <= 0) continue;
         if (!di.a_kc || !di.b_kc || di.batch != d[0].batch || di.epi.kind != EPI_STORE || di.epi.rowsum_dst != nullptr)
             return note_hip_error(hipErrorInvalidValue);
-        const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, 14, 1);
+        const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, CFG_KG_32x32, 1);
         const GemmKParams q = fill_params(di, pl, nullptr);
         if (!dma_eligible(di, q) || di.K / kDmaBK < kThinKGroups) {
             GemmDesc one = di;
@@ -294,7 +288,7 @@ int gemm_launch_grouped(const GemmDesc* d, int count, hipStream_t stream, bool t
             if (di.M <= 0 || di.N <= 0 || di.batch <= 0) continue;
             if (di.a_kc != d[0].a_kc || di.b_kc != d[0].b_kc || di.batch != d[0].batch) return note_hip_error(hipErrorInvalidValue);
             if (di.epi.rowsum_dst != nullptr && di.a_kc) return note_hip_error(hipErrorInvalidValue);
-            const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, 1, 1);      // 64x64 tiles, unsplit
+            const GemmPlan pl = gemm_plan(di.M, di.N, di.K, di.batch, CFG_64, 1);      // 64x64 tiles, unsplit
             const GemmKParams q = fill_params(di, pl, nullptr);
             if (dma_eligible(di, q) != dma) continue;
             a_kc = di.a_kc; b_kc = di.b_kc; batch = di.batch;

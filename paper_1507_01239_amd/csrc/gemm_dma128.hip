@@ -13,8 +13,8 @@ static void launch_dma_t(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, 
 }
 
 void launch_dma128(int cfg, const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
-    if (cfg == 9) launch_dma_t<2, 1, 4>(p, a_kc, b_kc, grid, s);
-    else if (cfg == 10) launch_dma_t<1, 2, 4>(p, a_kc, b_kc, grid, s);
+    if (cfg == CFG_128x64) launch_dma_t<2, 1, 4>(p, a_kc, b_kc, grid, s);
+    else if (cfg == CFG_64x128) launch_dma_t<1, 2, 4>(p, a_kc, b_kc, grid, s);
     else launch_dma_t<2, 2, 4>(p, a_kc, b_kc, grid, s);
 }
 

@@ -14,7 +14,7 @@ static void launch_dma_t(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, 
 }
 
 void launch_dma64(int cfg, const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
-    if (cfg == 12) launch_dma_t<1, 1, 3>(p, a_kc, b_kc, grid, s);
+    if (cfg == CFG_64_RING3) launch_dma_t<1, 1, 3>(p, a_kc, b_kc, grid, s);
     else launch_dma_t<1, 1, 4>(p, a_kc, b_kc, grid, s);
 }
 

@@ -14,7 +14,7 @@ static void launch_kg_t(const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, h
 }
 
 void launch_kg(int cfg, const GemmKParams& p, bool a_kc, bool b_kc, dim3 grid, hipStream_t s) {
-    if (cfg == 13) launch_kg_t<2>(p, a_kc, b_kc, grid, s);
+    if (cfg == CFG_KG_32x64) launch_kg_t<2>(p, a_kc, b_kc, grid, s);
     else launch_kg_t<1>(p, a_kc, b_kc, grid, s);
 }
 

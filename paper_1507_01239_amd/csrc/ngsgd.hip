@@ -34,7 +34,7 @@ constexpr int kJacobiSweeps = 14;
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
-struct StateView { float* R; double* d; double* rho; int64_t* t; };
+struct StateView { float* R; double* d; double* rho; int64_t* t; int32_t* info; };
 __host__ __device__ inline StateView state_view(char* st, int dim, int rank) {
     const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
     StateView v;
@@ -42,6 +42,7 @@ __host__ __device__ inline StateView state_view(char* st, int dim, int rank) {
     v.d = reinterpret_cast<double*>(st + (int64_t)rank * ld * 4);
     v.rho = v.d + rank;
     v.t = reinterpret_cast<int64_t*>(v.rho + 1);
+    v.info = reinterpret_cast<int32_t*>(v.t + 1);     // [0] Jacobi sweeps of the last fold, [1] folds that ran out of sweeps
     return v;
 }
 
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(256) void ng_init_kernel(char* state, int dim, int 
     }
     if (blockIdx.x == 0) {
         if (threadIdx.x < rank) v.d[threadIdx.x] = kEps;
-        if (threadIdx.x == 0) { *v.rho = kEps; *v.t = 0; }
+        if (threadIdx.x == 0) { *v.rho = kEps; *v.t = 0; v.info[0] = 0; v.info[1] = 0; }
     }
 }
 
@@ -206,7 +207,9 @@ __global__ __launch_bounds__(kEigThreads) void ng_eig_kernel(NgFoldTable tb, int
     __syncthreads();
     const int m = (r + 1) & ~1;      // even number of players
     const int half = m / 2;
-    for (int sweep = 0; sweep < kJacobiSweeps; ++sweep) {
+    int sweeps_done = 0;
+    bool converged = false;
+    for (int sweep = 0; sweep <= kJacobiSweeps; ++sweep) {
         // stop when the off-diagonal mass is negligible against the diagonal
         double off = 0.0, dg = 0.0;
         for (int i = grp; i < r; i += ngrp)
@@ -218,7 +221,9 @@ __global__ __launch_bounds__(kEigThreads) void ng_eig_kernel(NgFoldTable tb, int
         dg = block_sum_eig(dg, red);
         // off-diagonal norm below 1e-13 of the diagonal: Z spans many orders of magnitude, and a looser stop (1e-10)
         // leaves its small eigenvalues, hence the weak rows of R, outside the parity tolerance
-        if (off <= 1e-26 * dg) break;
+        if (off <= 1e-26 * dg) { converged = true; break; }
+        if (sweep == kJacobiSweeps) break;          // out of sweeps: the state's info word counts it
+        ++sweeps_done;
         for (int round = 0; round < m - 1; ++round) {
             // Z <- J^T Z J, U^T <- J^T U^T with, for every pair (p, q) of the round,
             // row_p <- c row_p - s row_q,  row_q <- s row_p + c row_q  (and the same for the columns of Z)
@@ -309,6 +314,8 @@ __global__ __launch_bounds__(kEigThreads) void ng_eig_kernel(NgFoldTable tb, int
         for (int i = 0; i < r; ++i) v.d[i] = fmax(v.d[i], floor_d);
         *v.rho = rho_new;
         if (bump_t) *v.t = *v.t + 1;
+        v.info[0] = sweeps_done;
+        if (!converged) v.info[1] += 1;
     }
     __syncthreads();
     double* __restrict__ Wb = Wt + zi * kMaxRank * kMaxRank;
@@ -1047,7 +1054,7 @@ using namespace mavg;
 extern "C" int64_t ngsgd_state_bytes(int32_t dim, int32_t rank) {
     if (dim < 2 || rank < 1 || rank > kMaxRank || rank >= dim) return MAVG_E_DIM;
     const int64_t ld = ((int64_t)dim + 3) / 4 * 4;
-    return round_up((int64_t)rank * ld * 4 + (int64_t)rank * 8 + 16, 16);
+    return round_up((int64_t)rank * ld * 4 + (int64_t)rank * 8 + 24, 16);
 }
 
 extern "C" int64_t ngsgd_workspace_bytes(int32_t dim, int32_t rank, int32_t n) {

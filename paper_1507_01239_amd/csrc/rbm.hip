@@ -10,6 +10,7 @@
 #include "../../include/mavg.h"
 #include "gemm.h"
 #include "kernels.h"
+#include "device_math.h"
 
 using namespace mavg;
 
@@ -51,6 +52,19 @@ extern "C" int64_t rbm_workspace_bytes(int32_t n_vis, int32_t n_hid, int32_t n) 
     return rbm_ws(n_vis, n_hid, n).total * 4 + 256;
 }
 
+// Where rbm_cd1_step leaves its intermediate matrices: byte offsets from the 256-byte aligned workspace base and row
+// strides in floats.
+extern "C" int32_t rbm_workspace_layout(int32_t n_vis, int32_t n_hid, int32_t n, int64_t* out) {
+    if (!out) return MAVG_E_NULL;
+    if (n_vis < 1 || n_hid < 1 || n < 1) return MAVG_E_DIM;
+    const RbmWs w = rbm_ws(n_vis, n_hid, n);
+    out[0] = w.off_ph * 4;                               out[1] = w.ldh;     // P_h0
+    out[2] = w.off_h0 * 4;                               out[3] = w.ldh;     // H0
+    out[4] = (w.off_vv + (int64_t)n * w.ldv) * 4;        out[5] = w.ldv;     // V1
+    out[6] = (w.off_ph + (int64_t)n * w.ldh) * 4;        out[7] = w.ldh;     // -P_h1
+    return MAVG_OK;
+}
+
 extern "C" int32_t rbm_hidden_prob(int32_t n_vis, int32_t n_hid, const float* w, const float* c, const float* v,
                                    int32_t n, float* out, void* workspace, int64_t workspace_bytes, void* stream) {
     if (!w || !c || !v || !out) return MAVG_E_NULL;
@@ -69,11 +83,11 @@ extern "C" int32_t rbm_hidden_prob(int32_t n_vis, int32_t n_hid, const float* w,
     return MAVG_OK;
 }
 
-extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w, float* a, float* c, float* mw,
-                                float* ma, float* mc, const float* v0, int32_t n, float lr, float momentum,
-                                uint64_t seed, uint32_t step, uint32_t layer, uint32_t flags, float* recon_err,
-                                float* dbg_ph0, float* dbg_h0, float* dbg_v1, void* workspace, int64_t workspace_bytes,
-                                void* stream) {
+namespace {
+
+// Host-side checks shared by the two CD-1 entry points (everything except the workspace).
+int cd1_check(int32_t V, int32_t H, int32_t vis_type, const float* w, const float* a, const float* c, const float* mw,
+              const float* ma, const float* mc, const float* v0, int32_t n, uint32_t flags) {
     if (!w || !a || !c || !mw || !ma || !mc || !v0) return MAVG_E_NULL;
     if (V < 1 || H < 1 || n < 1) return MAVG_E_DIM;
     if (vis_type != MAVG_VIS_BERNOULLI && vis_type != MAVG_VIS_GAUSSIAN) return MAVG_E_FLAG;
@@ -82,10 +96,14 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
     if (!aligned16(w) || !aligned16(a) || !aligned16(c) || !aligned16(mw) || !aligned16(ma) || !aligned16(mc) ||
         !aligned16(v0))
         return MAVG_E_ALIGN;
-    const RbmWs lay = rbm_ws(V, H, n);
-    if (!workspace || workspace_bytes < lay.total * 4 + 256) return MAVG_E_WORKSPACE;
-    float* ws = ws_base(workspace);
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    return MAVG_OK;
+}
+
+// The launches of one CD-1 step; ws: 256-byte aligned scratch of rbm_ws(V, H, n).total floats, contents undefined on
+// entry (every element that a stored result depends on is written before it is read).
+int32_t cd1_run(int32_t V, int32_t H, int32_t vis_type, float* w, float* a, float* c, float* mw, float* ma, float* mc,
+                const float* v0, int32_t n, float lr, float momentum, uint64_t seed, uint32_t step, uint32_t layer,
+                uint32_t flags, float* recon_err, const RbmWs& lay, float* ws, hipStream_t s) {
     float* ph0 = ws + lay.off_ph;                       // rows 0..n-1 of the stacked hidden statistics
     float* ph1 = ph0 + (int64_t)n * lay.ldh;            // rows n..2n-1, stored NEGATED
     float* h0 = ws + lay.off_h0;
@@ -132,9 +150,6 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
         g.epi.kind = EPI_BIAS_SIGMOID; g.epi.bias = c; g.epi.alpha = -1.f;
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
-    if (dbg_ph0 && note_hip_error(hipMemcpy2DAsync(dbg_ph0, (size_t)H * 4, ph0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
-    if (dbg_h0 && note_hip_error(hipMemcpy2DAsync(dbg_h0, (size_t)H * 4, h0, (size_t)lay.ldh * 4, (size_t)H * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
-    if (dbg_v1 && note_hip_error(hipMemcpy2DAsync(dbg_v1, (size_t)V * 4, v1, (size_t)lay.ldv * 4, (size_t)V * 4, n, hipMemcpyDeviceToDevice, s)) != 0) return MAVG_E_LAUNCH;
     // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma;  the same pass copies V0 under V1's rows' stride
     // and leaves the squared reconstruction error of each block of 32 columns, summed afterwards in block order
     if (colsum_axpby_launch(v0, V, v1, lay.ldv, ma, a, vv, lay.ldv, recon_err ? ws + lay.off_part : nullptr, n, V, lr * invn,
@@ -156,4 +171,42 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
     return MAVG_OK;
+}
+
+}  // namespace
+
+extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w, float* a, float* c, float* mw,
+                                float* ma, float* mc, const float* v0, int32_t n, float lr, float momentum,
+                                uint64_t seed, uint32_t step, uint32_t layer, uint32_t flags, float* recon_err,
+                                void* workspace, int64_t workspace_bytes, void* stream) {
+    const int rc = cd1_check(V, H, vis_type, w, a, c, mw, ma, mc, v0, n, flags);
+    if (rc) return rc;
+    const RbmWs lay = rbm_ws(V, H, n);
+    if (!workspace || workspace_bytes < lay.total * 4 + 256) return MAVG_E_WORKSPACE;
+    return cd1_run(V, H, vis_type, w, a, c, mw, ma, mc, v0, n, lr, momentum, seed, step, layer, flags, recon_err, lay,
+                   ws_base(workspace), static_cast<hipStream_t>(stream));
+}
+
+// ---- the generator by itself ------------------------------------------------------------------------
+namespace mavg {
+__global__ __launch_bounds__(256) void philox_fill_kernel(uint32_t* __restrict__ out, int64_t nblocks, uint32_t first,
+                                                          uint32_t k0, uint32_t k1, uint32_t step, uint32_t layer, uint32_t phase) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nblocks; i += (int64_t)gridDim.x * 256) {
+        const uint4 r = philox4x32_10(make_uint4(first + (uint32_t)i, step, layer, phase), k0, k1);
+        reinterpret_cast<uint4*>(out)[i] = r;
+    }
+}
+}  // namespace mavg
+
+extern "C" int32_t mavg_philox_fill(uint32_t* out, int64_t nblocks, uint32_t first_block, uint64_t seed, uint32_t step,
+                                    uint32_t layer, uint32_t phase, void* stream) {
+    if (!out) return MAVG_E_NULL;
+    if (nblocks < 0 || nblocks > ((int64_t)1 << 32)) return MAVG_E_DIM;
+    if (!aligned16(out)) return MAVG_E_ALIGN;
+    if (nblocks == 0) return MAVG_OK;
+    int64_t gx = (nblocks + 255) / 256;
+    if (gx > 4096) gx = 4096;
+    hipLaunchKernelGGL(philox_fill_kernel, dim3((unsigned)gx), dim3(256), 0, static_cast<hipStream_t>(stream), out, nblocks,
+                       first_block, (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32), step, layer, phase);
+    return note_hip_error(hipGetLastError()) == 0 ? MAVG_OK : MAVG_E_LAUNCH;
 }

@@ -44,7 +44,7 @@ def _run(m, n, k, a_kc, b_kc, epi=0, cfg=-1, splits=0, seed=0, pad=0, alpha=1.0,
 
 
 @pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
-@pytest.mark.parametrize("cfg", [0, 1])
+@pytest.mark.parametrize("cfg", [2, 0])
 def test_layouts_and_tiles(a_kc, b_kc, cfg):
     # several tiles each way plus ragged tails in m, n and k
     assert _run(200, 328, 148, a_kc, b_kc, cfg=cfg, seed=1) < 2e-6
@@ -55,18 +55,18 @@ def test_layouts_and_tiles(a_kc, b_kc, cfg):
 @pytest.mark.parametrize("splits", [1, 3])
 def test_epilogues_with_and_without_split(epi, splits):
     assert _run(96, 160, 200, 1, 1, epi=epi, splits=splits, seed=3, alpha=-0.5, beta=1.0) < 3e-6
-    assert _run(70, 132, 260, 0, 0, epi=epi, cfg=1, splits=splits, seed=4, alpha=0.25, beta=0.5) < 3e-6
+    assert _run(70, 132, 260, 0, 0, epi=epi, cfg=0, splits=splits, seed=4, alpha=0.25, beta=0.5) < 3e-6
 
 
 @pytest.mark.parametrize("a_kc,b_kc", [(1, 1), (1, 0), (0, 0), (0, 1)])
-@pytest.mark.parametrize("cfg", [1, 8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("cfg", [0, 1, 3, 4, 5, 6, 7, 8])
 def test_direct_to_lds_variant_and_its_register_staged_twin(a_kc, b_kc, cfg):
-    # shapes the direct-to-LDS kernels accept (16-byte aligned rows, contraction a multiple of 16); cfg 1 runs the
-    # 64x64 one, cfg 8 forces the register-staged kernel on the same problem, 9 / 10 / 11 are the 128x64, 64x128
-    # and 128x128 direct-to-LDS tiles, 12 the 64x64 one with a ring of three LDS stages, 13 the
-    # 32x64 tile whose contraction is split four ways inside the workgroup (falls back to 8 below four k-tiles), 14 its
-    # 32x32 variant with one wavefront per k-group and no barrier in the loop.  Ragged tile edges in m and n (clamped loads), one to many k-tiles (ring
-    # start-up and tail), padded leading dimensions, splits.
+    # shapes the direct-to-LDS kernels accept (16-byte aligned rows, contraction a multiple of 16); cfg 0 runs the
+    # 64x64 one, cfg 1 forces the register-staged kernel on the same problem, 3 / 4 / 5 are the 128x64, 64x128
+    # and 128x128 direct-to-LDS tiles, 6 the 64x64 one with a ring of three LDS stages, 7 the 32x64 tile whose
+    # contraction is split four ways inside the workgroup (falls back to 1 below four k-tiles), 8 its 32x32 variant
+    # with one wavefront per k-group and no barrier in the loop.  Ragged tile edges in m and n (clamped loads), one
+    # to many k-tiles (ring start-up and tail), padded leading dimensions, splits.
     assert _run(200, 328, 144, a_kc, b_kc, cfg=cfg, seed=21) < 2e-6
     assert _run(132, 68, 16, a_kc, b_kc, cfg=cfg, seed=22, pad=4) < 2e-6
     assert _run(64, 64, 32, a_kc, b_kc, cfg=cfg, seed=23) < 2e-6
@@ -82,14 +82,14 @@ def test_direct_to_lds_variant_and_its_register_staged_twin(a_kc, b_kc, cfg):
 
 @pytest.mark.parametrize("epi", [0, 1, 2, 3, 4])
 def test_direct_to_lds_epilogues(epi):
-    assert _run(200, 264, 64, 0, 0, epi=epi, cfg=11, splits=1, seed=34, alpha=-0.5, beta=1.0) < 3e-6
-    assert _run(136, 72, 96, 1, 0, epi=epi, cfg=9, splits=2, seed=35, alpha=0.5, beta=2.0) < 3e-6
-    assert _run(96, 160, 208, 1, 1, epi=epi, cfg=1, splits=1, seed=31, alpha=-0.5, beta=1.0) < 3e-6
-    assert _run(100, 200, 304, 1, 1, epi=epi, cfg=13, seed=36, alpha=-0.5, beta=1.0) < 3e-6
-    assert _run(72, 136, 1024, 1, 0, epi=epi, cfg=13, seed=37, alpha=0.5, beta=2.0) < 3e-6
-    assert _run(72, 136, 1024, 1, 1, epi=epi, cfg=14, seed=38, alpha=0.5, beta=2.0) < 3e-6
-    assert _run(72, 132, 256, 0, 0, epi=epi, cfg=1, splits=2, seed=32, alpha=0.25, beta=0.5) < 3e-6
-    assert _run(100, 64, 96, 1, 0, epi=epi, cfg=1, splits=1, seed=33, alpha=2.0, beta=-1.0) < 3e-6
+    assert _run(200, 264, 64, 0, 0, epi=epi, cfg=5, splits=1, seed=34, alpha=-0.5, beta=1.0) < 3e-6
+    assert _run(136, 72, 96, 1, 0, epi=epi, cfg=3, splits=2, seed=35, alpha=0.5, beta=2.0) < 3e-6
+    assert _run(96, 160, 208, 1, 1, epi=epi, cfg=0, splits=1, seed=31, alpha=-0.5, beta=1.0) < 3e-6
+    assert _run(100, 200, 304, 1, 1, epi=epi, cfg=7, seed=36, alpha=-0.5, beta=1.0) < 3e-6
+    assert _run(72, 136, 1024, 1, 0, epi=epi, cfg=7, seed=37, alpha=0.5, beta=2.0) < 3e-6
+    assert _run(72, 136, 1024, 1, 1, epi=epi, cfg=8, seed=38, alpha=0.5, beta=2.0) < 3e-6
+    assert _run(72, 132, 256, 0, 0, epi=epi, cfg=0, splits=2, seed=32, alpha=0.25, beta=0.5) < 3e-6
+    assert _run(100, 64, 96, 1, 0, epi=epi, cfg=0, splits=1, seed=33, alpha=2.0, beta=-1.0) < 3e-6
 
 
 def test_unaligned_operands_use_the_scalar_path():

@@ -8,7 +8,8 @@ import pytest
 
 import gen
 from oracle import dnn, ngsgd
-from tests.util import dev, host, rel_err, workspace
+from oracle import averaging
+from tests.util import check_close, dev, host, rel_err, workspace
 
 pytestmark = pytest.mark.gpu
 
@@ -21,6 +22,8 @@ def read_state(buf, dim, rank):
     d = np.frombuffer(raw, np.float64, rank, off)
     rho = np.frombuffer(raw, np.float64, 1, off + rank * 8)[0]
     t = np.frombuffer(raw, np.int64, 1, off + rank * 8 + 8)[0]
+    sweeps, unconverged = np.frombuffer(raw, np.int32, 2, off + rank * 8 + 16)
+    assert unconverged == 0 and 0 <= sweeps <= 14          # no fold so far ran out of Jacobi sweeps
     assert np.all(R[:, dim:] == 0)
     return R[:, :dim].astype(np.float64), d.copy(), float(rho), int(t)
 
@@ -140,6 +143,106 @@ class NgGpu:
         self.torch.cuda.synchronize()
         return host(self.theta[:, :self.P])
 
+    def probe_update(self, X, Y, lr_big, eta, fold=True):
+        """The update lr_big * (preconditioned gradient) this step would make, without making it: float32
+        parameters resolve a step of the trajectory's own small learning rate only to about 1e-3 of its
+        norm, so the step is taken once with a large power-of-two learning rate on a copy and undone."""
+        theta, states, first = self.theta.clone(), self.states.clone(), self.first
+        self.step(X, Y, lr_big, eta, fold)
+        upd = self.params().astype(np.float64) - host(theta[:, :self.P]).astype(np.float64)
+        self.theta.copy_(theta)
+        self.states.copy_(states)
+        self.first = first
+        return upd
+
+    def average(self):
+        self.B.replicas_average(self.theta, self.stride, self.P, self.k)
+
+    def state_blob(self, st, dim):
+        """Bytes of a device state holding the oracle state st (R rounded to float32)."""
+        ld = (dim + 3) // 4 * 4
+        R = np.zeros((self.rank, ld), np.float32)
+        R[:, :dim] = st.R
+        raw = R.tobytes() + np.asarray(st.d, np.float64).tobytes() + np.float64(st.rho).tobytes() + np.int64(st.t).tobytes()
+        raw += np.zeros(2, np.int32).tobytes()
+        return np.frombuffer(raw + bytes(self.sb - len(raw)), np.uint8)
+
+    def probe_update_from(self, thetas, states, X, Y, lr_big, eta):
+        """As probe_update, but teacher-forced: the step starts from the given parameters (K x P) and oracle states
+        (states[k] = (input-side list, output-side list)) instead of the device's own; those are restored afterwards.
+        Returns the update and the float32 parameters it started from."""
+        L = len(self.dims) - 1
+        keep_theta, keep_states, keep_first = self.theta.clone(), self.states.clone(), self.first
+        blobs = np.zeros((self.k * 2 * L, self.sb), np.uint8)
+        for k in range(self.k):
+            for l in range(1, L + 1):
+                blobs[k * 2 * L + 2 * (l - 1)] = self.state_blob(states[k][0][l - 1], self.dims[l - 1] + 1)
+                blobs[k * 2 * L + 2 * (l - 1) + 1] = self.state_blob(states[k][1][l - 1], self.dims[l])
+        self.states.copy_(dev(blobs))
+        start = np.asarray(thetas, np.float32)
+        self.theta[:, :self.P] = dev(start)
+        self.first = False
+        self.step(X, Y, lr_big, eta)
+        upd = self.params().astype(np.float64) - start.astype(np.float64)
+        self.theta.copy_(keep_theta)
+        self.states.copy_(keep_states)
+        self.first = keep_first
+        return upd, start
+
+
+def _oracle_states(dims, rank):
+    return ([ngsgd.init_state(dims[l - 1] + 1, rank) for l in range(1, len(dims))],
+            [ngsgd.init_state(dims[l], rank) for l in range(1, len(dims))])
+
+
+def _oracle_probe(dims, theta, batch, lr_big, eta, s_in, s_out, fold=True):
+    """Oracle counterpart of NgGpu.probe_update for one replica: the step from (theta, states) on copies of the states."""
+    pre = ngsgd.make_layer_preconditioner([s.copy() for s in s_in], [s.copy() for s in s_out], 4.0, eta, update=fold)
+    new, _, _ = dnn.sgd_step(theta, dims, batch[0], batch[1], lr_big, precondition=pre)
+    return new - theta
+
+
+def check_update_tensors(upd_gpu, upd_ref, dims, tol, what):
+    worst = 0.0
+    for l, ((Wg, bg), (Wr, br)) in enumerate(zip(dnn.unpack(upd_gpu, dims), dnn.unpack(upd_ref, dims)), start=1):
+        worst = max(worst, check_close(Wg, Wr, tol, f"{what} W{l}")[0], check_close(bg, br, tol, f"{what} b{l}")[0])
+    return worst
+
+
+def _run_small_ng_case(dims, K, n, lr, rank, eta, seed, fold):
+    """Trajectory of len(fold) minibatches on K replicas against the oracle: before every step the preconditioned
+    update itself within 1e-4 per tensor (probe at learning rate 64), after it the parameters within 1e-5."""
+    T = len(fold)
+    theta0 = gen.init_theta(dims, seed, 0.1)
+    shards = [[(gen.features_iid(n, dims[0], seed, k, t), gen.labels_uniform(n, dims[-1], seed, k, t)) for t in range(T)]
+              for k in range(K)]
+    g = NgGpu(dims, K, n, theta0, rank)
+    L = len(dims) - 1
+    th = [theta0.astype(np.float64) for _ in range(K)]
+    st = [_oracle_states(dims, rank) for _ in range(K)]
+    worst = 0.0
+    for t in range(T):
+        X = np.stack([shards[k][t][0] for k in range(K)])
+        Y = np.stack([shards[k][t][1] for k in range(K)])
+        upd = g.probe_update(X, Y, 64.0, eta, fold[t])
+        for k in range(K):
+            ref = _oracle_probe(dims, th[k], shards[k][t], 64.0, eta, st[k][0], st[k][1], fold[t])
+            worst = max(worst, check_update_tensors(upd[k], ref, dims, 1e-4, f"minibatch {t}, replica {k}, update"))
+        before = host(g.states).copy() if not fold[t] else None
+        g.step(X, Y, lr, eta, fold=fold[t])
+        got = g.params()
+        if not fold[t]:
+            assert np.array_equal(host(g.states), before)          # apply-only leaves every state bit for bit
+        for k in range(K):
+            pre = ngsgd.make_layer_preconditioner(st[k][0], st[k][1], 4.0, eta, update=fold[t])
+            th[k], _, _ = dnn.sgd_step(th[k], dims, shards[k][t][0], shards[k][t][1], lr, precondition=pre)
+            assert rel_err(got[k], th[k]) < 1e-5
+    for k in range(K):
+        for l in range(1, L + 1):
+            check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, st[k][0][l - 1], tol=5e-3)
+            check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, st[k][1][l - 1], tol=5e-3)
+    print(f"worst per-tensor relative error of a preconditioned update: {worst:.2e}")
+
 
 def _oracle_ng_run(dims, theta0, shards, lr, rank, eta, fold=None):
     # fold[t] False: minibatch t is preconditioned with the states as they are and not folded into them
@@ -161,25 +264,7 @@ def _oracle_ng_run(dims, theta0, shards, lr, rank, eta, fold=None):
 
 
 def test_ng_training_step_tiny_two_replicas():
-    dims, K, T, n, lr, rank, eta, seed = gen.CONFIG_TINY_DIMS, 2, 4, 32, 0.1, 8, 0.2, 5
-    theta0 = gen.init_theta(dims, seed, 0.1)
-    shards = [[(gen.features_iid(n, dims[0], seed, k, t), gen.labels_uniform(n, dims[-1], seed, k, t)) for t in range(T)]
-              for k in range(K)]
-    ref = _oracle_ng_run(dims, theta0, shards, lr, rank, eta)
-    g = NgGpu(dims, K, n, theta0, rank)
-    for t in range(T):
-        g.step(np.stack([shards[k][t][0] for k in range(K)]), np.stack([shards[k][t][1] for k in range(K)]), lr, eta)
-        th = g.params()
-        for k in range(K):
-            # the step itself (difference to the starting point) within 1e-3, parameters far tighter
-            prev = theta0.astype(np.float64) if t == 0 else ref[k][0][t - 1]
-            assert rel_err(th[k] - prev, ref[k][0][t] - prev) < 5e-4, (t, k)
-            assert rel_err(th[k], ref[k][0][t]) < 1e-5
-    L = len(dims) - 1
-    for k in range(K):
-        for l in range(1, L + 1):
-            check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, ref[k][1][l - 1], tol=5e-3)
-            check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, ref[k][2][l - 1], tol=5e-3)
+    _run_small_ng_case(gen.CONFIG_TINY_DIMS, 2, 32, 0.1, 8, 0.2, 5, [True] * 4)
 
 
 def test_ng_training_step_mixed_widths_rank_above_32():
@@ -187,51 +272,12 @@ def test_ng_training_step_mixed_widths_rank_above_32():
     # contraction), 91 / 200 / 201 / 1600 (one chunk, ragged tails), 48 (too short for the in-workgroup split: launched
     # by itself); rank 36 takes the two-half path of the rank update and 64-lane groups in the eigen-solver;
     # 96 rows = 3 row tiles; two replicas.
-    dims, K, T, n, lr, rank, eta, seed = [90, 200, 1600, 48], 2, 3, 96, 0.05, 36, 0.2, 9
-    theta0 = gen.init_theta(dims, seed, 0.1)
-    shards = [[(gen.features_iid(n, dims[0], seed, k, t), gen.labels_uniform(n, dims[-1], seed, k, t)) for t in range(T)]
-              for k in range(K)]
-    ref = _oracle_ng_run(dims, theta0, shards, lr, rank, eta)
-    g = NgGpu(dims, K, n, theta0, rank)
-    for t in range(T):
-        g.step(np.stack([shards[k][t][0] for k in range(K)]), np.stack([shards[k][t][1] for k in range(K)]), lr, eta)
-        th = g.params()
-        for k in range(K):
-            prev = theta0.astype(np.float64) if t == 0 else ref[k][0][t - 1]
-            assert rel_err(th[k] - prev, ref[k][0][t] - prev) < 5e-4, (t, k)
-            assert rel_err(th[k], ref[k][0][t]) < 1e-5
-    L = len(dims) - 1
-    for k in range(K):
-        for l in range(1, L + 1):
-            check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, ref[k][1][l - 1], tol=5e-3)
-            check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, ref[k][2][l - 1], tol=5e-3)
+    _run_small_ng_case([90, 200, 1600, 48], 2, 96, 0.05, 36, 0.2, 9, [True] * 3)
 
 
 def test_ng_training_with_folds_on_some_minibatches_only():
     # the states are folded on minibatches 0, 1 and 4 only; 2, 3 and 5 are preconditioned with the states as they are
-    dims, K, n, lr, rank, eta, seed = [70, 130, 96, 40], 2, 64, 0.05, 12, 0.2, 13
-    fold = [True, True, False, False, True, False]
-    T = len(fold)
-    theta0 = gen.init_theta(dims, seed, 0.1)
-    shards = [[(gen.features_iid(n, dims[0], seed, k, t), gen.labels_uniform(n, dims[-1], seed, k, t)) for t in range(T)]
-              for k in range(K)]
-    ref = _oracle_ng_run(dims, theta0, shards, lr, rank, eta, fold)
-    g = NgGpu(dims, K, n, theta0, rank)
-    L = len(dims) - 1
-    for t in range(T):
-        before = host(g.states).copy() if not fold[t] else None
-        g.step(np.stack([shards[k][t][0] for k in range(K)]), np.stack([shards[k][t][1] for k in range(K)]), lr, eta, fold=fold[t])
-        th = g.params()
-        if not fold[t]:
-            assert np.array_equal(host(g.states), before)          # apply-only leaves every state bit for bit
-        for k in range(K):
-            prev = theta0.astype(np.float64) if t == 0 else ref[k][0][t - 1]
-            assert rel_err(th[k] - prev, ref[k][0][t] - prev) < 5e-4, (t, k)
-            assert rel_err(th[k], ref[k][0][t]) < 1e-5
-    for k in range(K):
-        for l in range(1, L + 1):
-            check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, ref[k][1][l - 1], tol=5e-3)
-            check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, ref[k][2][l - 1], tol=5e-3)
+    _run_small_ng_case([70, 130, 96, 40], 2, 64, 0.05, 12, 0.2, 13, [True, True, False, False, True, False])
 
 
 def test_config5_ng_full_size_two_steps():
@@ -264,3 +310,62 @@ def test_config5_ng_full_size_two_steps():
         worst = max(worst, rel_err(Wg, Wr), rel_err(bg, br))
     print(f"NG-SGD full-size update, worst per-tensor relative error {worst:.2e}")
     assert worst < 1e-4
+
+
+def test_config5_eight_replicas_ng_sgd_averaged_every_five():
+    # Sec. 4 (eq. 4) together with Sec. 3 (eq. 2), the combination of Sec. 5.7: 8 replicas of the full-size
+    # network, NG-SGD of rank 30 at minibatch 512, parameters averaged every 5 minibatches, two averaging periods.
+    # The parameters are averaged; the 14 Fisher states of each replica are NOT (eq. 2 averages theta only) and
+    # keep following their own replica's data.  The oracle side is the loop of oracle.averaging.train_with_averaging
+    # written out, so that the states of the moment are at hand for the probe of a single update.
+    dims, K, n, lr, rank, seed, T, n_avg = gen.CONFIG_FULL_DIMS, 8, 512, 0.008, 30, 61, 10, 5
+    eta = ngsgd.default_eta(n)
+    L = len(dims) - 1
+    theta0 = gen.init_theta(dims, seed, 0.05)
+    st = [_oracle_states(dims, rank) for _ in range(K)]
+    pre = [ngsgd.make_layer_preconditioner(st[k][0], st[k][1], 4.0, eta) for k in range(K)]
+    th = np.tile(theta0.astype(np.float64), (K, 1))
+    g = NgGpu(dims, K, n, theta0, rank)
+    for t in range(T):
+        batch = [(gen.features_speech_like(n, dims[0], seed, k, t), gen.labels_zipf(n, dims[-1], seed, k, t)) for k in range(K)]
+        X = np.stack([b[0] for b in batch])
+        Y = np.stack([b[1] for b in batch])
+        if t == n_avg:
+            # First step after an averaging: the preconditioned update by itself, per tensor (first and last replica).
+            # (i) Teacher-forced, the per-step bar of 1e-4: device and oracle start from the same parameters and the
+            #     same Fisher states (the oracle's, R rounded to float32).
+            upd, start = g.probe_update_from(th, st, X, Y, 8.0, eta)
+            for k in (0, K - 1):
+                s32 = tuple([ngsgd.NGState(s.R.astype(np.float32).astype(np.float64), s.d, s.rho, s.t) for s in side] for side in st[k])
+                want = _oracle_probe(dims, start[k].astype(np.float64), batch[k], 8.0, eta, s32[0], s32[1])
+                worst = check_update_tensors(upd[k], want, dims, 1e-4, f"replica {k}, minibatch {t}, teacher-forced update")
+                print(f"replica {k}: teacher-forced update after the first averaging, worst tensor {worst:.2e}")
+            # (ii) Free-running: each side from its own parameters and its own states after five folds (which agree
+            #      to the tolerance of check_state, not bit for bit), so this is held to the several-steps bar.
+            upd = g.probe_update(X, Y, 8.0, eta)
+            for k in (0, K - 1):
+                want = _oracle_probe(dims, th[k], batch[k], 8.0, eta, st[k][0], st[k][1])
+                worst = check_update_tensors(upd[k], want, dims, 1e-3, f"replica {k}, minibatch {t}, free-running update")
+                print(f"replica {k}: free-running update after the first averaging, worst tensor {worst:.2e}")
+        g.step(X, Y, lr, eta)
+        losses = np.zeros(K)
+        for k in range(K):
+            th[k], losses[k], _ = dnn.sgd_step(th[k], dims, batch[k][0], batch[k][1], lr, precondition=pre[k])
+        assert np.allclose(host(g.loss), losses, rtol=1e-3), t
+        if (t + 1) % n_avg == 0:
+            th = averaging.average_replicas(th)
+            g.average()
+            got = g.params()
+            assert all(np.array_equal(got[0], got[r]) for r in range(1, K))      # every replica holds the mean
+            for l, ((Wg, bg), (Wr, br)) in enumerate(zip(dnn.unpack(got[0].astype(np.float64), dims), dnn.unpack(th[0], dims)), start=1):
+                check_close(Wg, Wr, 1e-3, f"W{l} after minibatch {t}")
+                check_close(bg, br, 1e-3, f"b{l} after minibatch {t}")
+    # the states: each replica's own, compared with the oracle's for that replica, and different between replicas
+    for k in range(K):
+        for l in range(1, L + 1):
+            check_state(g.states[k * 2 * L + 2 * (l - 1)], dims[l - 1] + 1, rank, st[k][0][l - 1], tol=5e-3, subspace_tol=0.05)
+            check_state(g.states[k * 2 * L + 2 * (l - 1) + 1], dims[l], rank, st[k][1][l - 1], tol=5e-3, subspace_tol=0.05)
+    raw = host(g.states)
+    for k in range(1, K):
+        for j in range(2 * L):
+            assert not np.array_equal(raw[k * 2 * L + j], raw[j]), (k, j)          # not averaged, not shared

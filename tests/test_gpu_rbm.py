@@ -11,9 +11,35 @@ from tests.util import dev, host, rel_err, workspace
 pytestmark = pytest.mark.gpu
 
 
-def test_philox_uniforms_agree_word_for_word():
-    # the sampling epilogue with p = 1/2 exposes one bit per uniform; with bias b the decision u < sigmoid(b)
-    # pins u between thresholds.  Here: 2^20 elements, thresholds k/8 -> 3 leading bits of every uniform.
+def _taps(ws, V, H, n):
+    """Views of P_h0, H0, V1 where rbm_cd1_step left them inside its workspace."""
+    import torch
+    from paper_1507_01239_amd import binding as B
+    base = (-ws.data_ptr()) % 256
+    out = []
+    for (off, ld), cols in zip(B.rbm_workspace_layout(V, H, n)[:3], (H, H, V)):
+        out.append(ws[base + off: base + off + n * ld * 4].view(torch.float32).view(n, ld)[:, :cols])
+    return out
+
+
+def test_philox_blocks_agree_word_for_word():
+    # the device generator against the oracle's 64-bit integer arithmetic: every word of 2^20 consecutive counters,
+    # for two keys / (step, layer, phase) settings and a window that crosses the 2^32 wrap of the first counter word
+    import torch
+    from paper_1507_01239_amd import binding as B
+    nb = 1 << 20
+    out = torch.empty(nb, 4, dtype=torch.int32, device="cuda")
+    for seed, step, layer, phase, first in ((0xDEADBEEFCAFEF00D, 5, 3, 0, 0), (7, 0xFFFFFFFF, 0, 1, 0xFFFFFFFF - 1000)):
+        B.mavg_philox_fill(out, nb, first, seed, step, layer, phase)
+        torch.cuda.synchronize()
+        ctr = (np.arange(nb, dtype=np.uint64) + np.uint64(first)) & np.uint64(0xFFFFFFFF)
+        want = np.stack(philox.philox4x32_10(ctr, step, layer, phase, seed & 0xFFFFFFFF, seed >> 32), axis=1)
+        assert np.array_equal(host(out).view(np.uint32), want)
+
+
+def test_sampling_epilogue_draws_the_element_indexed_uniforms():
+    # the sampling epilogue on top of the generator: which word of which block an element takes and the strict '<'.
+    # Constant probabilities k/8 pin the three leading bits of every one of 2^20 uniforms.
     import torch
     from paper_1507_01239_amd import binding as B
     n, H, V = 1024, 1024, 4
@@ -24,10 +50,10 @@ def test_philox_uniforms_agree_word_for_word():
     for k in range(1, 8):
         p = k / 8.0
         c = torch.full((H,), float(np.log(p / (1 - p))), device="cuda")
-        h0, ph0 = z(n, H), z(n, H)
         B.rbm_cd1_step(V, H, B.VIS_BERNOULLI, z(H, V), z(V), c, z(H, V), z(V), z(H), z(n, V), n, 0.0, 0.0, seed, step, layer,
-                       0, None, ws, dbg_ph0=ph0, dbg_h0=h0)
+                       0, None, ws)
         torch.cuda.synchronize()
+        ph0, h0, _ = _taps(ws, V, H, n)
         pg = host(ph0).astype(np.float64)
         expect = (u < pg)
         got = host(h0) == 1.0
@@ -41,12 +67,12 @@ def _one_step(V, H, n, vis_type, flags, lr, mom, seed, step, layer, state, V0, t
     from paper_1507_01239_amd import binding as B
     t = {k: dev(v) for k, v in state.items()}
     v0 = dev(V0)
-    ph0, h0, v1 = (torch.empty(n, H, device="cuda"), torch.empty(n, H, device="cuda"), torch.empty(n, V, device="cuda"))
     err = torch.zeros(1, device="cuda")
     ws = workspace(B.rbm_workspace_bytes(V, H, n))
     B.rbm_cd1_step(V, H, vis_type, t["W"], t["a"], t["c"], t["MW"], t["Ma"], t["Mc"], v0, n, lr, mom, seed, step, layer, flags,
-                   err, ws, dbg_ph0=ph0, dbg_h0=h0, dbg_v1=v1)
+                   err, ws)
     torch.cuda.synchronize()
+    ph0, h0, v1 = _taps(ws, V, H, n)
     sample_v1 = bool(flags & 1)
     u_h = philox.uniforms(n * H, seed, step, layer, 0).reshape(n, H)
     u_v = philox.uniforms(n * V, seed, step, layer, 1).reshape(n, V) if sample_v1 else None
