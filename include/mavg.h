@@ -184,6 +184,27 @@ int32_t rbm_cd1_step(int32_t n_vis, int32_t n_hid, int32_t vis_type,
  */
 int32_t rbm_workspace_layout(int32_t n_vis, int32_t n_hid, int32_t n, int64_t* out);
 /*
+ * rbm_cd1_step for callers that cannot allocate or own no scratch memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same step, same kernels and bit-identical results, with
+ * the workspace in a static device array of MAVG_RBM_STATIC_SCRATCH_BYTES inside the library instead of a
+ * caller-provided buffer.  Arguments as rbm_cd1_step without workspace / workspace_bytes.
+ *   - Size limit: returns MAVG_E_WORKSPACE, before anything is launched, when
+ *     rbm_workspace_bytes(n_vis, n_hid, n) - 256 exceeds MAVG_RBM_STATIC_SCRATCH_BYTES
+ *     (2048 x 2048 needs 28 MiB at minibatch 512 and fits; 440 x 2048 needs 14.9 MiB at minibatch 256, 36 MiB at 1024).
+ *   - Calls no allocator.  The first call on a device looks up that device's address of the array
+ *     (hipGetSymbolAddress) and keeps it; make that first call outside a stream capture.
+ *   - Each device holds its own copy of the array from module load until the process ends.  All calls on a device
+ *     share it and it keeps the last call's contents (nothing in it needs to start at zero: every element a
+ *     result depends on is written first).  Calls that overlap on one device, on different streams or from
+ *     different threads, race: serialise them, or use rbm_cd1_step with separate workspaces.
+ */
+#define MAVG_RBM_STATIC_SCRATCH_BYTES ((int64_t)32 << 20)
+int32_t rbm_cd1_step_static(int32_t n_vis, int32_t n_hid, int32_t vis_type,
+                            float* w, float* a, float* c, float* mw, float* ma, float* mc,
+                            const float* v0, int32_t n, float lr, float momentum,
+                            uint64_t seed, uint32_t step, uint32_t layer, uint32_t flags,
+                            float* recon_err, void* stream);
+/*
  * The generator of the sampler by itself (Sec. 5.1 pretraining draws its Bernoulli decisions from it):
  * out[4 i .. 4 i + 3] (device, uint32, 16-byte aligned) <- Philox4x32-10 block of counter
  * (first_block + i mod 2^32, step, layer, phase) under key (seed lo32, seed hi32), for i in [0, nblocks).

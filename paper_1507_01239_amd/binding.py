@@ -75,6 +75,8 @@ _SIG = {
     "rbm_workspace_bytes": (_i64, [_i32, _i32, _i32]),
     "rbm_cd1_step": (_i32, [_i32, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _i32, _f, _f, _u64, _u32, _u32, _u32,
                             _p, _p, _i64, _p]),
+    "rbm_cd1_step_static": (_i32, [_i32, _i32, _i32, _p, _p, _p, _p, _p, _p, _p, _i32, _f, _f, _u64, _u32, _u32, _u32,
+                                   _p, _p]),
     "rbm_workspace_layout": (_i32, [_i32, _i32, _i32, _p]),
     "mavg_philox_fill": (_i32, [_p, _i64, _u32, _u64, _u32, _u32, _u32, _p]),
     "rbm_hidden_prob": (_i32, [_i32, _i32, _p, _p, _p, _i32, _p, _p, _i64, _p]),
@@ -182,6 +184,16 @@ def rbm_cd1_step(n_vis, n_hid, vis_type, w, a, c, mw, ma, mc, v0, n, lr, momentu
     return _check(lib.rbm_cd1_step(n_vis, n_hid, vis_type, ptr(w), ptr(a), ptr(c), ptr(mw), ptr(ma), ptr(mc), ptr(v0), n,
                                    lr, momentum, seed, step, layer, flags, ptr(recon_err), ptr(workspace), wb,
                                    _stream(stream)), "rbm_cd1_step")
+
+
+RBM_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def rbm_cd1_step_static(n_vis, n_hid, vis_type, w, a, c, mw, ma, mc, v0, n, lr, momentum, seed, step, layer, flags,
+                        recon_err, stream=None):
+    return _check(lib.rbm_cd1_step_static(n_vis, n_hid, vis_type, ptr(w), ptr(a), ptr(c), ptr(mw), ptr(ma), ptr(mc),
+                                          ptr(v0), n, lr, momentum, seed, step, layer, flags, ptr(recon_err),
+                                          _stream(stream)), "rbm_cd1_step_static")
 
 
 def rbm_workspace_layout(n_vis, n_hid, n):

@@ -7,6 +7,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/mavg.h"
 #include "gemm.h"
 #include "kernels.h"
@@ -185,6 +187,48 @@ extern "C" int32_t rbm_cd1_step(int32_t V, int32_t H, int32_t vis_type, float* w
     if (!workspace || workspace_bytes < lay.total * 4 + 256) return MAVG_E_WORKSPACE;
     return cd1_run(V, H, vis_type, w, a, c, mw, ma, mc, v0, n, lr, momentum, seed, step, layer, flags, recon_err, lay,
                    ws_base(workspace), static_cast<hipStream_t>(stream));
+}
+
+// ---- CD-1 without a workspace argument ----------------------------------------------------------------
+// For callers that cannot allocate (code under HIP graph capture, serving loops that own no scratch memory): the
+// same step with its scratch in a static device array.  Every device the library runs on holds the array from
+// module load to process end; its device address is looked up once per device and kept.
+namespace {
+
+constexpr int64_t kStaticScratchBytes = MAVG_RBM_STATIC_SCRATCH_BYTES;       // 32 MiB: covers 2048 x 2048 up to minibatch 512
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};     // per device: where that device's copy of `scratch` lives
+
+// Device address of the current device's scratch array (nullptr and a noted HIP error on failure).
+float* static_scratch() {
+    int dev = -1;
+    if (note_hip_error(hipGetDevice(&dev)) != 0 || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (note_hip_error(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) != 0) return nullptr;
+        g_scratch_ptr[dev] = static_cast<float*>(p);
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" int32_t rbm_cd1_step_static(int32_t V, int32_t H, int32_t vis_type, float* w, float* a, float* c, float* mw,
+                                       float* ma, float* mc, const float* v0, int32_t n, float lr, float momentum,
+                                       uint64_t seed, uint32_t step, uint32_t layer, uint32_t flags, float* recon_err,
+                                       void* stream) {
+    const int rc = cd1_check(V, H, vis_type, w, a, c, mw, ma, mc, v0, n, flags);
+    if (rc) return rc;
+    const RbmWs lay = rbm_ws(V, H, n);
+    if (lay.total * 4 > kStaticScratchBytes) return MAVG_E_WORKSPACE;       // before anything touches the device
+    float* ws = static_scratch();
+    if (!ws) return MAVG_E_LAUNCH;
+    return cd1_run(V, H, vis_type, w, a, c, mw, ma, mc, v0, n, lr, momentum, seed, step, layer, flags, recon_err, lay, ws,
+                   static_cast<hipStream_t>(stream));
 }
 
 // ---- the generator by itself ------------------------------------------------------------------------
