@@ -294,6 +294,30 @@ int32_t mavg_gemm(const float* a, int64_t lda, int32_t a_kc, const float* b, int
                   int32_t epi, const float* bias, const float* aux, int64_t ldaux, float alpha, float beta,
                   int32_t cfg, int32_t splits, void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * Several independent contractions C_i = epilogue(A_i B_i) of the same operand layouts in ONE launch (64x64 tiles,
+ * unsplit contraction): the form in which dnn_backward_update issues the weight gradients and SGD updates of all
+ * layers of a step (eq. 3).  Exported for tests and for timing that launch by itself.
+ *   problems  host array of `count` records (1 <= count <= 8), read during the call; all pointers inside device
+ *   a_kc, b_kc  as in mavg_gemm, shared by all problems
+ *   epi, alpha, beta, bias, aux, ldaux per problem as in mavg_gemm
+ *   rowsum_dst (nullable, only with a_kc == 0): rowsum_dst[m] <- rowsum_beta rowsum_dst[m] + rowsum_alpha sum_k A(m,k)
+ *   a_pad4 / b_pad4: rows of an m/n-contiguous operand may be read up to the next multiple of 4 columns
+ * Errors: MAVG_E_NULL, MAVG_E_DIM, MAVG_E_FLAG, MAVG_E_ALIGN, MAVG_E_LAUNCH.
+ */
+typedef struct {
+    const float* a; int64_t lda;
+    const float* b; int64_t ldb;
+    float* c; int64_t ldc;
+    int32_t m, n, k;
+    int32_t epi;
+    const float* bias; const float* aux; int64_t ldaux;
+    float alpha, beta;
+    float* rowsum_dst; float rowsum_alpha, rowsum_beta;
+    int32_t a_pad4, b_pad4;
+} mavg_gemm_problem;
+int32_t mavg_gemm_grouped(const mavg_gemm_problem* problems, int32_t count, int32_t a_kc, int32_t b_kc, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

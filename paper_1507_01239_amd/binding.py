@@ -87,6 +87,7 @@ _SIG = {
     "mavg_gemm": (_i32, [_p, _i64, _i32, _p, _i64, _i32, _p, _i64, _i32, _i32, _i32, _i32, _p, _p, _i64, _f, _f,
                          _i32, _i32, _p, _i64, _p]),
     "mavg_gemm_workspace_bytes": (_i64, [_i32, _i32, _i32, _i32, _i32]),
+    "mavg_gemm_grouped": (_i32, [_p, _i32, _i32, _i32, _p]),
 }
 EXPORTS = tuple(_SIG)
 for _name, (_res, _args) in _SIG.items():
@@ -241,3 +242,23 @@ def mavg_gemm(a, lda, a_kc, b, ldb, b_kc, c, ldc, m, n, k, epi, bias, aux, ldaux
     wb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     return _check(lib.mavg_gemm(ptr(a), lda, int(a_kc), ptr(b), ldb, int(b_kc), ptr(c), ldc, m, n, k, epi, ptr(bias),
                                 ptr(aux), ldaux, alpha, beta, cfg, splits, ptr(workspace), wb, _stream(stream)), "mavg_gemm")
+
+
+class GemmProblem(C.Structure):
+    """mavg_gemm_problem of include/mavg.h."""
+    _fields_ = [("a", _p), ("lda", _i64), ("b", _p), ("ldb", _i64), ("c", _p), ("ldc", _i64),
+                ("m", _i32), ("n", _i32), ("k", _i32), ("epi", _i32),
+                ("bias", _p), ("aux", _p), ("ldaux", _i64), ("alpha", _f), ("beta", _f),
+                ("rowsum_dst", _p), ("rowsum_alpha", _f), ("rowsum_beta", _f), ("a_pad4", _i32), ("b_pad4", _i32)]
+
+
+def gemm_problem(a, lda, b, ldb, c, ldc, m, n, k, epi=0, bias=None, aux=None, ldaux=0, alpha=1.0, beta=0.0,
+                 rowsum_dst=None, rowsum_alpha=1.0, rowsum_beta=0.0, a_pad4=False, b_pad4=False) -> GemmProblem:
+    return GemmProblem(ptr(a), lda, ptr(b), ldb, ptr(c), ldc, m, n, k, epi, ptr(bias), ptr(aux), ldaux, alpha, beta,
+                       ptr(rowsum_dst), rowsum_alpha, rowsum_beta, int(a_pad4), int(b_pad4))
+
+
+def mavg_gemm_grouped(problems, a_kc, b_kc, stream=None):
+    arr = (GemmProblem * len(problems))(*problems)
+    return _check(lib.mavg_gemm_grouped(C.cast(arr, C.c_void_p), len(problems), int(a_kc), int(b_kc), _stream(stream)),
+                  "mavg_gemm_grouped")

@@ -345,3 +345,29 @@ extern "C" int32_t mavg_gemm(const float* a, int64_t lda, int32_t a_kc, const fl
     float* ws = workspace ? reinterpret_cast<float*>((reinterpret_cast<uintptr_t>(workspace) + 255u) & ~uintptr_t(255)) : nullptr;
     return gemm_launch(g, ws, need, static_cast<hipStream_t>(stream)) == 0 ? MAVG_OK : MAVG_E_LAUNCH;
 }
+
+extern "C" int32_t mavg_gemm_grouped(const mavg_gemm_problem* pr, int32_t count, int32_t a_kc, int32_t b_kc, void* stream) {
+    if (!pr) return MAVG_E_NULL;
+    if (count < 1 || count > kMaxGroups) return MAVG_E_DIM;
+    GemmDesc g[kMaxGroups];
+    for (int i = 0; i < count; ++i) {
+        const mavg_gemm_problem& q = pr[i];
+        if (!q.a || !q.b || !q.c) return MAVG_E_NULL;
+        if (q.m < 1 || q.n < 1 || q.k < 0) return MAVG_E_DIM;
+        if (q.epi < EPI_STORE || q.epi > EPI_AXPBY) return MAVG_E_FLAG;
+        if ((q.epi == EPI_BIAS || q.epi == EPI_BIAS_SIGMOID) && !q.bias) return MAVG_E_NULL;
+        if (q.epi == EPI_MUL_DSIGMOID && !q.aux) return MAVG_E_NULL;
+        if (q.rowsum_dst && a_kc) return MAVG_E_FLAG;
+        if (q.lda < (a_kc ? q.k : q.m) || q.ldb < (b_kc ? q.k : q.n) || q.ldc < q.n || (q.epi == EPI_MUL_DSIGMOID && q.ldaux < q.n))
+            return MAVG_E_ALIGN;
+        GemmDesc& d = g[i];
+        d.A = q.a; d.lda = q.lda; d.a_kc = a_kc != 0;
+        d.B = q.b; d.ldb = q.ldb; d.b_kc = b_kc != 0;
+        d.C = q.c; d.ldc = q.ldc;
+        d.M = q.m; d.N = q.n; d.K = q.k;
+        d.a_pad4 = q.a_pad4 != 0; d.b_pad4 = q.b_pad4 != 0;
+        d.epi.kind = q.epi; d.epi.bias = q.bias; d.epi.aux = q.aux; d.epi.ldaux = q.ldaux; d.epi.alpha = q.alpha; d.epi.beta = q.beta;
+        d.epi.rowsum_dst = q.rowsum_dst; d.epi.rowsum_alpha = q.rowsum_alpha; d.epi.rowsum_beta = q.rowsum_beta;
+    }
+    return gemm_launch_grouped(g, count, static_cast<hipStream_t>(stream)) == 0 ? MAVG_OK : MAVG_E_LAUNCH;
+}

@@ -125,3 +125,11 @@ def test_rbm_and_gemm_validation():
     assert g(epi=1) == B.E_NULL                          # bias epilogue without a bias
     assert g(cfg=99) == B.E_FLAG
     assert g(splits=2, wb=0) == B.E_WORKSPACE
+    pr = lambda **kw: B.gemm_problem(kw.get("a", A), kw.get("lda", 64), A, 64, A, 64, 8, 8, 16, epi=kw.get("epi", 0))
+    gg = lambda probs, a_kc=1: _rc(B.mavg_gemm_grouped, probs, a_kc, 1, stream=0)
+    assert B.lib.mavg_gemm_grouped(None, 1, 1, 1, None) == B.E_NULL
+    assert gg([pr()] * 9) == B.E_DIM                     # at most 8 problems per launch
+    assert gg([pr(a=None)]) == B.E_NULL
+    assert gg([pr(lda=4)]) == B.E_ALIGN
+    assert gg([pr(epi=7)]) == B.E_FLAG
+    assert gg([pr(epi=1)]) == B.E_NULL                   # bias epilogue without a bias

@@ -127,3 +127,33 @@ def test_runs_are_bitwise_reproducible():
         torch.cuda.synchronize()
         outs.append(host(c))
     assert np.array_equal(outs[0], outs[1])
+
+
+def test_grouped_launch_of_weight_gradient_shaped_problems():
+    # three problems of different sizes in one launch, in the form of a step's weight updates: C <- C + alpha A^T B
+    # with both operands row-major over the contraction index (m- and n-contiguous), row sums of A into a vector;
+    # one width that is 2 mod 4 read through padded rows
+    import torch
+    from paper_1507_01239_amd import binding as B
+    rng = np.random.default_rng(40)
+    n = 96
+    shapes = [(200, 72), (64, 136), (86, 52)]          # (m, n_cols): outputs m x n_cols, contraction over n rows
+    probs, refs, outs, rows = [], [], [], []
+    for (m, nc) in shapes:
+        ldd = (m + 3) // 4 * 4
+        D = np.zeros((n, ldd), np.float32)
+        D[:, :m] = rng.standard_normal((n, m)).astype(np.float32)
+        A = rng.standard_normal((n, nc)).astype(np.float32)
+        W = rng.standard_normal((m, nc)).astype(np.float32)
+        bvec = rng.standard_normal(m).astype(np.float32)
+        d_d, a_d, w_d, b_d = dev(D), dev(A), dev(W), dev(bvec)
+        probs.append(B.gemm_problem(d_d, ldd, a_d, nc, w_d, nc, m, nc, n, epi=4, alpha=-0.25, beta=1.0,
+                                    rowsum_dst=b_d, rowsum_alpha=-0.25, rowsum_beta=1.0, a_pad4=True))
+        refs.append((W.astype(np.float64) - 0.25 * D[:, :m].astype(np.float64).T @ A.astype(np.float64),
+                     bvec.astype(np.float64) - 0.25 * D[:, :m].astype(np.float64).sum(axis=0)))
+        outs.append((w_d, b_d))
+        rows.append((d_d, a_d))
+    B.mavg_gemm_grouped(probs, 0, 0)
+    torch.cuda.synchronize()
+    for (w_d, b_d), (Wr, br) in zip(outs, refs):
+        assert rel_err(host(w_d), Wr) < 3e-6 and rel_err(host(b_d), br) < 3e-6
