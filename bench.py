@@ -289,9 +289,10 @@ def main():
         return {"ms": round(ms, 4), "frames/s": round(n / ms * 1e3, 1), "TFLOP/s": round(tf, 2), "frac_of_mfma_peak": frac(tf)}
 
     if want("cd1"):
-        # RBM CD-1 steps (10*n*V*H FLOP each): Gaussian 440 -> 2048, then Bernoulli 2048 -> 2048 with sampled visibles
-        extras["cd1_gaussian_440x2048"] = cd1_leg(440, 2048, B.VIS_GAUSSIAN, 0, 0.01, xs[0])
-        extras["cd1_bernoulli_2048x2048"] = cd1_leg(2048, 2048, B.VIS_BERNOULLI, B.SAMPLE_V1, 0.4, torch.rand(n, 2048, device="cuda"))
+        # RBM CD-1 steps (10*n*V*H FLOP each): Gaussian 440 -> 2048, then Bernoulli 2048 -> 2048 with sampled visibles;
+        # rates 0.01 / 0.4 scaled by (1 - momentum), without which the recursion diverges on these inputs
+        extras["cd1_gaussian_440x2048"] = cd1_leg(440, 2048, B.VIS_GAUSSIAN, 0, 0.001, xs[0])
+        extras["cd1_bernoulli_2048x2048"] = cd1_leg(2048, 2048, B.VIS_BERNOULLI, B.SAMPLE_V1, 0.04, torch.rand(n, 2048, device="cuda"))
         log(f"cd1: {extras['cd1_gaussian_440x2048']} {extras['cd1_bernoulli_2048x2048']}")
 
     if want("stack"):
@@ -305,7 +306,7 @@ def main():
         warm_clocks(0.2)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        times = PT.pretrain_stack(widths, mbs, init, per_rbm, 0.01, 0.4, 0.9, seed, timings=True)[1]
+        times = PT.pretrain_stack(widths, mbs, init, per_rbm, 0.001, 0.04, 0.9, seed, timings=True)[1]
         th_stack = torch.from_numpy(theta0).cuda()
         PT.init_dnn_from_stack(shape, 1, th_stack, P, init)
         torch.cuda.synchronize()
@@ -489,8 +490,8 @@ def main():
             other["config3_mb256_8_replicas_n2"] = {"frames/s": round(8 * 2 * n / (time.perf_counter() - t0), 1),
                                                     "sample": "8 replicas x 2 minibatches, one averaging"}
             # config 4: 20 CD-1 steps of each RBM
-            for name, V, H, vis, lr_r, v0, sv in (("gaussian_440x2048", 440, 2048, orbm.GAUSSIAN, 0.01, xs_h[0], False),
-                                                   ("bernoulli_2048x2048", 2048, 2048, orbm.BERNOULLI, 0.4,
+            for name, V, H, vis, lr_r, v0, sv in (("gaussian_440x2048", 440, 2048, orbm.GAUSSIAN, 0.001, xs_h[0], False),
+                                                   ("bernoulli_2048x2048", 2048, 2048, orbm.BERNOULLI, 0.04,
                                                     np.random.default_rng(0).random((n, 2048)).astype(np.float32), True)):
                 W_, a_, c_ = gen.rbm_params(V, H, seed, 0)
                 MW, Ma, Mc = np.zeros_like(W_), np.zeros_like(a_), np.zeros_like(c_)

@@ -124,3 +124,32 @@ def test_arg_max_takes_the_lowest_index_among_equal_posteriors():
         correct = torch.full((1,), 123, dtype=torch.int32, device="cuda")
         B.dnn_count_correct(shape, 1, acts, 0, dev(np.array(labels, np.int32)), 0, n, correct)
         assert int(correct.item()) == want
+
+
+def test_full_width_stack_of_six_rbms_and_initialisation():
+    # Sec. 5.1 at size: 440 -> 2048 and five RBMs of 2048 -> 2048, minibatch 256, two CD-1 updates per RBM from the
+    # same start on both sides (a longer run is a free-running comparison: see the 500-minibatch test of the single
+    # RBMs), then the copy into the six hidden layers of the 440-6x2048-8000 network
+    import torch
+    from paper_1507_01239_amd import binding as B
+    from paper_1507_01239_amd import pretrain as P
+    seed, n, steps = 78, 256, 2
+    widths = list(gen.CONFIG_FULL_DIMS[:-1])
+    mbs, init = _stack_case(widths, n, 2, seed)
+    ref_stack, ref_errs = opre.pretrain_stack(widths, mbs, init, steps, 0.01, 0.4, 0.9, seed)
+    d_init = [tuple(dev(t) for t in r) for r in init]
+    errs = P.pretrain_stack(widths, [dev(m) for m in mbs], d_init, steps, 0.01, 0.4, 0.9, seed)
+    torch.cuda.synchronize()
+    for l, (rbm_g, rbm_o) in enumerate(zip(d_init, ref_stack), start=1):
+        for name, g, o in zip("Wac", rbm_g, rbm_o):
+            assert rel_err(host(g), o) < 1e-3, (l, name)
+        assert rel_err(host(errs[l - 1]), np.array(ref_errs[l - 1])) < 1e-3, l
+    dims = gen.CONFIG_FULL_DIMS
+    shape = B.Shape(dims)
+    Pn = B.mavg_param_count(shape)
+    theta0 = gen.init_theta(dims, seed, 0.05)
+    theta = dev(theta0)
+    P.init_dnn_from_stack(shape, 1, theta, Pn, d_init)
+    torch.cuda.synchronize()
+    want = opre.init_dnn_from_stack(theta0, dims, [tuple(host(t) for t in r) for r in d_init])
+    assert np.array_equal(host(theta), want.astype(np.float32))

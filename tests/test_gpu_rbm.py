@@ -153,3 +153,81 @@ def test_zero_lr_and_momentum_leave_parameters_bit_identical():
                    workspace(B.rbm_workspace_bytes(V, H, n)))
     torch.cuda.synchronize()
     assert np.array_equal(host(t[0]), W) and np.array_equal(host(t[1]), a) and np.array_equal(host(t[2]), c)
+
+
+def test_config4_free_running_500_minibatches_each():
+    # Config 4 at its stated horizon: Gaussian-Bernoulli RBM 440 -> 2048 (rate 0.01), then Bernoulli-Bernoulli RBM
+    # 2048 -> 2048 (rate 0.4, sampled reconstruction) on the first one's hidden probabilities; minibatch 256,
+    # momentum 0.9, 500 minibatches each, device and oracle both FREE-RUNNING from the same start.
+    # The rates are passed as rate * (1 - momentum) = 0.001 / 0.04: with the update M <- momentum M + lr d taken
+    # literally at lr = 0.01, the Gaussian RBM's reconstruction error grows from 2.9e5 to 2e23 within ten minibatches
+    # on these inputs (2048 hidden units make the loop gain of the linear reconstruction about 10), on the oracle
+    # and on the device alike; scaling the rate by (1 - momentum) when momentum is on keeps the long-run step size
+    # at the nominal rate and is what makes the 500-minibatch horizon meaningful.  A Bernoulli
+    # decision whose uniform lies within float32 rounding of its probability may fall differently on the two sides
+    # (excused where |u - p| <= 1e-5), after which the two trajectories are different samples of the same process:
+    # they are compared through the reconstruction-error curves and the final parameters, and the decisions
+    # themselves are checked at three steps against the oracle's probabilities for the DEVICE's parameters of that step.
+    import torch
+    from paper_1507_01239_amd import binding as B
+    n, seed, T, distinct = 256, 41, 500, 16
+    X = [gen.features_speech_like(n, 440, seed, 0, t) for t in range(distinct)]
+    check_at = (0, 250, 499)
+    flips_total = 0
+
+    def run_pair(V, H, vis, flags, lr, layer, inputs):
+        nonlocal flips_total
+        W, a, c = gen.rbm_params(V, H, seed, layer)
+        dv = [dev(t) for t in (W, a, c, np.zeros_like(W), np.zeros_like(a), np.zeros_like(c))]
+        d_in = [dev(v) for v in inputs]
+        err = torch.zeros(T, device="cuda")
+        ws = workspace(B.rbm_workspace_bytes(V, H, n))
+        for t in range(T):
+            if t in check_at:
+                torch.cuda.synchronize()
+                Wg, ag, cg = (host(x).astype(np.float64) for x in dv[:3])
+            B.rbm_cd1_step(V, H, vis, *dv, d_in[t % distinct], n, lr, 0.9, seed, t, layer, flags, err[t:t + 1], ws)
+            if t in check_at:
+                torch.cuda.synchronize()
+                ph0, h0, v1 = _taps(ws, V, H, n)
+                u_h = philox.uniforms(n * H, seed, t, layer, 0).reshape(n, H)
+                u_v = philox.uniforms(n * V, seed, t, layer, 1).reshape(n, V) if (flags & 1) else None
+                s = rbm.cd1_statistics(Wg, ag, cg, inputs[t % distinct], vis, u_h, u_v)
+                flips = host(h0).astype(np.float64) != s["H0"]
+                assert np.all(np.abs(u_h - s["P_h0"])[flips] <= 1e-5), f"unexcused hidden flip at step {t}"
+                flips_total += int(flips.sum())
+                if flags & 1:
+                    s = rbm.cd1_statistics(Wg, ag, cg, inputs[t % distinct], vis, np.where(host(h0) == 1.0, 0.0, 1.0), u_v)
+                    vflips = host(v1).astype(np.float64) != s["V1"]
+                    assert np.all(np.abs(u_v - s["V1mean"])[vflips] <= 1e-5), f"unexcused visible flip at step {t}"
+                    flips_total += int(vflips.sum())
+        torch.cuda.synchronize()
+        # the oracle, free-running over the same horizon
+        W, a, c = (t.astype(np.float64) for t in (W, a, c))
+        MW, Ma, Mc = np.zeros_like(W), np.zeros_like(a), np.zeros_like(c)
+        ref_err = np.zeros(T)
+        for t in range(T):
+            W, a, c, MW, Ma, Mc, info = rbm.cd1_step(W, a, c, MW, Ma, Mc, inputs[t % distinct], vis, lr, 0.9, seed, t, layer,
+                                                     sample_v1=bool(flags & 1))
+            ref_err[t] = info["recon_err"]
+        got_err = host(err).astype(np.float64)
+        curve = np.abs(got_err - ref_err) / ref_err
+        final = [rel_err(host(g), r) for g, r in zip(dv[:3], (W, a, c))]
+        print(f"RBM {V}x{H}: reconstruction error {ref_err[0]:.4g} -> {ref_err[-1]:.4g}; curve deviation max {curve.max():.2e}, "
+              f"mean {curve.mean():.2e}; final W / a / c relative error {final[0]:.2e} / {final[1]:.2e} / {final[2]:.2e}")
+        if vis == B.VIS_GAUSSIAN:
+            assert ref_err[-1] < 0.5 * ref_err[0]              # it learns (a sampled binary reconstruction keeps its sampling noise)
+        assert curve.max() < 1e-2 and curve.mean() < 1e-3      # the same curve, step by step
+        assert max(final) < 1e-2
+        return [host(x) for x in dv[:3]], (W, a, c)
+
+    (Wg, ag, cg), (Wo, ao, co) = run_pair(440, 2048, B.VIS_GAUSSIAN, 0, 0.01 * (1 - 0.9), 0, X)
+    # stacking: each side feeds its second RBM with the hidden probabilities of ITS OWN trained first RBM
+    P_o = [rbm.hidden_prob(x, Wo, co).astype(np.float32) for x in X]
+    ws1 = workspace(B.rbm_workspace_bytes(440, 2048, n))
+    out = torch.empty(n, 2048, device="cuda")
+    B.rbm_hidden_prob(440, 2048, dev(Wg), dev(cg), dev(X[0]), n, out, ws1)
+    torch.cuda.synchronize()
+    assert rel_err(host(out), P_o[0]) < 1e-2
+    run_pair(2048, 2048, B.VIS_BERNOULLI, B.SAMPLE_V1, 0.4 * (1 - 0.9), 1, P_o)
+    print(f"excused decision flips at the {len(check_at)} checked steps of both RBMs: {flips_total}")
