@@ -253,10 +253,11 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
             a.gemm_ws = gws; a.gemm_ws_floats = w.gemm_floats;
             if ((flags & MAVG_NG_FIRST) && ng_layer_update(a, s) != 0) return MAVG_E_LAUNCH;
         }
-        if (!(flags & MAVG_NG_FIRST) && ng_dnn_update(la, y.L, s) != 0) return MAVG_E_LAUNCH;
-        if (!(flags & MAVG_NG_APPLY_ONLY) &&
-            ng_dnn_finish(y.d, y.L, n, k, ng_rank, ng_eta, static_cast<char*>(ng_state), ng_state_stride, ws + w.off_ng, s) != 0)
+        if (!(flags & MAVG_NG_FIRST)) {
+            if (ng_dnn_update(la, y.L, static_cast<char*>(ng_state), ng_state_stride, s) != 0) return MAVG_E_LAUNCH;
+        } else if (ng_dnn_finish(y.d, y.L, n, k, ng_rank, ng_eta, static_cast<char*>(ng_state), ng_state_stride, ws + w.off_ng, s) != 0) {
             return MAVG_E_LAUNCH;
+        }
     }
     return MAVG_OK;
 }

@@ -42,6 +42,10 @@ struct Epilogue {
     //   if rowsum_dst2: rowsum_dst2[b][m] += rowsum_dst[b][m]   (a bias next to its momentum vector)
     float* rowsum_dst = nullptr; int64_t rowsum_bstride = 0; float rowsum_alpha = 1.f, rowsum_beta = 0.f;
     float* rowsum_dst2 = nullptr; int64_t rowsum2_bstride = 0;
+    //   rowsum_w (optional): weights of the sum, sum_k A(m,k) * rowsum_w[b][k] (a matrix-vector product next to the
+    //   matrix-matrix one: the bias gradient when the "ones" column has been preconditioned); the factors
+    //   alpha_dev0[b] * alpha_dev1[b] of alpha apply to rowsum_alpha as well
+    const float* rowsum_w = nullptr; int64_t rowsum_w_bstride = 0;
     uint32_t key0 = 0, key1 = 0, step = 0, layer = 0, phase = 0;   // Philox stream of the sampling epilogue
 };
 

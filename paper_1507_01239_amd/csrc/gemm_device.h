@@ -328,6 +328,7 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
     // delta^T 1 next to the weight gradient delta^T A: taken from the LDS tiles by the first tile column only
     const bool do_rowsum = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0 && tid < BM;
     float rowsum = 0.f;
+    const float* __restrict__ rw = p.epi.rowsum_w ? p.epi.rowsum_w + (int64_t)b * p.epi.rowsum_w_bstride + kbeg : nullptr;
 
     // The loop over k-tiles.  Global loads run PF tiles ahead of the multiply: tile kt+PF is requested while
     // tile kt is multiplied out of LDS, and lives in registers until it is copied to the other LDS buffer
@@ -380,8 +381,14 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
                         });
                     });
                     if (do_rowsum) {
+                        if (rw) {      // (tiles are zero-filled past kend; the weights are not read there)
 #pragma unroll
-                        for (int kk = 0; kk < BK; ++kk) rowsum += As[buf][kk][tid];
+                            for (int kk = 0; kk < BK; ++kk)
+                                if (kbeg + kt * BK + kk < kend) rowsum += As[buf][kk][tid] * rw[kt * BK + kk];
+                        } else {
+#pragma unroll
+                            for (int kk = 0; kk < BK; ++kk) rowsum += As[buf][kk][tid];
+                        }
                     }
                     if (kt + 1 < nkt) {
                         constexpr int nx = (st + 1) % PF;
@@ -400,6 +407,8 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
     if (do_rowsum && m0 + tid < p.M) {
         float* d = p.epi.rowsum_dst + (int64_t)b * p.epi.rowsum_bstride + m0 + tid;
         float r = p.epi.rowsum_alpha * rowsum;
+        if (p.epi.alpha_dev0) r *= p.epi.alpha_dev0[b];
+        if (p.epi.alpha_dev1) r *= p.epi.alpha_dev1[b];
         if (p.epi.rowsum_beta != 0.f) r += p.epi.rowsum_beta * *d;
         *d = r;
         if (p.epi.rowsum_dst2) p.epi.rowsum_dst2[(int64_t)b * p.epi.rowsum2_bstride + m0 + tid] += r;
@@ -605,6 +614,7 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
     });
     const bool do_rowsum = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0 && tid < BM;
     float rowsum = 0.f;
+    const float* __restrict__ rw = p.epi.rowsum_w ? p.epi.rowsum_w + (int64_t)b * p.epi.rowsum_w_bstride + kbeg : nullptr;
 
     if (nkt > 0) {
 #pragma unroll
@@ -627,8 +637,13 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
             constexpr int set = decltype(uc)::value & 1;    // register set of tile t
             multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{});
             if (do_rowsum) {      // the stage is overwritten after the coming barrier: read it before
+                if (rw) {
 #pragma unroll
-                for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * BM + tid];
+                    for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * BM + tid] * rw[t * BK + kk];
+                } else {
+#pragma unroll
+                    for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * BM + tid];
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
             if (t + NST - 1 < nkt) {
@@ -679,7 +694,7 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
                     const int k = ktail + 8 * pr + c;
-                    if (k < kend && m0 + tid < p.M) rowsum += Ab[(int64_t)k * p.lda + m0 + tid];
+                    if (k < kend && m0 + tid < p.M) rowsum += Ab[(int64_t)k * p.lda + m0 + tid] * (rw ? rw[k - kbeg] : 1.f);
                 }
             }
             static_for<4 * TM * TN>([&](auto qc) {
@@ -693,6 +708,8 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
     if (do_rowsum && m0 + tid < p.M) {
         float* d = p.epi.rowsum_dst + (int64_t)b * p.epi.rowsum_bstride + m0 + tid;
         float r = p.epi.rowsum_alpha * rowsum;
+        if (p.epi.alpha_dev0) r *= p.epi.alpha_dev0[b];
+        if (p.epi.alpha_dev1) r *= p.epi.alpha_dev1[b];
         if (p.epi.rowsum_beta != 0.f) r += p.epi.rowsum_beta * *d;
         *d = r;
         if (p.epi.rowsum_dst2) p.epi.rowsum_dst2[(int64_t)b * p.epi.rowsum2_bstride + m0 + tid] += r;

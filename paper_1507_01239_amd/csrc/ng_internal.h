@@ -25,8 +25,10 @@ int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank);
 // left pending (their Y matrices stay in the scratch) until ng_dnn_finish.
 int ng_layer_update(const NgLayerArgs& a, hipStream_t s);
 // The same for all layers of the network at once (layers[l - 1] describes layer l; all share k, n, rank, alpha, eta,
-// ws): one launch per step of the recipe instead of one per step and layer side.  Modes 0 and 1.
-int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s);
+// ws): one launch per step of the recipe instead of one per step and layer side.  Modes 0 and 1; in mode 1 the folds
+// of all 2*L*k states (state (r, j) at ng_state + (r*2L + j)*state_stride bytes) are finished too, on an internal
+// stream beside the weight update when one is available, and joined into `s` before the call's work is complete.
+int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t state_stride, hipStream_t s);
 // Fold this minibatch into all 2*L*k states (after ng_layer_update has run for every layer).
 int ng_dnn_finish(const int* d, int L, int n, int k, int rank, float eta, char* ng_state, int64_t state_stride, float* ws,
                   hipStream_t s);

@@ -16,6 +16,7 @@
 // sides of a backward pass through each step in one launch, ng_run is the same recipe for a table of one.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "../../include/mavg.h"
 #include "device_math.h"
@@ -174,24 +175,46 @@ __global__ __launch_bounds__(256) void ng_z_kernel(NgFoldTable tb, int rank, dou
     }
 }
 
+// Reciprocal square root and reciprocal in float64 from the hardware's approximations and two Newton steps each
+// (relative error at rounding level for normal arguments; no special-case handling: the callers pass positive, finite,
+// normal values).
+__device__ __forceinline__ double fast_rsqrt(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+    y = y * (1.5 - 0.5 * x * y * y);
+    y = y * (1.5 - 0.5 * x * y * y);
+    return y;
+}
+__device__ __forceinline__ double fast_rcp(double x) {
+    double y = __builtin_amdgcn_rcp(x);
+    y = y * (2.0 - x * y);
+    y = y * (2.0 - x * y);
+    return y;
+}
+
 // Symmetric eigen-decomposition of the rank x rank matrix Z by cyclic Jacobi rotations in a round-robin
 // (tournament) order, so that the rank/2 disjoint rotations of a round are applied in parallel, rows and
 // columns in one pass (the column partner's entries come from a neighbouring lane); then the
 // new d, rho, t and the matrix Wt = diag(c)^-1/2 U^T (rows in descending order of c).
+//
+// Threads form groups of 32 lanes (64 above rank 32), lane l standing for index l of the matrix.  In round `rd` of
+// the tournament among m = rank rounded up to even players, player m-1 meets player rd and every other player l
+// meets (2 rd - l) mod (m - 1); an odd rank leaves the player that would meet the dummy idle.  Every lane works out
+// the rotation of its own index's pair from the three entries it depends on (all groups do so redundantly: no
+// hand-over through LDS, no barrier between computing the rotations and applying them); the group that owns a pair's
+// two rows takes that pair's rotation from its lane p.  Z and U^T are kept twice: a round reads one copy and writes the
+// other (every row belongs to exactly one pair, or is the idle one, and is written once per round), so a wavefront
+// that is ahead never overwrites what a slower one still has to read, and one barrier per round is enough.
 __global__ __launch_bounds__(kEigThreads) void ng_eig_kernel(NgFoldTable tb, int rank, int n, float eta, const double* __restrict__ Zg,
                                                      double* __restrict__ Wt, int bump_t) {
     extern __shared__ double smem[];
     const int r = rank;
-    const int rs = r | 1;            // odd row stride: column walks spread over the LDS banks
-    double* Zs = smem;               // r x rs
+    const int rs = (r + 1) & ~1;     // even row stride: the diagonal (stride rs + 1 doubles, odd) spreads over all LDS banks
+    double* Zs = smem;               // r x rs, current copy (the two copies swap after every round)
     double* Us = Zs + r * rs;        // r x rs, holds U TRANSPOSED (row k = eigenvector k), so its update is a row rotation
-    double* al = Us + r * rs;        // 64: a round turns row (and column) i into al[i] row_i + be[i] row_partner(i)
-    double* be = al + 64;            // 64
-    double* red = be + 64;           // 8
-    int* pp = reinterpret_cast<int*>(red + 8);   // 32 + 32 pair indices
-    int* qq = pp + 32;
-    int* order = qq + 32;            // 64
-    int* partner = order + 64;       // 64
+    double* Zn = Us + r * rs;        // the copies the current round writes
+    double* Un = Zn + r * rs;
+    double* red = Un + r * rs;       // 16
+    int* order = reinterpret_cast<int*>(red + 16);   // 64
     const int slot = blockIdx.x / tb.batch, b = blockIdx.x - slot * tb.batch, tid = threadIdx.x;
     const int dim = tb.dim[slot];
     const int64_t zi = (int64_t)(tb.first + slot) * tb.batch + b;
@@ -207,74 +230,83 @@ __global__ __launch_bounds__(kEigThreads) void ng_eig_kernel(NgFoldTable tb, int
     __syncthreads();
     const int m = (r + 1) & ~1;      // even number of players
     const int half = m / 2;
+    const bool on = lane < r;
     int sweeps_done = 0;
     bool converged = false;
     for (int sweep = 0; sweep <= kJacobiSweeps; ++sweep) {
         // stop when the off-diagonal mass is negligible against the diagonal
         double off = 0.0, dg = 0.0;
         for (int i = grp; i < r; i += ngrp)
-            if (lane < r) {
+            if (on) {
                 const double v = Zs[i * rs + lane];
                 if (i == lane) dg += v * v; else off += v * v;
             }
-        off = block_sum_eig(off, red);
-        dg = block_sum_eig(dg, red);
+        off = wave_sum(off);
+        dg = wave_sum(dg);
+        if ((tid & 63) == 0) { red[tid >> 6] = off; red[8 + (tid >> 6)] = dg; }
+        __syncthreads();
+        off = ((red[0] + red[1]) + (red[2] + red[3])) + ((red[4] + red[5]) + (red[6] + red[7]));
+        dg = ((red[8] + red[9]) + (red[10] + red[11])) + ((red[12] + red[13]) + (red[14] + red[15]));
+        __syncthreads();
         // off-diagonal norm below 1e-13 of the diagonal: Z spans many orders of magnitude, and a looser stop (1e-10)
         // leaves its small eigenvalues, hence the weak rows of R, outside the parity tolerance
         if (off <= 1e-26 * dg) { converged = true; break; }
         if (sweep == kJacobiSweeps) break;          // out of sweeps: the state's info word counts it
         ++sweeps_done;
         for (int round = 0; round < m - 1; ++round) {
-            // Z <- J^T Z J, U^T <- J^T U^T with, for every pair (p, q) of the round,
+            // Z <- J^T Z J, U^T <- J^T U^T with, for every pair (p, q), p < q, of the round,
             // row_p <- c row_p - s row_q,  row_q <- s row_p + c row_q  (and the same for the columns of Z)
-            if (tid < half) {
-                int p, q;
-                if (tid == 0) { p = m - 1; q = round; }
-                else { p = (round + tid) % (m - 1); q = (round - tid + (m - 1)) % (m - 1); }
-                if (p > q) { const int t = p; p = q; q = t; }
-                if (q < r) {
-                    double c = 1.0, s = 0.0;
-                    const double apq = Zs[p * rs + q];
-                    if (apq != 0.0) {
-                        // t = sgn(tau) / (|tau| + sqrt(1 + tau^2)) with tau = (aqq - app) / (2 apq), written with one
-                        // square root, one division and one reciprocal square root
-                        const double d = Zs[q * rs + q] - Zs[p * rs + p], b2 = 2.0 * apq;
-                        const double t = (d >= 0.0 ? b2 : -b2) / (fabs(d) + sqrt(d * d + b2 * b2));
-                        c = rsqrt(1.0 + t * t);
-                        s = t * c;
-                    }
-                    al[p] = c; be[p] = -s; partner[p] = q;
-                    al[q] = c; be[q] = s;  partner[q] = p;
-                } else {          // the bye of an odd rank: row and column p stay
-                    al[p] = 1.0; be[p] = 0.0; partner[p] = p;
-                    q = -1;
-                }
-                pp[tid] = p; qq[tid] = q;
+            int pl = lane;                               // the index this lane's index meets (itself: idle)
+            if (on) {
+                int w = 2 * round - lane;                // in (-(m-1), 2(m-1)): reduce mod m-1 without a division
+                if (w < 0) w += m - 1;
+                if (w >= m - 1) w -= m - 1;
+                pl = lane == m - 1 ? round : lane == round ? m - 1 : w;
+                if (pl >= r) pl = lane;                  // the bye of an odd rank
             }
-            __syncthreads();
+            double cl = 1.0, sl = 0.0;                   // rotation of the pair this lane's index is in
+            if (pl != lane) {
+                const int p = min(lane, pl), q = max(lane, pl);
+                const double app = Zs[p * rs + p], aqq = Zs[q * rs + q], apq = Zs[p * rs + q];
+                // t = sgn(tau) / (|tau| + sqrt(1 + tau^2)) with tau = (aqq - app) / (2 apq)
+                const double d = aqq - app, b2 = 2.0 * apq;
+                const double h2 = d * d + b2 * b2;
+                if (apq != 0.0 && h2 > 1e-280) {         // (below that the entry is nothing against any diagonal)
+                    const double t = (d >= 0.0 ? b2 : -b2) * fast_rcp(fabs(d) + h2 * fast_rsqrt(h2));
+                    cl = fast_rsqrt(1.0 + t * t);
+                    sl = t * cl;
+                }
+            }
+            // row `lane` (and column `lane`) turns into al row_lane + bl row_partner
+            const double al = cl, bl = lane < pl ? -sl : sl;
             // One pass: the group of pair k holds rows p and q; lane l rotates the rows (in registers), fetches the
             // rotated entries of column partner(l) from the lane that holds them and rotates the columns.
             for (int k = grp; k < half; k += ngrp) {
-                const int p = pp[k], q = qq[k];
-                const bool on = lane < r, two = q >= 0;
-                const double c = al[p], s = two ? be[q] : 0.0;
+                int p, q;
+                if (k == 0) { p = m - 1; q = round; }
+                else {
+                    p = round + k;     if (p >= m - 1) p -= m - 1;
+                    q = round - k;     if (q < 0) q += m - 1;
+                }
+                if (p > q) { const int t = p; p = q; q = t; }
+                const bool two = q < r;                  // else the bye: row and column p stay
                 const int qr = two ? q : p;
+                const double c = two ? __shfl(cl, p, lw) : 1.0, s = two ? __shfl(sl, p, lw) : 0.0;
                 const double zp = on ? Zs[p * rs + lane] : 0.0, zq = (on && two) ? Zs[qr * rs + lane] : 0.0;
                 const double up = on ? Us[p * rs + lane] : 0.0, uq = (on && two) ? Us[qr * rs + lane] : 0.0;
                 const double wp = c * zp - s * zq, wq = s * zp + c * zq;
-                const int pl = on ? partner[lane] : lane;
-                const double a = on ? al[lane] : 1.0, bb = on ? be[lane] : 0.0;
                 const double wpo = __shfl(wp, pl, lw), wqo = __shfl(wq, pl, lw);
                 if (on) {
-                    Zs[p * rs + lane] = a * wp + bb * wpo;
-                    Us[p * rs + lane] = c * up - s * uq;
+                    Zn[p * rs + lane] = al * wp + bl * wpo;
+                    Un[p * rs + lane] = c * up - s * uq;
                     if (two) {
-                        Zs[q * rs + lane] = a * wq + bb * wqo;
-                        Us[q * rs + lane] = s * up + c * uq;
+                        Zn[q * rs + lane] = al * wq + bl * wqo;
+                        Un[q * rs + lane] = s * up + c * uq;
                     }
                 }
             }
             __syncthreads();
+            { double* t = Zs; Zs = Zn; Zn = t; t = Us; Us = Un; Un = t; }
         }
     }
     // descending order of the eigenvalues (ties by index)
@@ -440,9 +472,10 @@ struct NgSlots {
     double* part;                               // at + q * 256
     double* scal;                               // at + q * 2: ||X||^2, ||Xh||^2
     float* gamma;                               // at + q
+    float* wcol = nullptr;                      // optional, at + q * n: receives the last column of the preconditioned matrix
 };
 
-__global__ __launch_bounds__(256) void ng_sumsq_partial_slots_kernel(NgSlots t) {
+__global__ __launch_bounds__(256) void ng_sumsq_partial_slots_kernel(NgSlots t, int write_lastcol) {
     __shared__ double sh[4];
     const int slot = blockIdx.y, b = blockIdx.z;
     const int64_t q = (int64_t)slot * t.batch + b;
@@ -453,6 +486,7 @@ __global__ __launch_bounds__(256) void ng_sumsq_partial_slots_kernel(NgSlots t) 
     double s = 0.0;
     for (int r = blockIdx.x; r < n; r += gridDim.x) {
         const float* __restrict__ row = xb + (int64_t)r * ldx;
+        if (write_lastcol && threadIdx.x == 0) t.wcol[q * n + r] = row[dim - 1];
         float a = 0.f;
         if (vec) {
             const int nq = dim >> 2;
@@ -657,10 +691,11 @@ struct NgCall {
     } while (0)
 #define NG_LAUNCHED() NG_CHECK(note_hip_error(hipGetLastError()))
 
-int ng_eig_smem_bytes(int rank) { return (2 * rank * (rank | 1) + 64 + 64 + 8) * 8 + (32 + 32 + 64 + 64) * 4; }
+int ng_eig_smem_bytes(int rank) { return (4 * rank * ((rank + 1) & ~1) + 16) * 8 + 64 * 4; }
 
-// Z = Y Y^T, eigen-decomposition, new (R, d, rho, t) for every (slot, replica) of the table: three launches.
-int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, double* Wt, int bump, hipStream_t s) {
+// Z = Y Y^T and its eigen-decomposition, new (d, rho, t) and Wt for every (slot, replica) of the table: two launches.
+// Reads Y, the squared norms and the old d, rho; does not touch R.
+int ng_finish_zeig(const NgFoldTable& tb, int rank, int n, float eta, bool y64, double* Z, double* Wt, int bump, hipStream_t s) {
     const int smem = ng_eig_smem_bytes(rank);
     if (smem > 64 * 1024) {
         static bool raised = false;     // idempotent; benign if two threads race to set the same value
@@ -670,14 +705,19 @@ int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, d
             raised = true;
         }
     }
-    int maxdim = 0;
-    for (int i = 0; i < tb.nslots; ++i) if (tb.dim[i] > maxdim) maxdim = tb.dim[i];
     const dim3 gz(rank * rank, tb.nslots, tb.batch);
     if (y64) hipLaunchKernelGGL(ng_z_kernel<double>, gz, dim3(256), 0, s, tb, rank, Z);
     else hipLaunchKernelGGL(ng_z_kernel<float>, gz, dim3(256), 0, s, tb, rank, Z);
     NG_LAUNCHED();
     hipLaunchKernelGGL(ng_eig_kernel, dim3(tb.nslots * tb.batch), dim3(kEigThreads), smem, s, tb, rank, n, eta, Z, Wt, bump);
     NG_LAUNCHED();
+    return 0;
+}
+
+// R <- Wt Y for every (slot, replica) of the table: the one step of a fold that writes R.
+int ng_finish_newr(const NgFoldTable& tb, int rank, bool y64, const double* Wt, hipStream_t s) {
+    int maxdim = 0;
+    for (int i = 0; i < tb.nslots; ++i) if (tb.dim[i] > maxdim) maxdim = tb.dim[i];
     const dim3 gr((unsigned)((maxdim + 3 + 31) / 32), tb.nslots, tb.batch);
     if (y64) hipLaunchKernelGGL(ng_newr_kernel<double>, gr, dim3(256), 0, s, tb, rank, Wt);
     else hipLaunchKernelGGL(ng_newr_kernel<float>, gr, dim3(256), 0, s, tb, rank, Wt);
@@ -685,9 +725,15 @@ int ng_finish(NgFoldTable tb, int rank, int n, float eta, bool y64, double* Z, d
     return 0;
 }
 
+int ng_finish(const NgFoldTable& tb, int rank, int n, float eta, bool y64, double* Z, double* Wt, int bump, hipStream_t s) {
+    NG_CHECK(ng_finish_zeig(tb, rank, n, eta, y64, Z, Wt, bump, s));
+    return ng_finish_newr(tb, rank, y64, Wt, s);
+}
+
 // Host side of the steps of the apply for a table of slots.
 int ng_slots_norms(const NgSlots& t, int which, float alpha, float eta, hipStream_t s) {
-    hipLaunchKernelGGL(ng_sumsq_partial_slots_kernel, dim3(256, t.nslots, t.batch), dim3(256), 0, s, t);
+    hipLaunchKernelGGL(ng_sumsq_partial_slots_kernel, dim3(256, t.nslots, t.batch), dim3(256), 0, s, t,
+                       (which == 1 && t.wcol != nullptr) ? 1 : 0);
     NG_LAUNCHED();
     hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, which, alpha, eta);
     NG_LAUNCHED();
@@ -839,7 +885,7 @@ struct NgDnnLayout {
     // all layers at once: augmented inputs of every layer, then per-(slot, replica) H, H2, coefficients, partial
     // sums and gamma
     int64_t xaug_off[64 + 1], ld_in[64 + 1];
-    int64_t ldr, H_b, h_off, h2_off, coef_off, part_off, gamma_off, hp_off;
+    int64_t ldr, H_b, h_off, h2_off, coef_off, part_off, gamma_off, hp_off, wcol_off;
 };
 NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     NgDnnLayout y;
@@ -878,6 +924,7 @@ NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     int64_t nprob = 0;
     for (int l = 1; l <= L; ++l) nprob += ng_chunk_count(d[l - 1] + 1) + ng_chunk_count(d[l]);
     y.hp_off = off;    off += nprob * k * y.H_b;
+    y.wcol_off = off;  off += round_up(q * n, 64);
     y.total = off;
     return y;
 }
@@ -885,25 +932,58 @@ NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
 
 int64_t ng_dnn_ws_floats(const int* d, int L, int n, int k, int rank) { return ng_dnn_layout(d, L, n, k, rank).total; }
 
+namespace {
+// The fold table of slots [j0, j0 + nslots) of a network's 2 L layer sides.
+NgFoldTable ng_dnn_fold_table(const NgDnnLayout& y, const int* d, int L, int k, char* ng_state, int64_t state_stride, float* ws, int j0) {
+    double* scal = reinterpret_cast<double*>(ws + y.scal_off);
+    NgFoldTable tb;
+    tb.nslots = (2 * L - j0) < kNgSlots ? (2 * L - j0) : kNgSlots;
+    tb.batch = k; tb.first = j0; tb.st_b = (int64_t)2 * L * state_stride;
+    for (int i = 0; i < tb.nslots; ++i) {
+        const int j = j0 + i, l = j / 2 + 1;
+        tb.state[i] = ng_state + (int64_t)j * state_stride;
+        tb.dim[i] = (j % 2 == 0) ? d[l - 1] + 1 : d[l];
+        tb.Y[i] = ws + y.y_off[j];
+        tb.y_b[i] = y.y_b[j];
+        tb.scal[i] = scal + (int64_t)j * k * 2;
+    }
+    return tb;
+}
+
+// One internal stream and three events per host thread and device, created on first use and kept until the
+// process ends (default priority, no timing): the folds of the Fisher states run there beside the weight update.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    bool ok = false, tried = false;
+};
+SideStream* side_stream() {
+    constexpr int kMaxDev = 64;
+    static thread_local SideStream table[kMaxDev];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return nullptr;
+    SideStream& ss = table[dev];
+    if (!ss.tried) {
+        ss.tried = true;
+        const char* serial = getenv("MAVG_NG_SERIAL_FOLD");       // "1": keep every launch on the caller's stream
+        if (serial && serial[0] == '1') return nullptr;
+        bool good = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess;
+        for (int i = 0; i < 3 && good; ++i) good = hipEventCreateWithFlags(&ss.ev[i], hipEventDisableTiming) == hipSuccess;
+        if (!good) (void)hipGetLastError();      // fall back to the caller's stream alone
+        ss.ok = good;
+    }
+    return ss.ok ? &ss : nullptr;
+}
+}  // namespace
+
 // Finish the folds of all layer sides and replicas of one backward pass (three launches per 32 slots).
 int ng_dnn_finish(const int* d, int L, int n, int k, int rank, float eta, char* ng_state, int64_t state_stride, float* ws,
                   hipStream_t s) {
     const NgDnnLayout y = ng_dnn_layout(d, L, n, k, rank);
-    double* scal = reinterpret_cast<double*>(ws + y.scal_off);
     double* Z = reinterpret_cast<double*>(ws + y.z_off);
     double* Wt = reinterpret_cast<double*>(ws + y.wt_off);
     for (int j0 = 0; j0 < 2 * L; j0 += kNgSlots) {
-        NgFoldTable tb;
-        tb.nslots = (2 * L - j0) < kNgSlots ? (2 * L - j0) : kNgSlots;
-        tb.batch = k; tb.first = j0; tb.st_b = (int64_t)2 * L * state_stride;
-        for (int i = 0; i < tb.nslots; ++i) {
-            const int j = j0 + i, l = j / 2 + 1;
-            tb.state[i] = ng_state + (int64_t)j * state_stride;
-            tb.dim[i] = (j % 2 == 0) ? d[l - 1] + 1 : d[l];
-            tb.Y[i] = ws + y.y_off[j];
-            tb.y_b[i] = y.y_b[j];
-            tb.scal[i] = scal + (int64_t)j * k * 2;
-        }
+        const NgFoldTable tb = ng_dnn_fold_table(y, d, L, k, ng_state, state_stride, ws, j0);
         NG_CHECK(ng_finish(tb, rank, n, eta, false, Z, Wt, 1, s));
     }
     return 0;
@@ -959,12 +1039,20 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
 // The preconditioned update of every layer (steady state: one fold per minibatch), a fixed number of launches
 // whatever the depth: augment, ||X||^2 + coefficients, H, Y, X1, H2, combine, Xh, ||Xh||^2 + gamma, then the weight
 // gradients of all layers as one grouped launch.  The folds stay pending until ng_dnn_finish.
-int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
+int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t state_stride, hipStream_t s) {
     const NgLayerArgs& a0 = layers[0];
     const int n = a0.n, k = a0.k, rank = a0.rank;
     const NgDnnLayout lay = ng_dnn_layout(a0.dims, L, n, k, rank);
     if (a0.ws_floats < lay.total) return (int)hipErrorInvalidValue;
     float* ws = a0.ws;
+    // The fold (Z = Y Y^T, its eigen-decomposition, R <- Wt Y) needs only Y, the squared norms and the old state, and
+    // is a chain of small, latency-bound launches (14 workgroups in the eigen-solver): with all layers in one pass it
+    // runs on the internal stream beside the rest of the apply and the weight update, which occupy the whole chip.
+    // Its last step, the only one that writes R, waits until the apply has read R for the last time; the caller's
+    // stream waits for it before this call's work is complete.
+    SideStream* side = (a0.mode == 1 && L <= kNgSlots / 2) ? side_stream() : nullptr;
+    double* Zf = reinterpret_cast<double*>(ws + lay.z_off);
+    double* Wtf = reinterpret_cast<double*>(ws + lay.wt_off);
     double* scal = reinterpret_cast<double*>(ws + lay.scal_off);
     constexpr int kLayersPerPass = kNgSlots / 2;
     for (int l0 = 0; l0 < L; l0 += kLayersPerPass) {
@@ -980,6 +1068,7 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
         t.part = reinterpret_cast<double*>(ws + lay.part_off) + (int64_t)j0 * k * 256;
         t.scal = scal + (int64_t)j0 * k * 2;
         t.gamma = ws + lay.gamma_off + (int64_t)j0 * k;
+        t.wcol = ws + lay.wcol_off + (int64_t)j0 * k * n;
         au.n = n;
         int64_t max_aug = 0;
         for (int i = 0; i < nl; ++i) {
@@ -1020,18 +1109,33 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
                 q.epi.aux = reinterpret_cast<const float*>(t.state[j]); q.epi.ldaux = ld; q.epi.aux_bstride = t.st_b / 4;
             }
             NG_CHECK(gemm_launch_grouped(g, t.nslots, s));
+            if (side) {
+                NG_CHECK(note_hip_error(hipEventRecord(side->ev[0], s)));
+                NG_CHECK(note_hip_error(hipStreamWaitEvent(side->stream, side->ev[0], 0)));
+                const NgFoldTable tb = ng_dnn_fold_table(lay, a0.dims, L, k, ng_state, state_stride, ws, 0);
+                NG_CHECK(ng_finish_zeig(tb, rank, n, a0.eta, false, Zf, Wtf, 1, side->stream));
+            }
         }
         NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s));       // X1 = X - H R
         NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s));            // H2 = X1 R^T
         NG_CHECK(ng_slots_combine(t, s));
         NG_CHECK(ng_slots_rank_update(t, 1, 1.f, s));        // Xh = X1 + (H (I - E) - H2) R
+        if (side) {      // R has been read for the last time: the fold may write it
+            NG_CHECK(note_hip_error(hipEventRecord(side->ev[1], s)));
+            NG_CHECK(note_hip_error(hipStreamWaitEvent(side->stream, side->ev[1], 0)));
+            const NgFoldTable tb = ng_dnn_fold_table(lay, a0.dims, L, k, ng_state, state_stride, ws, 0);
+            NG_CHECK(ng_finish_newr(tb, rank, false, Wtf, side->stream));
+            NG_CHECK(note_hip_error(hipEventRecord(side->ev[2], side->stream)));
+        }
         NG_CHECK(ng_slots_norms(t, 1, a0.alpha, a0.eta, s));
-        {   // [W | b] <- [W | b] - lr g_out g_in Xh_out^T Xh_in for the layers of this pass
+        {   // W <- W - lr g_out g_in Xh_out^T Xh_in[:, :d_in] for the layers of this pass, and as the weighted row sums
+            // of the same launch b <- b - lr g_out g_in Xh_out^T Xh_in[:, d_in] (the preconditioned "ones" column,
+            // left contiguous by the pass that took the norms)
             GemmDesc g[kLayersPerPass];
             for (int i = 0; i < nl; ++i) {
                 const NgLayerArgs& a = layers[l0 + i];
                 GemmDesc& q = g[i];
-                q.M = a.d_out; q.N = a.d_in + 1; q.K = n; q.batch = k;
+                q.M = a.d_out; q.N = a.d_in; q.K = n; q.batch = k;
                 q.A = a.delta; q.lda = a.ldd; q.a_bstride = a.d_bstride; q.a_kc = false;
                 q.a_pad4 = true;
                 q.B = t.x[2 * i]; q.ldb = t.ldx[2 * i]; q.b_bstride = t.x_b[2 * i]; q.b_kc = false;
@@ -1039,11 +1143,14 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, hipStream_t s) {
                 q.C = a.W; q.ldc = a.d_in; q.c_bstride = a.theta_stride;
                 q.epi.kind = EPI_AXPBY; q.epi.alpha = -a.lr; q.epi.beta = 1.f;
                 q.epi.alpha_dev0 = t.gamma + (int64_t)(2 * i) * k; q.epi.alpha_dev1 = t.gamma + (int64_t)(2 * i + 1) * k;
-                q.epi.lastcol = a.d_in; q.epi.lastcol_dst = a.b; q.epi.lastcol_bstride = a.theta_stride;
+                q.epi.rowsum_dst = a.b; q.epi.rowsum_bstride = a.theta_stride; q.epi.rowsum_alpha = -a.lr; q.epi.rowsum_beta = 1.f;
+                q.epi.rowsum_w = t.wcol + (int64_t)(2 * i) * k * n; q.epi.rowsum_w_bstride = n;
             }
             NG_CHECK(gemm_launch_grouped(g, nl, s));
         }
     }
+    if (side) NG_CHECK(note_hip_error(hipStreamWaitEvent(s, side->ev[2], 0)));
+    else if (a0.mode == 1) NG_CHECK(ng_dnn_finish(a0.dims, L, n, k, rank, a0.eta, ng_state, state_stride, ws, s));
     return 0;
 }
 
