@@ -98,9 +98,11 @@ __device__ __forceinline__ const float* at_off(const float* ubase, uint32_t off)
 // row 8*(v/4) + 4*(lane/32) + v%4, column lane%32 of its 32x32 block.  `mbase` is uniform over the wavefront.
 // Every access is (uniform row pointer) + (per-lane byte offset): row 8*(v/4) + v%4 of the block goes into the
 // scalar pointer, the lane's 4*(lane/32) rows and its column into one offset register per matrix.
+// `band` (uniform over the wavefront): -1 = all 16 elements; 0..3 = only elements 4 band .. 4 band + 3, i.e. rows
+// 8 band .. 8 band + 7 of each 32x32 block (a workgroup whose wavefronts share the epilogue of one accumulator).
 template <int KIND, int TM, int TN>
 __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const Epilogue& e, const EpiCtx& c,
-                                           int64_t ldc, int M, int N, int mbase, int nbase, int lrow, int lcol) {
+                                           int64_t ldc, int M, int N, int mbase, int nbase, int lrow, int lcol, int band = -1) {
     constexpr bool kReadsC = KIND == EPI_AXPBY;
     constexpr bool kReadsAux = KIND == EPI_MUL_DSIGMOID || KIND == EPI_ROWSCALE_ADD;
     constexpr bool kBias = KIND == EPI_BIAS || KIND == EPI_BIAS_SIGMOID || KIND == EPI_BIAS_SIGMOID_SAMPLE;
@@ -135,7 +137,7 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                     const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
                     const int m = mu + 4 * lrow;
                     old[v] = 0.f;
-                    if (need_old && (IN || m < M) && n_ok) {
+                    if (need_old && (band < 0 || band == (v >> 2)) && (IN || m < M) && n_ok) {
                         if constexpr (kReadsC) old[v] = lastcol ? c.lastcol_dst[m] : *at_off(c.C + (int64_t)mu * ldc, offC);
                         else old[v] = *at_off(c.aux + (int64_t)mu * e.ldaux, offAux);
                     }
@@ -145,7 +147,7 @@ __device__ __forceinline__ void write_tile(const floatx16 (&acc)[TM][TN], const 
                 constexpr int v = decltype(vc)::value;
                 const int mu = mb + i * 32 + 8 * (v >> 2) + (v & 3);
                 const int m = mu + 4 * lrow;
-                if ((IN || m < M) && n_ok) {
+                if ((band < 0 || band == (v >> 2)) && (IN || m < M) && n_ok) {
                     const float a = acc[i][j][v];
                     float* dst = at_off(c.C + (int64_t)mu * ldc, offC);
                     if constexpr (KIND == EPI_STORE) {
@@ -932,22 +934,25 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     }
 
     // Add the k-groups' accumulators in group order.  Every read of the rings is behind the last barrier of the loop
-    // and every load has landed, so a k-group parks its accumulators in its own B ring (1024 floats per wavefront).
+    // and every load has landed, so each k-group parks its accumulators in its own B ring (1024 floats per wavefront).
+    // The sum and the epilogue are shared out: with four k-groups, group g adds up and writes elements 4 g .. 4 g + 3
+    // of every lane (rows 8 g .. 8 g + 7 of the 32x32 block), so that all wavefronts work through the tail of the
+    // kernel (transcendentals, sampling, the loads and stores of the epilogue) instead of one group in four.
     float* red = &Bs[kg][0][0] + gw * 1024;
-    if (kg > 0) {
-        static_for<16>([&](auto vc) { red[decltype(vc)::value * 64 + lane] = acc[0][0][decltype(vc)::value]; });
-    }
+    static_for<16>([&](auto vc) { red[decltype(vc)::value * 64 + lane] = acc[0][0][decltype(vc)::value]; });
     __syncthreads();
-    if (kg > 0) return;
+    static_assert(KG == 4, "the epilogue is shared out in bands of 16 / 4 elements");
     static_for<16>([&](auto vc) {
         constexpr int v = decltype(vc)::value;
-        float r = acc[0][0][v];
+        if ((v >> 2) == kg) {       // (uniform over the wavefront)
+            float r = (&Bs[0][0][0] + gw * 1024)[v * 64 + lane];
 #pragma unroll
-        for (int g = 1; g < KG; ++g) r += (&Bs[g][0][0] + gw * 1024)[v * 64 + lane];
-        acc[0][0][v] = r;
+            for (int g = 1; g < KG; ++g) r += (&Bs[g][0][0] + gw * 1024)[v * 64 + lane];
+            acc[0][0][v] = r;
+        }
     });
     const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
-    MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0, n0 + wn, lrow, lcol)))
+    MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, 1, 1>(acc, p.epi, c, p.ldc, p.M, p.N, m0, n0 + wn, lrow, lcol, kg)))
 }
 
 // The 32x64 variant (one workgroup per compute unit) takes k-tiles of 32 steps in a ring of three stages (144 KB of
