@@ -32,6 +32,7 @@ constexpr double kEps = 1e-10, kDelta = 5e-4, kCFloor = 1e-24;
 constexpr int kInitFolds = 3;
 constexpr int kMaxRank = 64;
 constexpr int kJacobiSweeps = 14;
+constexpr int kNgParts = 2048;     // partial sums of squares per (slot, replica)
 
 inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
@@ -81,7 +82,7 @@ NgWs ng_ws(int dim, int rank, int n, int batch) {
     w.off_coef = off;  off += w.coef_b * batch;
     w.off_gamma = off; off += round_up(2 * (int64_t)batch, 64);
     w.off_scal = off;  off += round_up(2 * 2 * (int64_t)batch, 64);
-    w.off_part = off;  off += 2 * 256 * (int64_t)batch;
+    w.off_part = off;  off += 2 * kNgParts * (int64_t)batch;
     w.off_Z = off;     off += 2 * (int64_t)kMaxRank * kMaxRank * batch;
     w.off_Wt = off;    off += 2 * (int64_t)kMaxRank * kMaxRank * batch;
     w.H64_b = 2 * (int64_t)n * kMaxRank;
@@ -469,7 +470,7 @@ struct NgSlots {
     // scratch with one stride per (slot, replica) pair q = slot * batch + b
     float* H; float* H2; int64_t ldr, H_b;      // n x ldr each, at + q * H_b
     float* coef;                                // at + q * 3 kMaxRank
-    double* part;                               // at + q * 256
+    double* part;                               // at + q * kNgParts
     double* scal;                               // at + q * 2: ||X||^2, ||Xh||^2
     float* gamma;                               // at + q
     float* wcol = nullptr;                      // optional, at + q * n: receives the last column of the preconditioned matrix
@@ -512,25 +513,29 @@ __global__ __launch_bounds__(256) void ng_sumsq_partial_slots_kernel(NgSlots t, 
         s += (double)a;
     }
     s = block_sum_d(s, sh);
-    if (threadIdx.x == 0) t.part[q * 256 + blockIdx.x] = s;
+    if (threadIdx.x == 0) t.part[q * kNgParts + blockIdx.x] = s;
 }
 
-// which == 0: scal[q][0] = ||X||^2 and the coefficients of the apply and the fold (as ng_coeff_kernel);
-// which == 1: scal[q][1] = ||Xh||^2 and gamma[q] = ||X|| / ||Xh|| (1 if either is 0)
-__global__ __launch_bounds__(256) void ng_sumsq_final_slots_kernel(NgSlots t, int which, float alpha, float eta) {
+// what & 1: sum the first `nparts` partial sums of every (slot, replica) in index order into scal[q][which]
+//           (which 0: ||X||^2, which 1: ||Xh||^2 and gamma[q] = ||X|| / ||Xh||, 1 if either is 0);
+// what & 2: the coefficients of the apply and the fold from the state (e, (1 - eta)(d + rho), 1 - e)
+__global__ __launch_bounds__(256) void ng_sumsq_final_slots_kernel(NgSlots t, int which, float alpha, float eta, int nparts, int what) {
     __shared__ double sh[4];
     const int slot = blockIdx.x, b = blockIdx.y;
     const int64_t q = (int64_t)slot * t.batch + b;
-    double s = t.part[q * 256 + threadIdx.x];
-    s = block_sum_d(s, sh);
-    if (threadIdx.x == 0) {
-        t.scal[q * 2 + which] = s;
-        if (which == 1) {
-            const double nx = t.scal[q * 2 + 0];
-            t.gamma[q] = (nx > 0.0 && s > 0.0) ? (float)sqrt(nx / s) : 1.f;
+    if (what & 1) {
+        double s = 0.0;
+        for (int i = threadIdx.x; i < nparts; i += 256) s += t.part[q * kNgParts + i];
+        s = block_sum_d(s, sh);
+        if (threadIdx.x == 0) {
+            t.scal[q * 2 + which] = s;
+            if (which == 1) {
+                const double nx = t.scal[q * 2 + 0];
+                t.gamma[q] = (nx > 0.0 && s > 0.0) ? (float)sqrt(nx / s) : 1.f;
+            }
         }
     }
-    if (which == 0) {
+    if (what & 2) {
         const int dim = t.dim[slot], rank = t.rank;
         const StateView v = state_view(t.state[slot] + (int64_t)b * t.st_b, dim, rank);
         double sumd = 0.0;
@@ -584,62 +589,86 @@ __global__ __launch_bounds__(256) void ng_combine_slots_kernel(NgSlots t) {
 // columns, keeps its 32 (x KH) x 32 block of R in registers as MFMA B operands and walks down `rows` rows in tiles
 // of 32; per tile it reads 32 x rank of Cm (16 contiguous floats per lane) and 32 x 32 of X, multiplies with
 // 16 KH v_mfma_f32_32x32x2_f32 and adds the product to X.  Contraction index of MFMA step s: k = 32 kh + s in
-// lanes 0-31 and 32 kh + 16 + s in lanes 32-63, zero operands beyond `rank`.  No LDS, no barrier.
+// lanes 0-31 and 32 kh + 16 + s in lanes 32-63, zero operands beyond `rank`.  No LDS in the loop, no barrier.
+//
+// `fuse` folds the passes over the matrices that take the norms into the two rank updates of a preconditioning:
+//   0  nothing else;
+//   1  (first update, X1 = X - H R) also leaves the workgroup's share of ||X||^2, of X as it was read;
+//   2  (second update) also leaves the workgroup's share of ||Xh||^2 of the result, and the result's last column in
+//      t.wcol.
+// The shares go to t.part[q][blockIdx.y * gridDim.x + blockIdx.x] (0 from workgroups beyond the slot's width).
+// (Summing the chunks of H2 and forming H (I - E) - H2 on the way in as well was measured slower: every one of the
+// up to 250 column blocks of a slot would redo that sum.)
 typedef float ng_floatx16 __attribute__((ext_vector_type(16)));
 template <int KH>
-__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows) {
+__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows, int fuse) {
+    __shared__ double sh[4];
     const int slot = blockIdx.z / t.batch, b = blockIdx.z - slot * t.batch;
     const int dim = t.dim[slot], n = t.n, rank = t.rank;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, lc = lane & 31;
     const int c0 = (blockIdx.x * 4 + wave) * 32;
-    if (c0 >= dim) return;                              // the grid is as wide as the widest slot
-    const int col = c0 + lc;
-    const bool col_ok = col < dim;
     const int64_t q = (int64_t)slot * t.batch + b;
-    const int64_t ldR = ((int64_t)dim + 3) / 4 * 4, ldx = t.ldx[slot], ldc = t.ldr;
-    const float* __restrict__ R = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b);
-    const float* __restrict__ C = (use_h2 ? t.H2 : t.H) + q * t.H_b;
-    float* __restrict__ X = t.x[slot] + (int64_t)b * t.x_b[slot];
-    float bf[KH][16];
-#pragma unroll
-    for (int kh = 0; kh < KH; ++kh)
-#pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const int k = 32 * kh + 16 * h + s;
-            bf[kh][s] = (k < rank && col_ok) ? R[(int64_t)k * ldR + col] : 0.f;
-        }
-    const int rbeg = blockIdx.y * rows, rend = min(n, rbeg + rows);
-    for (int r0 = rbeg; r0 < rend; r0 += 32) {
-        const int row = r0 + lc;
-        float af[KH][16];
+    float ssq = 0.f;
+    if (c0 < dim) {                                     // the grid is as wide as the widest slot
+        const int col = c0 + lc;
+        const bool col_ok = col < dim;
+        const int64_t ldR = ((int64_t)dim + 3) / 4 * 4, ldx = t.ldx[slot], ldc = t.ldr;
+        const float* __restrict__ R = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b);
+        const float* __restrict__ C = (use_h2 ? t.H2 : t.H) + q * t.H_b;
+        float* __restrict__ X = t.x[slot] + (int64_t)b * t.x_b[slot];
+        float bf[KH][16];
 #pragma unroll
         for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int k4 = 32 * kh + 16 * h + 4 * j;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (row < rend && k4 < ldc) v = *reinterpret_cast<const float4*>(C + (int64_t)row * ldc + k4);   // ldc is a multiple of 4
-                af[kh][4 * j + 0] = (k4 + 0 < rank) ? v.x : 0.f;
-                af[kh][4 * j + 1] = (k4 + 1 < rank) ? v.y : 0.f;
-                af[kh][4 * j + 2] = (k4 + 2 < rank) ? v.z : 0.f;
-                af[kh][4 * j + 3] = (k4 + 3 < rank) ? v.w : 0.f;
+            for (int s = 0; s < 16; ++s) {
+                const int k = 32 * kh + 16 * h + s;
+                bf[kh][s] = (k < rank && col_ok) ? R[(int64_t)k * ldR + col] : 0.f;
             }
-        float old[16];
+        const int rbeg = blockIdx.y * rows, rend = min(n, rbeg + rows);
+        for (int r0 = rbeg; r0 < rend; r0 += 32) {
+            const int row = r0 + lc;
+            float af[KH][16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
-            old[v] = (rr < rend && col_ok) ? X[(int64_t)rr * ldx + col] : 0.f;
+            for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int k4 = 32 * kh + 16 * h + 4 * j;
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (row < rend && k4 < ldc) v = *reinterpret_cast<const float4*>(C + (int64_t)row * ldc + k4);   // ldc is a multiple of 4
+                    af[kh][4 * j + 0] = (k4 + 0 < rank) ? v.x : 0.f;
+                    af[kh][4 * j + 1] = (k4 + 1 < rank) ? v.y : 0.f;
+                    af[kh][4 * j + 2] = (k4 + 2 < rank) ? v.z : 0.f;
+                    af[kh][4 * j + 3] = (k4 + 3 < rank) ? v.w : 0.f;
+                }
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                old[v] = (rr < rend && col_ok) ? X[(int64_t)rr * ldx + col] : 0.f;
+                if (fuse == 1) ssq += old[v] * old[v];
+            }
+            ng_floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[kh][s], bf[kh][s], acc, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (rr < rend && col_ok) {
+                    const float xn = old[v] + sign * acc[v];
+                    X[(int64_t)rr * ldx + col] = xn;
+                    if (fuse == 2) {
+                        ssq += xn * xn;
+                        if (col == dim - 1) t.wcol[q * n + rr] = xn;
+                    }
+                }
+            }
         }
-        ng_floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kh = 0; kh < KH; ++kh)
-#pragma unroll
-            for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[kh][s], bf[kh][s], acc, 0, 0, 0);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (rr < rend && col_ok) X[(int64_t)rr * ldx + col] = old[v] + sign * acc[v];
-        }
+    }
+    if (fuse != 0) {      // (uniform over the workgroup: every wavefront reaches the barriers)
+        const double tot = block_sum_d((double)ssq, sh);
+        if (threadIdx.x == 0) t.part[q * kNgParts + blockIdx.y * gridDim.x + blockIdx.x] = tot;
     }
 }
 
@@ -735,7 +764,8 @@ int ng_slots_norms(const NgSlots& t, int which, float alpha, float eta, hipStrea
     hipLaunchKernelGGL(ng_sumsq_partial_slots_kernel, dim3(256, t.nslots, t.batch), dim3(256), 0, s, t,
                        (which == 1 && t.wcol != nullptr) ? 1 : 0);
     NG_LAUNCHED();
-    hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, which, alpha, eta);
+    hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, which, alpha, eta, 256,
+                       which == 0 ? 3 : 1);
     NG_LAUNCHED();
     return 0;
 }
@@ -744,7 +774,7 @@ int ng_slots_norms(const NgSlots& t, int which, float alpha, float eta, hipStrea
 // partial products), then their sums
 int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s) {
     GemmDesc g[kThinMaxProblems];
-    NgChunkTable ct;
+    NgChunkTable ct = {};
     int np = 0, pi = 0;                               // descriptors pending, problems so far
     for (int j = 0; j < t.nslots; ++j) {
         const int dim = t.dim[j], kc = ng_chunk_len(dim), nch = ng_chunk_count(dim);
@@ -772,15 +802,23 @@ int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s) {
 }
 
 // X <- X + sign * (H or H2) R for every slot
-int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s) {
+// fuse: see the kernel; *nparts (when asked for) receives the number of partial sums of squares per (slot, replica)
+// the launch leaves.
+int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s, int fuse = 0, int* nparts = nullptr) {
     constexpr int kRows = 64;                        // rows a wavefront walks with its block of R in registers
     int maxdim = 0;
     for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
     const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((t.n + kRows - 1) / kRows), (unsigned)(t.nslots * t.batch));
-    if (t.rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<1>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
-    else hipLaunchKernelGGL(ng_rank_update_slots_kernel<2>, grid, dim3(256), 0, s, t, use_h2, sign, kRows);
+    if (nparts) *nparts = (int)(grid.x * grid.y);
+    if (t.rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<1>, grid, dim3(256), 0, s, t, use_h2, sign, kRows, fuse);
+    else hipLaunchKernelGGL(ng_rank_update_slots_kernel<2>, grid, dim3(256), 0, s, t, use_h2, sign, kRows, fuse);
     NG_LAUNCHED();
     return 0;
+}
+inline bool ng_parts_fit(const NgSlots& t) {
+    int maxdim = 0;
+    for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
+    return (int64_t)((maxdim + 127) / 128) * ((t.n + 63) / 64) <= kNgParts;
 }
 
 int ng_slots_combine(const NgSlots& t, hipStream_t s) {
@@ -844,7 +882,7 @@ int ng_run(const NgCall& c, hipStream_t s) {
             NG_CHECK(finish_fold(0, true));
         }
         // the coefficients again, from the folded state (the partial sums of ||X||^2 are still in place)
-        hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(1, c.batch), dim3(256), 0, s, t, 0, c.alpha, c.eta);
+        hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(1, c.batch), dim3(256), 0, s, t, 0, c.alpha, c.eta, 256, 2);
         NG_LAUNCHED();
     }
     NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
@@ -919,7 +957,7 @@ NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     y.h_off = off;     off += q * y.H_b;
     y.h2_off = off;    off += q * y.H_b;
     y.coef_off = off;  off += q * 3 * kMaxRank;
-    y.part_off = off;  off += q * 2 * 256;
+    y.part_off = off;  off += q * 2 * kNgParts;
     y.gamma_off = off; off += round_up(q, 64);
     int64_t nprob = 0;
     for (int l = 1; l <= L; ++l) nprob += ng_chunk_count(d[l - 1] + 1) + ng_chunk_count(d[l]);
@@ -1065,7 +1103,7 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
         t.H = ws + lay.h_off + (int64_t)j0 * k * lay.H_b;
         t.H2 = ws + lay.h2_off + (int64_t)j0 * k * lay.H_b;
         t.coef = ws + lay.coef_off + (int64_t)j0 * k * 3 * kMaxRank;
-        t.part = reinterpret_cast<double*>(ws + lay.part_off) + (int64_t)j0 * k * 256;
+        t.part = reinterpret_cast<double*>(ws + lay.part_off) + (int64_t)j0 * k * kNgParts;
         t.scal = scal + (int64_t)j0 * k * 2;
         t.gamma = ws + lay.gamma_off + (int64_t)j0 * k;
         t.wcol = ws + lay.wcol_off + (int64_t)j0 * k * n;
@@ -1091,7 +1129,16 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
             NG_LAUNCHED();
         }
         float* P = ws + lay.hp_off;                      // partial products [problem][replica][n x ldr]
-        NG_CHECK(ng_slots_norms(t, 0, a0.alpha, a0.eta, s));
+        // The two rank updates take the norms with them (||X||^2 as the first one reads X, ||Xh||^2 as the second one
+        // writes it) whenever the per-workgroup partial sums fit their table: two passes over the matrices fewer.
+        const bool fused = ng_parts_fit(t);
+        int nparts = 0;
+        if (fused) {
+            hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, 0, a0.alpha, a0.eta, 0, 2);
+            NG_LAUNCHED();
+        } else {
+            NG_CHECK(ng_slots_norms(t, 0, a0.alpha, a0.eta, s));
+        }
         NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
         if (a0.mode >= 1) {   // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it
             GemmDesc g[kNgSlots];
@@ -1109,17 +1156,23 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
                 q.epi.aux = reinterpret_cast<const float*>(t.state[j]); q.epi.ldaux = ld; q.epi.aux_bstride = t.st_b / 4;
             }
             NG_CHECK(gemm_launch_grouped(g, t.nslots, s));
-            if (side) {
-                NG_CHECK(note_hip_error(hipEventRecord(side->ev[0], s)));
-                NG_CHECK(note_hip_error(hipStreamWaitEvent(side->stream, side->ev[0], 0)));
-                const NgFoldTable tb = ng_dnn_fold_table(lay, a0.dims, L, k, ng_state, state_stride, ws, 0);
-                NG_CHECK(ng_finish_zeig(tb, rank, n, a0.eta, false, Zf, Wtf, 1, side->stream));
-            }
         }
-        NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s));       // X1 = X - H R
+        if (fused) {                                         // X1 = X - H R, and ||X||^2
+            NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s, 1, &nparts));
+            hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, 0, a0.alpha, a0.eta, nparts, 1);
+            NG_LAUNCHED();
+        } else {
+            NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s));
+        }
+        if (a0.mode >= 1 && side) {      // Y and ||X||^2 are there: the fold may start
+            NG_CHECK(note_hip_error(hipEventRecord(side->ev[0], s)));
+            NG_CHECK(note_hip_error(hipStreamWaitEvent(side->stream, side->ev[0], 0)));
+            const NgFoldTable tb = ng_dnn_fold_table(lay, a0.dims, L, k, ng_state, state_stride, ws, 0);
+            NG_CHECK(ng_finish_zeig(tb, rank, n, a0.eta, false, Zf, Wtf, 1, side->stream));
+        }
         NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s));            // H2 = X1 R^T
         NG_CHECK(ng_slots_combine(t, s));
-        NG_CHECK(ng_slots_rank_update(t, 1, 1.f, s));        // Xh = X1 + (H (I - E) - H2) R
+        NG_CHECK(ng_slots_rank_update(t, 1, 1.f, s, fused ? 2 : 0, &nparts));     // Xh = X1 + (H (I - E) - H2) R (, ||Xh||^2, last column)
         if (side) {      // R has been read for the last time: the fold may write it
             NG_CHECK(note_hip_error(hipEventRecord(side->ev[1], s)));
             NG_CHECK(note_hip_error(hipStreamWaitEvent(side->stream, side->ev[1], 0)));
@@ -1127,7 +1180,12 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
             NG_CHECK(ng_finish_newr(tb, rank, false, Wtf, side->stream));
             NG_CHECK(note_hip_error(hipEventRecord(side->ev[2], side->stream)));
         }
-        NG_CHECK(ng_slots_norms(t, 1, a0.alpha, a0.eta, s));
+        if (fused) {
+            hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, 1, a0.alpha, a0.eta, nparts, 1);
+            NG_LAUNCHED();
+        } else {
+            NG_CHECK(ng_slots_norms(t, 1, a0.alpha, a0.eta, s));
+        }
         {   // W <- W - lr g_out g_in Xh_out^T Xh_in[:, :d_in] for the layers of this pass, and as the weighted row sums
             // of the same launch b <- b - lr g_out g_in Xh_out^T Xh_in[:, d_in] (the preconditioned "ones" column,
             // left contiguous by the pass that took the norms)
