@@ -14,6 +14,8 @@
  *     memory read during the call.  The library allocates nothing, frees nothing, keeps no pointer
  *     after the call returns and never synchronises: kernels are enqueued on `stream`
  *     (a hipStream_t passed as void*, NULL = the default stream) and the call returns.
+ *     Two documented exceptions: dnn_backward_update with MAVG_USE_NGSGD (an internal stream, see there) and
+ *     rbm_cd1_step_static (a static device array).
  *   - Matrices are dense row-major float32.  Every device pointer must be 16-byte aligned; replica
  *     strides are counted in elements.
  *   - Workspace: the caller passes a device scratch buffer of at least the size the matching
@@ -120,6 +122,13 @@ int32_t dnn_forward(const mavg_shape* shape, int32_t k,
  * downwards is not.  Every call folds its minibatch into the 2*L states (update mode MAVG_NG_UPDATE;
  * MAVG_NG_INIT_UPDATE with MAVG_NG_FIRST) unless MAVG_NG_APPLY_ONLY is set (mode MAVG_NG_APPLY: the
  * states are read and left as they are).
+ * With MAVG_USE_NGSGD (and neither MAVG_NG_FIRST nor MAVG_NG_APPLY_ONLY, at most 16 layers) the folds run on an
+ * internal stream beside the weight update: the first such call of a host thread on a device creates one stream
+ * (default priority, non-blocking) and three events that live until the process ends; the call forks that stream
+ * from `stream` and joins it back before it returns, so everything the call enqueues is complete before anything
+ * enqueued on `stream` afterwards starts, and results are bit-identical to the serial order.  Make that first call
+ * outside a stream capture.  MAVG_NG_SERIAL_FOLD=1 in the environment (read once per host thread and device) keeps
+ * every launch on `stream`.
  *   labels    device int32, n per replica, replica r at labels + r*label_stride (label_stride >= n, or 0 to share
  *             one label vector); each in [0, d_L)
  *             (an out-of-range label contributes no "-1" and no loss; it is not detected)

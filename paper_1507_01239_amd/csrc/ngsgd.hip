@@ -947,7 +947,7 @@ NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     }
     off += y.layer_floats;
     for (int l = 1; l <= L; ++l) {
-        y.ld_in[l] = round_up(d[l - 1] + 1, 4);
+        y.ld_in[l] = round_up(d[l - 1] + 1, 32);
         y.xaug_off[l] = off;
         off += round_up((int64_t)k * n * y.ld_in[l], 64);
     }
