@@ -614,9 +614,18 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         constexpr int t = decltype(tc)::value;
         acc[t / TN][t % TN] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     });
-    const bool do_rowsum = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0 && tid < BM;
+    // Fused (optionally weighted) row sums of A, by the workgroups of the first tile column: all wavefronts take
+    // part, wavefront group rs_grp summing its RS_KPG k-rows of every stage for row rs_row; the groups' partial
+    // sums meet in LDS after the loop.  The weights are workgroup-uniform and written by no launch that runs
+    // beside this one, so they are read through the constant address space: scalar loads, which cost no vector
+    // registers and stay out of the vmcnt bookkeeping of the direct loads.
+    constexpr int RS_G = 256 / BM, RS_KPG = BK / RS_G;
+    const bool rs_block = !AKC && p.epi.rowsum_dst != nullptr && tn_i == 0;
+    const int rs_grp = __builtin_amdgcn_readfirstlane(tid / BM), rs_row = tid % BM;
     float rowsum = 0.f;
-    const float* __restrict__ rw = p.epi.rowsum_w ? p.epi.rowsum_w + (int64_t)b * p.epi.rowsum_w_bstride + kbeg : nullptr;
+    typedef const __attribute__((address_space(4))) float* ConstF;
+    const ConstF rw = p.epi.rowsum_w
+        ? (ConstF)reinterpret_cast<uintptr_t>(p.epi.rowsum_w + (int64_t)b * p.epi.rowsum_w_bstride + kbeg) : (ConstF)0;
 
     if (nkt > 0) {
 #pragma unroll
@@ -638,13 +647,14 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
             constexpr int u = decltype(uc)::value % NST;    // stage of tile t
             constexpr int set = decltype(uc)::value & 1;    // register set of tile t
             multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{});
-            if (do_rowsum) {      // the stage is overwritten after the coming barrier: read it before
+            if (rs_block) {       // the stage is overwritten after the coming barrier: read it before
+                const float* a = &As[u][rs_grp * RS_KPG * BM + rs_row];
                 if (rw) {
 #pragma unroll
-                    for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * BM + tid] * rw[t * BK + kk];
+                    for (int kk = 0; kk < RS_KPG; ++kk) rowsum += a[kk * BM] * rw[t * BK + rs_grp * RS_KPG + kk];
                 } else {
 #pragma unroll
-                    for (int kk = 0; kk < BK; ++kk) rowsum += As[u][kk * BM + tid];
+                    for (int kk = 0; kk < RS_KPG; ++kk) rowsum += a[kk * BM];
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -692,11 +702,12 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
                     tb[j][c] = ok ? (BKC ? Bb[(int64_t)n * p.ldb + k] : Bb[(int64_t)k * p.ldb + n]) : 0.f;
                 }
             }
-            if (do_rowsum) {      // (rows of A summed over k: this thread's row is tid, not its MFMA lane's)
+            if (rs_block && rs_grp == 0) {      // (this thread's row is rs_row, not its MFMA lane's)
 #pragma unroll
                 for (int c = 0; c < 8; ++c) {
                     const int k = ktail + 8 * pr + c;
-                    if (k < kend && m0 + tid < p.M) rowsum += Ab[(int64_t)k * p.lda + m0 + tid] * (rw ? rw[k - kbeg] : 1.f);
+                    if (k < kend && m0 + rs_row < p.M)
+                        rowsum += Ab[(int64_t)k * p.lda + m0 + rs_row] * (rw ? rw[k - kbeg] : 1.f);
                 }
             }
             static_for<4 * TM * TN>([&](auto qc) {
@@ -707,14 +718,24 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         });
     }
 
-    if (do_rowsum && m0 + tid < p.M) {
-        float* d = p.epi.rowsum_dst + (int64_t)b * p.epi.rowsum_bstride + m0 + tid;
+    if (rs_block) {       // (workgroup-uniform) the groups' partial sums, added in the order of the groups
+        float* red = &As[0][0];
+        __syncthreads();
+        if (rs_grp > 0) red[(rs_grp - 1) * BM + rs_row] = rowsum;
+        __syncthreads();
+        if (rs_grp == 0) {
+#pragma unroll
+            for (int g = 1; g < RS_G; ++g) rowsum += red[(g - 1) * BM + rs_row];
+        }
+    }
+    if (rs_block && rs_grp == 0 && m0 + rs_row < p.M) {
+        float* d = p.epi.rowsum_dst + (int64_t)b * p.epi.rowsum_bstride + m0 + rs_row;
         float r = p.epi.rowsum_alpha * rowsum;
         if (p.epi.alpha_dev0) r *= p.epi.alpha_dev0[b];
         if (p.epi.alpha_dev1) r *= p.epi.alpha_dev1[b];
         if (p.epi.rowsum_beta != 0.f) r += p.epi.rowsum_beta * *d;
         *d = r;
-        if (p.epi.rowsum_dst2) p.epi.rowsum_dst2[(int64_t)b * p.epi.rowsum2_bstride + m0 + tid] += r;
+        if (p.epi.rowsum_dst2) p.epi.rowsum_dst2[(int64_t)b * p.epi.rowsum2_bstride + m0 + rs_row] += r;
     }
     if (p.splits > 1) {
         Epilogue raw;
