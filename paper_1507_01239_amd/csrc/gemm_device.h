@@ -635,18 +635,28 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-        auto multiply = [&](auto setc, auto prc) {
+        // MFMAs first .. last - 1 of one half of the k-tile (a half has 4 TM TN of them)
+        auto multiply = [&](auto setc, auto prc, const int first, const int last) {
             constexpr int set = decltype(setc)::value, pr = decltype(prc)::value;
             static_for<4 * TM * TN>([&](auto qc) {
                 constexpr int q = decltype(qc)::value;
                 constexpr int c = q / (TM * TN), i = (q / TN) % TM, j = q % TN;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][i][pr][c], fb[set][j][pr][c], acc[i][j], 0, 0, 0);
+                if (q >= first && q < last)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][i][pr][c], fb[set][j][pr][c], acc[i][j], 0, 0, 0);
             });
         };
+        constexpr int NMF = 4 * TM * TN;
         auto step = [&](auto uc, const int t) {
             constexpr int u = decltype(uc)::value % NST;    // stage of tile t
             constexpr int set = decltype(uc)::value & 1;    // register set of tile t
-            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{});
+            // The loads of tile t + NST - 1 go out behind the first MFMA of the step and the operand reads for tile
+            // t + 1 behind the first MFMA after the barrier, under cover of the matrix pipe: between the halves only
+            // the wait and the barrier remain.  (The loads' stage held tile t - 1, which every wavefront has multiplied.)
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{}, 0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + NST - 1 < nkt) issue(t + NST - 1, (u + NST - 1) % NST);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{}, 1, NMF);
             if (rs_block) {       // the stage is overwritten after the coming barrier: read it before
                 const float* a = &As[u][rs_grp * RS_KPG * BM + rs_row];
                 if (rw) {
@@ -658,16 +668,14 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            if (t + NST - 1 < nkt) {
-                issue(t + NST - 1, (u + NST - 1) % NST);
-                wait_next();                                  // tiles t+2, t+3 may stay in flight
-            } else {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            }
+            if (t + NST - 1 < nkt) wait_next();               // tiles t+2, t+3 may stay in flight
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 0, 1);
+            __builtin_amdgcn_sched_barrier(0);
             if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
             __builtin_amdgcn_sched_barrier(0);
-            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{});
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 1, NMF);
             __builtin_amdgcn_sched_barrier(0);
         };
         constexpr int PERIOD = (NST % 2 == 0) ? NST : 2 * NST;      // stages and register sets repeat together
@@ -901,28 +909,37 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     group_barrier();
     if (nkt > 0) read_frags(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-    auto multiply = [&](auto setc, auto halfc) {       // one half of the k-tile's MFMAs
+    // MFMAs first .. last - 1 of one half of the k-tile (a half has 4 NPR / 2 of them)
+    auto multiply = [&](auto setc, auto halfc, const int first, const int last) {
         constexpr int set = decltype(setc)::value, half = decltype(halfc)::value;
 #pragma unroll
-        for (int pr = half * (NPR / 2); pr < (half + 1) * (NPR / 2); ++pr)
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][pr][c], fb[set][pr][c], acc[0][0], 0, 0, 0);
+        for (int q = 0; q < 2 * NPR; ++q) {
+            const int pr = half * (NPR / 2) + q / 4, c = q % 4;
+            if (q >= first && q < last)
+                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][pr][c], fb[set][pr][c], acc[0][0], 0, 0, 0);
+        }
     };
     auto step = [&](auto uc, const int t) {
         constexpr int u = decltype(uc)::value % NST;      // stage of tile t
         constexpr int set = decltype(uc)::value & 1;      // register set of tile t
-        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{});
+        // The loads of tile t + NST - 1 are issued behind the first MFMA of the step, under cover of the matrix pipe:
+        // between the two halves only the wait, the barrier and the operand reads remain, during which both wavefronts
+        // of the SIMD stand still.  (Their stage held tile t - 1, which every wavefront has multiplied.)
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{}, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
-        if (t + NST - 1 < nkt) {
-            issue(t + NST - 1, (u + NST - 1) % NST);
-            wait_next();
-        } else {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        }
+        if (t + NST - 1 < nkt) issue(t + NST - 1, (u + NST - 1) % NST);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{}, 1, 2 * NPR);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + NST - 1 < nkt) wait_next();
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         group_barrier();
+        // the second half's operands are in registers already: its first MFMA goes ahead of the reads for tile t + 1
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 0, 1);
+        __builtin_amdgcn_sched_barrier(0);
         if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
         __builtin_amdgcn_sched_barrier(0);
-        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{});
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 1, 2 * NPR);
         __builtin_amdgcn_sched_barrier(0);
     };
     constexpr int PERIOD = (NST % 2 == 0) ? NST : 2 * NST;      // stages and register sets repeat together
