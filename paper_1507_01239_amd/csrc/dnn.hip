@@ -194,14 +194,12 @@ extern "C" int32_t dnn_backward_update(const mavg_shape* shape, int32_t k, float
     float* ws = ws_base(workspace);
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* gws = ws + w.off_gemm;
-    float* rowloss = ws + w.off_rowloss;
     const float scale = (flags & MAVG_MEAN_GRAD) ? 1.0f / (float)n : 1.0f;
     auto delta_of = [&](int l) { return ws + w.off_delta[l]; };
     auto dstride_of = [&](int l) { return (int64_t)n * w.ld_delta[l]; };
 
     if (ce_delta_launch(acts + y.a_off[y.L], y.d[y.L], act_stride, labels, label_stride, delta_of(y.L), w.ld_delta[y.L],
-                        dstride_of(y.L), rowloss, n, y.d[y.L], k, scale, s) != 0) return MAVG_E_LAUNCH;
-    if (loss_sum && sum_segments_launch(rowloss, n, k, loss_sum, s) != 0) return MAVG_E_LAUNCH;
+                        dstride_of(y.L), loss_sum, n, y.d[y.L], k, scale, s) != 0) return MAVG_E_LAUNCH;
 
     // 1. the chain: delta_{l-1} = (delta_l W_l) * A_{l-1} (1 - A_{l-1}), l = L..2, with every W_l as it was in the
     //    forward pass (no weight is touched before the chain is complete)

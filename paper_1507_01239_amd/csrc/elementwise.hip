@@ -82,35 +82,44 @@ int softmax_rows_launch(float* z, int64_t ld, int64_t bstride, int rows, int col
 }
 
 // ---- cross-entropy output error ------------------------------------------------------------------
+// One more row of workgroups than the matrix has rows: workgroup (0, rows, b) gathers p(n, labels[n]) of all rows of
+// replica b by itself and sums -log of them in a fixed order (thread-strided partial sums, then the workgroup's tree),
+// so the loss needs neither a per-row buffer nor a launch of its own.  p is only read by this launch.
 __global__ __launch_bounds__(kThreads) void ce_delta_kernel(const float* __restrict__ p, int64_t ldp, int64_t p_bstride,
                                                             const int32_t* __restrict__ labels, int64_t label_bstride,
                                                             float* __restrict__ delta, int64_t ldd, int64_t d_bstride,
-                                                            float* __restrict__ rowloss, int rows, int cols, float scale) {
+                                                            float* __restrict__ loss_sum, int rows, int cols, float scale) {
+    __shared__ float sh[4];
     const int b = blockIdx.z, n = blockIdx.y;
+    if (n == rows) {      // (uniform over the workgroup)
+        if (blockIdx.x != 0 || loss_sum == nullptr) return;
+        float s = 0.f;
+        for (int i = threadIdx.x; i < rows; i += kThreads) {
+            const int y = labels[(int64_t)b * label_bstride + i];
+            if (y >= 0 && y < cols) s += -logf(p[(int64_t)b * p_bstride + (int64_t)i * ldp + y]);
+        }
+        s = block_sum(s, sh);
+        if (threadIdx.x == 0) loss_sum[b] = s;
+        return;
+    }
     const int y = labels[(int64_t)b * label_bstride + n];
     const float* __restrict__ pr = p + (int64_t)b * p_bstride + (int64_t)n * ldp;
     float* __restrict__ dr = delta + (int64_t)b * d_bstride + (int64_t)n * ldd;
     for (int j = blockIdx.x * kThreads + threadIdx.x; j < cols; j += gridDim.x * kThreads) {
         const float q = pr[j];
-        float d = q;
-        if (j == y) {
-            d = q - 1.f;
-            rowloss[(int64_t)b * rows + n] = -logf(q);
-        }
-        dr[j] = d * scale;
+        dr[j] = (j == y ? q - 1.f : q) * scale;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0 && (y < 0 || y >= cols)) rowloss[(int64_t)b * rows + n] = 0.f;
 }
 
 int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride, const int32_t* labels, int64_t label_bstride,
-                    float* delta, int64_t ldd, int64_t d_bstride, float* rowloss, int rows, int cols, int batch,
+                    float* delta, int64_t ldd, int64_t d_bstride, float* loss_sum, int rows, int cols, int batch,
                     float scale, hipStream_t s) {
     if (rows <= 0 || cols <= 0 || batch <= 0) return 0;
     int gx = (cols + kThreads * 4 - 1) / (kThreads * 4);
     if (gx < 1) gx = 1;
-    dim3 grid((unsigned)gx, (unsigned)rows, (unsigned)batch);
+    dim3 grid((unsigned)gx, (unsigned)rows + 1u, (unsigned)batch);
     hipLaunchKernelGGL(ce_delta_kernel, grid, dim3(kThreads), 0, s, p, ldp, p_bstride, labels, label_bstride, delta, ldd,
-                       d_bstride, rowloss, rows, cols, scale);
+                       d_bstride, loss_sum, rows, cols, scale);
     return note_hip_error(hipGetLastError());
 }
 

@@ -8,11 +8,12 @@ namespace mavg {
 // rows x cols matrix z (row stride ld), batch b at z + b*bstride: z <- softmax of each row (max-subtracted).
 int softmax_rows_launch(float* z, int64_t ld, int64_t bstride, int rows, int cols, int batch, hipStream_t s);
 
-// delta[b](n,j) = scale * (p[b](n,j) - [j == labels[b][n]]);  rowloss[b][n] = -log p[b](n, labels[b][n]).
+// delta[b](n,j) = scale * (p[b](n,j) - [j == labels[b][n]]);  loss_sum[b] (nullable) = sum_n -log p[b](n, labels[b][n]),
+// summed in a fixed order; labels outside [0, cols) contribute neither a "-1" nor a loss.  rows <= 65534.
 int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride,
                     const int32_t* labels, int64_t label_bstride,
                     float* delta, int64_t ldd, int64_t d_bstride,
-                    float* rowloss, int rows, int cols, int batch, float scale, hipStream_t s);
+                    float* loss_sum, int rows, int cols, int batch, float scale, hipStream_t s);
 
 // out[b] = sum_{i<n} v[b*n + i], summed in a fixed order (one workgroup per b).
 int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s);
