@@ -892,6 +892,26 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
 
     floatx16 acc[1][1];
     acc[0][0] = floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // Contraction steps past the last whole k-tile (fewer than BK) are the last k-group's, straight from global memory,
+    // element by element.  Their operands are requested here, ahead of every direct load (so they are the oldest
+    // loads in flight and the vmcnt waits of the ring cover them), and multiplied after the loop: the latency of these
+    // scattered loads runs beside the loop instead of behind it.
+    const bool has_tail = kg == KG - 1 && nkt_all * BK < p.K;      // (uniform over the wavefront)
+    float ta[NPR][4], tb[NPR][4];
+    if (has_tail) {
+        const float* __restrict__ Ab = p.A + (int64_t)b * p.a_bstride;
+        const float* __restrict__ Bb = p.B + (int64_t)b * p.b_bstride;
+        const int m = min(m0 + lcol, p.M - 1), n = min(n0 + wn + lcol, p.N - 1);
+#pragma unroll
+        for (int pr = 0; pr < NPR; ++pr)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int k = nkt_all * BK + 8 * pr + 4 * lrow + c;
+                const bool ok = k < p.K;
+                ta[pr][c] = ok ? (AKC ? Ab[(int64_t)m * p.lda + k] : Ab[(int64_t)k * p.lda + m]) : 0.f;
+                tb[pr][c] = ok ? (BKC ? Bb[(int64_t)n * p.ldb + k] : Bb[(int64_t)k * p.ldb + n]) : 0.f;
+            }
+    }
 #pragma unroll
     for (int t = 0; t < NST - 1; ++t)
         if (t < nkt) issue(t, t);
@@ -949,24 +969,12 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         });
     }
 
-    // contraction steps past the last whole k-tile (fewer than BK): the last k-group, straight from global memory
-    if (kg == KG - 1 && nkt_all * BK < p.K) {
-        const float* __restrict__ Ab = p.A + (int64_t)b * p.a_bstride;
-        const float* __restrict__ Bb = p.B + (int64_t)b * p.b_bstride;
-        const int m = min(m0 + lcol, p.M - 1), n = min(n0 + wn + lcol, p.N - 1);
+    if (has_tail) {      // the contraction steps past the last whole k-tile, operands requested before the loop
         static_for<NPR>([&](auto prc) {
             constexpr int pr = decltype(prc)::value;
             if (nkt_all * BK + 8 * pr < p.K) {        // (uniform) pairs wholly past the end are skipped
-                float ta[4], tb[4];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const int k = nkt_all * BK + 8 * pr + 4 * lrow + c;
-                    const bool ok = k < p.K;
-                    ta[c] = ok ? (AKC ? Ab[(int64_t)m * p.lda + k] : Ab[(int64_t)k * p.lda + m]) : 0.f;
-                    tb[c] = ok ? (BKC ? Bb[(int64_t)n * p.ldb + k] : Bb[(int64_t)k * p.ldb + n]) : 0.f;
-                }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ta[c], tb[c], acc[0][0], 0, 0, 0);
+                for (int c = 0; c < 4; ++c) acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ta[pr][c], tb[pr][c], acc[0][0], 0, 0, 0);
             }
         });
     }
