@@ -650,8 +650,8 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
             constexpr int u = decltype(uc)::value % NST;    // stage of tile t
             constexpr int set = decltype(uc)::value & 1;    // register set of tile t
             // The loads of tile t + NST - 1 go out behind the first MFMA of the step and the operand reads for tile
-            // t + 1 behind the first MFMA after the barrier, under cover of the matrix pipe: between the halves only
-            // the wait and the barrier remain.  (The loads' stage held tile t - 1, which every wavefront has multiplied.)
+            // t + 1 behind the first half of the MFMAs after the barrier, under cover of the matrix pipe: between the
+            // halves only the wait and the barrier remain.  (The loads' stage held tile t - 1, which every wavefront has multiplied.)
             multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{}, 0, 1);
             __builtin_amdgcn_sched_barrier(0);
             if (t + NST - 1 < nkt) issue(t + NST - 1, (u + NST - 1) % NST);
@@ -671,11 +671,11 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
             if (t + NST - 1 < nkt) wait_next();               // tiles t+2, t+3 may stay in flight
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 0, 1);
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 0, NMF / 2);
             __builtin_amdgcn_sched_barrier(0);
             if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
             __builtin_amdgcn_sched_barrier(0);
-            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 1, NMF);
+            multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, NMF / 2, NMF);
             __builtin_amdgcn_sched_barrier(0);
         };
         constexpr int PERIOD = (NST % 2 == 0) ? NST : 2 * NST;      // stages and register sets repeat together
