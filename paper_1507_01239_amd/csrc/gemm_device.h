@@ -955,11 +955,11 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         group_barrier();
         // the second half's operands are in registers already: its first MFMA goes ahead of the reads for tile t + 1
-        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 0, 1);
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 0, 2);
         __builtin_amdgcn_sched_barrier(0);
         if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
         __builtin_amdgcn_sched_barrier(0);
-        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 1, 2 * NPR);
+        if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 2, 2 * NPR);
         __builtin_amdgcn_sched_barrier(0);
     };
     constexpr int PERIOD = (NST % 2 == 0) ? NST : 2 * NST;      // stages and register sets repeat together
