@@ -943,8 +943,8 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         constexpr int u = decltype(uc)::value % NST;      // stage of tile t
         constexpr int set = decltype(uc)::value & 1;      // register set of tile t
         // The loads of tile t + NST - 1 are issued behind the first MFMA of the step, under cover of the matrix pipe:
-        // between the two halves only the wait, the barrier and the operand reads remain, during which both wavefronts
-        // of the SIMD stand still.  (Their stage held tile t - 1, which every wavefront has multiplied.)
+        // between the two halves only the wait and the barrier remain, during which both wavefronts of the SIMD stand
+        // still.  (The loads' stage held tile t - 1, which every wavefront has multiplied.)
         if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 0>{}, 0, 1);
         __builtin_amdgcn_sched_barrier(0);
         if (t + NST - 1 < nkt) issue(t + NST - 1, (u + NST - 1) % NST);
@@ -954,7 +954,7 @@ __device__ __forceinline__ void gemm_dma_kg_body(const GemmKParams& p, const int
         if (t + NST - 1 < nkt) wait_next();
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         group_barrier();
-        // the second half's operands are in registers already: its first MFMA goes ahead of the reads for tile t + 1
+        // the second half's operands are in registers already: its first two MFMAs go ahead of the reads for tile t + 1
         if (t < nkt) multiply(std::integral_constant<int, set>{}, std::integral_constant<int, 1>{}, 0, 2);
         __builtin_amdgcn_sched_barrier(0);
         if (t + 1 < nkt) read_frags(std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, (u + 1) % NST>{});
