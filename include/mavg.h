@@ -102,7 +102,7 @@ int64_t mavg_workspace_bytes(const mavg_shape* shape, int32_t n, int32_t k, uint
  *   theta  device, replica r at theta + r*theta_stride  (theta_stride >= P, multiple of 4)
  *   x      device, n x d_0, replica r at x + r*x_stride  (x_stride >= n*d_0 or 0 to share one batch)
  *   acts   device, written; replica r at acts + r*act_stride (act_stride >= mavg_act_count, multiple of 4)
- *   n      rows per replica, >= 1;  k >= 1
+ *   n      rows per replica, 1 <= n <= 65534;  1 <= k <= 65535 (MAVG_E_DIM otherwise, here and in dnn_backward_update)
  */
 int32_t dnn_forward(const mavg_shape* shape, int32_t k,
                     const float* theta, int64_t theta_stride,

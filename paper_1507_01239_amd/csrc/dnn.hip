@@ -123,6 +123,7 @@ static int check_common(const mavg_shape* shape, int32_t k, const void* theta, i
     if (rc) return rc;
     if (!theta || !x || !acts) return MAVG_E_NULL;
     if (k < 1 || n < 1) return MAVG_E_DIM;
+    if (k > 65535 || n > 65534) return MAVG_E_DIM;      // replicas and rows (+ 1 for the loss) are grid dimensions of some launches
     *out = make_layout(shape, n);
     if (!aligned16(theta) || !aligned16(x) || !aligned16(acts)) return MAVG_E_ALIGN;
     if (k > 1) {

@@ -87,6 +87,8 @@ def test_dnn_calls_validate_before_touching_the_device():
     assert bw(flags=3, ng=A, rank=0) == B.E_DIM
     assert bw(flags=3, ng=A, rank=4) == B.E_DIM         # rank must be < every factor dimension
     assert bw(n=-1) == B.E_DIM
+    assert bw(n=65535) == B.E_DIM                       # rows (+ 1 for the loss) are a grid dimension
+    assert _rc(B.dnn_forward, s, 1, A, 0, A, 0, 65535, A, 0, **ok) == B.E_DIM
 
 
 def test_replicas_average_validation():
