@@ -46,6 +46,11 @@ struct Epilogue {
     //   matrix-matrix one: the bias gradient when the "ones" column has been preconditioned); the factors
     //   alpha_dev0[b] * alpha_dev1[b] of alpha apply to rowsum_alpha as well
     const float* rowsum_w = nullptr; int64_t rowsum_w_bstride = 0;
+    // optional, a short vector summed on the side of the launch (forces an unsplit contraction, not taken by the
+    // in-workgroup-split kernels): side_sum_dst[0] = sum_{i < side_sum_n} side_sum_src[i], by workgroup 0 of batch
+    // element 0 behind its own tile, in the order of a 256-thread fixed-order segment sum (thread-strided partial
+    // sums, then the four wavefronts' sums pairwise) - e.g. the per-block squared errors a preceding launch left
+    const float* side_sum_src = nullptr; float* side_sum_dst = nullptr; int side_sum_n = 0;
     uint32_t key0 = 0, key1 = 0, step = 0, layer = 0, phase = 0;   // Philox stream of the sampling epilogue
 };
 

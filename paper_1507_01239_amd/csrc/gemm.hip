@@ -182,8 +182,9 @@ static GemmKParams fill_params(const GemmDesc& d, const GemmPlan& pl, float* ws)
 
 int gemm_launch(const GemmDesc& d, float* ws, int64_t ws_floats, hipStream_t stream) {
     if (d.M <= 0 || d.N <= 0 || d.batch <= 0) return 0;
-    const bool rowsum = d.epi.rowsum_dst != nullptr;
-    if (rowsum && d.a_kc) return note_hip_error(hipErrorInvalidValue);
+    if (d.epi.rowsum_dst != nullptr && d.a_kc) return note_hip_error(hipErrorInvalidValue);
+    // fused row sums and the side sum are the work of the kernel that owns a whole tile: unsplit, not the in-workgroup split
+    const bool rowsum = d.epi.rowsum_dst != nullptr || d.epi.side_sum_src != nullptr;
     GemmPlan pl = gemm_plan(d.M, d.N, d.K, d.batch, d.force_cfg, rowsum ? 1 : d.force_splits);
     GemmKParams p = fill_params(d, pl, ws);
     const bool kg_cfg = cfg_kg(pl.cfg);

@@ -84,6 +84,20 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
     }
 }
 
+// The side sum of an epilogue (see gemm.h), by a whole workgroup of at least 256 threads; `sh`: 4 floats of LDS
+// that nothing else uses any more.  Bit for bit what sum_segments_kernel leaves for the same vector.
+__device__ __forceinline__ void side_sum(const Epilogue& e, float* sh) {
+    __syncthreads();
+    const int tid = threadIdx.x;
+    float s = 0.f;
+    if (tid < 256)
+        for (int i = tid; i < e.side_sum_n; i += 256) s += e.side_sum_src[i];
+    s = wave_sum(s);
+    if (tid < 256 && (tid & 63) == 0) sh[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) *e.side_sum_dst = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+}
+
 // Element at byte offset `off` from a pointer that is uniform over the wavefront: the form the hardware addresses
 // as scalar base + 32-bit per-lane offset, which costs one vector register per access pattern instead of a
 // 64-bit address per access.
@@ -426,6 +440,7 @@ __device__ __forceinline__ void gemm_body(const GemmKParams& p, const int tile, 
         const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
         MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, TM, TN>(acc, p.epi, c, p.ldc, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol)))
     }
+    if (p.epi.side_sum_src != nullptr && tile == 0 && bz == 0) side_sum(p.epi, &As[0][0][0]);      // (uniform over the workgroup)
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int PF, bool AKC, bool BKC>
@@ -755,6 +770,7 @@ __device__ __forceinline__ void gemm_dma_body(const GemmKParams& p, const int ti
         const EpiCtx c = epi_ctx(p.epi, p.C, p.c_bstride, b);
         MAVG_EPI_DISPATCH(p.epi.kind, (write_tile<KIND, TM, TN>(acc, p.epi, c, p.ldc, p.M, p.N, m0 + wm, n0 + wn, lrow, lcol)))
     }
+    if (p.epi.side_sum_src != nullptr && tile == 0 && bz == 0) side_sum(p.epi, &As[0][0]);      // (uniform over the workgroup)
 }
 
 template <int TM, int TN, int NST, bool AKC, bool BKC>

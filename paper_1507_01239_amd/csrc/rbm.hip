@@ -153,10 +153,9 @@ int32_t cd1_run(int32_t V, int32_t H, int32_t vis_type, float* w, float* a, floa
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
     // Ma <- momentum Ma + (lr/n) colsum(V0 - V1); a <- a + Ma;  the same pass copies V0 under V1's rows' stride
-    // and leaves the squared reconstruction error of each block of 32 columns, summed afterwards in block order
+    // and leaves the squared reconstruction error of each block of 32 columns (summed in block order by the launch below)
     if (colsum_axpby_launch(v0, V, v1, lay.ldv, ma, a, vv, lay.ldv, recon_err ? ws + lay.off_part : nullptr, n, V, lr * invn,
                             momentum, s) != 0) return MAVG_E_LAUNCH;
-    if (recon_err && sum_segments_launch(ws + lay.off_part, colsum_blocks(V), 1, recon_err, s) != 0) return MAVG_E_LAUNCH;
     {   // MW <- momentum MW + (lr/n) (P_h0^T V0 - P_h1^T V1) = momentum MW + (lr/n) [P_h0; -P_h1]^T [V0; V1];  W <- W + MW
         GemmDesc g;
         g.M = H; g.N = V; g.K = 2 * n;
@@ -170,6 +169,9 @@ int32_t cd1_run(int32_t V, int32_t H, int32_t vis_type, float* w, float* a, floa
         // Mc <- momentum Mc + (lr/n) colsum(P_h0 - P_h1), the row sums of this product's first operand;  c <- c + Mc
         g.epi.rowsum_dst = mc; g.epi.rowsum_alpha = lr * invn; g.epi.rowsum_beta = momentum;
         g.epi.rowsum_dst2 = c;
+        if (recon_err) {      // the reconstruction error: the blocks' squared errors, summed in block order on the side of this launch
+            g.epi.side_sum_src = ws + lay.off_part; g.epi.side_sum_dst = recon_err; g.epi.side_sum_n = colsum_blocks(V);
+        }
         if (gemm_launch(g, gws, lay.gemm_floats, s) != 0) return MAVG_E_LAUNCH;
     }
     return MAVG_OK;
