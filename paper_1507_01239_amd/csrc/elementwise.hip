@@ -123,22 +123,6 @@ int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride, const int32_
     return note_hip_error(hipGetLastError());
 }
 
-// ---- fixed-order segment sums --------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void sum_segments_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
-    __shared__ float sh[4];
-    const float* __restrict__ seg = v + (int64_t)blockIdx.x * n;
-    float s = 0.f;
-    for (int i = threadIdx.x; i < n; i += kThreads) s += seg[i];
-    s = block_sum(s, sh);
-    if (threadIdx.x == 0) out[blockIdx.x] = s;
-}
-
-int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s) {
-    if (batch <= 0) return 0;
-    hipLaunchKernelGGL(sum_segments_kernel, dim3((unsigned)batch), dim3(kThreads), 0, s, v, n, out);
-    return note_hip_error(hipGetLastError());
-}
-
 // ---- column sums with fused update ---------------------------------------------------------------
 // dst[j] = beta dst[j] + alpha sum_r (X(r, j) - Y(r, j));  dst2[j] += dst[j];  optionally Xcopy(r, j) = X(r, j) and
 // sq_partial[workgroup] = sum over the workgroup's 32 columns of (X - Y)^2 (fixed order; the caller adds them up).

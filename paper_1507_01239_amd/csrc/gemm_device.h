@@ -85,7 +85,8 @@ __device__ __forceinline__ void epi_apply(const Epilogue& e, const EpiCtx& c, in
 }
 
 // The side sum of an epilogue (see gemm.h), by a whole workgroup of at least 256 threads; `sh`: 4 floats of LDS
-// that nothing else uses any more.  Bit for bit what sum_segments_kernel leaves for the same vector.
+// that nothing else uses any more.  Fixed order: thread t of the first 256 adds elements t, t + 256, ..., a wavefront
+// adds its lanes by butterfly, the four wavefronts' sums are added pairwise.
 __device__ __forceinline__ void side_sum(const Epilogue& e, float* sh) {
     __syncthreads();
     const int tid = threadIdx.x;

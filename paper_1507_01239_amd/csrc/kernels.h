@@ -15,9 +15,6 @@ int ce_delta_launch(const float* p, int64_t ldp, int64_t p_bstride,
                     float* delta, int64_t ldd, int64_t d_bstride,
                     float* loss_sum, int rows, int cols, int batch, float scale, hipStream_t s);
 
-// out[b] = sum_{i<n} v[b*n + i], summed in a fixed order (one workgroup per b).
-int sum_segments_launch(const float* v, int n, int batch, float* out, hipStream_t s);
-
 // dst[j] = beta dst[j] + alpha colsum_j(X - Y) over `rows` rows (Y may be null);  dst2[j] += dst[j] (dst2 may be null);
 // xcopy (may be null): receives a copy of X with row stride ldc;  sq_partial (may be null): colsum_blocks(cols)
 // floats, entry w = sum of (X - Y)^2 over the 32 columns of workgroup w (their sum is the squared distance).
