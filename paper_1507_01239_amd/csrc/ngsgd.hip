@@ -685,13 +685,38 @@ __global__ __launch_bounds__(256) void ng_augment_slots_kernel(NgAugTable t) {
     const int d = t.d[l];
     const float* __restrict__ A = t.A[l] + (int64_t)b * t.a_b[l];
     float* __restrict__ X = t.X[l] + (int64_t)b * t.x_b[l];
-    const int64_t total = (int64_t)t.n * ldx;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int64_t r = e / ldx, c = e - r * ldx;
-        float v = 0.f;
-        if (c < d) v = A[r * lda + c];
-        else if (c == d) v = 1.f;
-        X[e] = v;
+    // a wavefront per row at a time (rows strided over the launch's wavefronts), four columns per lane and trip when
+    // both rows are 16-byte aligned: no division per element
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool vec = (lda & 3) == 0 && (ldx & 3) == 0 && (t.a_b[l] & 3) == 0 && (t.x_b[l] & 3) == 0 &&
+                     ((reinterpret_cast<uintptr_t>(t.A[l]) | reinterpret_cast<uintptr_t>(t.X[l])) & 15u) == 0;
+    for (int r = blockIdx.x * 4 + wave; r < t.n; r += gridDim.x * 4) {
+        const float* __restrict__ a = A + (int64_t)r * lda;
+        float* __restrict__ x = X + (int64_t)r * ldx;
+        if (vec) {
+            for (int c0 = 4 * lane; c0 < ldx; c0 += 4 * 256) {       // four trips' loads in flight before their stores
+                float4 v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + 256 * u;
+                    if (c + 3 < d) {
+                        v[u] = *reinterpret_cast<const float4*>(a + c);
+                    } else if (c < ldx) {
+                        v[u].x = c + 0 < d ? a[c + 0] : (c + 0 == d ? 1.f : 0.f);
+                        v[u].y = c + 1 < d ? a[c + 1] : (c + 1 == d ? 1.f : 0.f);
+                        v[u].z = c + 2 < d ? a[c + 2] : (c + 2 == d ? 1.f : 0.f);
+                        v[u].w = c + 3 < d ? a[c + 3] : (c + 3 == d ? 1.f : 0.f);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + 256 * u;
+                    if (c < ldx) *reinterpret_cast<float4*>(x + c) = v[u];
+                }
+            }
+        } else {
+            for (int c = lane; c < ldx; c += 64) x[c] = c < d ? a[c] : (c == d ? 1.f : 0.f);
+        }
     }
 }
 
@@ -1040,7 +1065,7 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
     float* gamma_out = gamma_in + round_up(a.k, 64);
     float* ngws = gamma_out + round_up(a.k, 64);
     {
-        int64_t gx = (aug_b + 255) / 256;
+        int64_t gx = (a.n + 3) / 4;       // a wavefront per row
         if (gx > 2048) gx = 2048;
         NgAugTable au;
         au.A[0] = a.A_in; au.lda[0] = a.a_ld; au.a_b[0] = a.a_bstride; au.d[0] = a.d_in;
@@ -1108,7 +1133,6 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
         t.gamma = ws + lay.gamma_off + (int64_t)j0 * k;
         t.wcol = ws + lay.wcol_off + (int64_t)j0 * k * n;
         au.n = n;
-        int64_t max_aug = 0;
         for (int i = 0; i < nl; ++i) {
             const NgLayerArgs& a = layers[l0 + i];
             const int l = a.l;
@@ -1116,14 +1140,13 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
             float* Xaug = ws + lay.xaug_off[l];
             au.A[i] = a.A_in; au.lda[i] = a.a_ld; au.a_b[i] = a.a_bstride; au.d[i] = a.d_in;
             au.X[i] = Xaug; au.ldx[i] = ld_in; au.x_b[i] = aug_b;
-            if (aug_b > max_aug) max_aug = aug_b;
             t.state[2 * i] = a.state_in;      t.x[2 * i] = Xaug;        t.ldx[2 * i] = ld_in;     t.x_b[2 * i] = aug_b;
             t.dim[2 * i] = a.d_in + 1;
             t.state[2 * i + 1] = a.state_out; t.x[2 * i + 1] = a.delta; t.ldx[2 * i + 1] = a.ldd; t.x_b[2 * i + 1] = a.d_bstride;
             t.dim[2 * i + 1] = a.d_out;
         }
         {
-            int64_t gx = (max_aug + 255) / 256;
+            int64_t gx = (n + 3) / 4;         // a wavefront per row
             if (gx > 1024) gx = 1024;
             hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, nl, k), dim3(256), 0, s, au);
             NG_LAUNCHED();
