@@ -516,6 +516,25 @@ __global__ __launch_bounds__(256) void ng_sumsq_partial_slots_kernel(NgSlots t, 
     if (threadIdx.x == 0) t.part[q * kNgParts + blockIdx.x] = s;
 }
 
+// The coefficients of the apply and the fold of (slot, replica b) from its state: e, (1 - eta)(d + rho), 1 - e.
+// By the first `rank` threads of a workgroup.
+__device__ __forceinline__ void ng_coefficients(const NgSlots& t, int slot, int b, float alpha, float eta) {
+    const int64_t q = (int64_t)slot * t.batch + b;
+    const int dim = t.dim[slot], rank = t.rank;
+    const StateView v = state_view(t.state[slot] + (int64_t)b * t.st_b, dim, rank);
+    double sumd = 0.0;
+    for (int j = 0; j < rank; ++j) sumd += v.d[j];
+    const double rho = *v.rho;
+    const double beta = rho * (1.0 + (double)alpha) + (double)alpha * sumd / (double)dim;
+    if ((int)threadIdx.x < rank) {
+        const double di = v.d[threadIdx.x];
+        float* __restrict__ cf = t.coef + q * (3 * kMaxRank);
+        cf[threadIdx.x] = (float)(di / (di + beta));
+        cf[kMaxRank + threadIdx.x] = (float)((1.0 - (double)eta) * (di + rho));
+        cf[2 * kMaxRank + threadIdx.x] = (float)(beta / (di + beta));
+    }
+}
+
 // what & 1: sum the first `nparts` partial sums of every (slot, replica) in index order into scal[q][which]
 //           (which 0: ||X||^2, which 1: ||Xh||^2 and gamma[q] = ||X|| / ||Xh||, 1 if either is 0);
 // what & 2: the coefficients of the apply and the fold from the state (e, (1 - eta)(d + rho), 1 - e)
@@ -535,53 +554,37 @@ __global__ __launch_bounds__(256) void ng_sumsq_final_slots_kernel(NgSlots t, in
             }
         }
     }
-    if (what & 2) {
-        const int dim = t.dim[slot], rank = t.rank;
-        const StateView v = state_view(t.state[slot] + (int64_t)b * t.st_b, dim, rank);
-        double sumd = 0.0;
-        for (int j = 0; j < rank; ++j) sumd += v.d[j];
-        const double rho = *v.rho;
-        const double beta = rho * (1.0 + (double)alpha) + (double)alpha * sumd / (double)dim;
-        if ((int)threadIdx.x < rank) {
-            const double di = v.d[threadIdx.x];
-            float* __restrict__ cf = t.coef + q * (3 * kMaxRank);
-            cf[threadIdx.x] = (float)(di / (di + beta));
-            cf[kMaxRank + threadIdx.x] = (float)((1.0 - (double)eta) * (di + rho));
-            cf[2 * kMaxRank + threadIdx.x] = (float)(beta / (di + beta));
-        }
-    }
+    if (what & 2) ng_coefficients(t, slot, b, alpha, eta);
 }
 
 // Hout of every slot = sum of the slot's partial products (one per chunk of the contraction), in chunk order
 struct NgChunkTable { int first[kNgSlots], count[kNgSlots]; };
+// combine != 0 (Hout = t.H2): what is left is H (I - E) - (that sum) in the columns below the rank, the combination
+// the second rank update multiplies by R
 __global__ __launch_bounds__(256) void ng_sum_chunks_slots_kernel(NgSlots t, NgChunkTable ct, const float* __restrict__ P,
-                                                                  float* __restrict__ Hout) {
+                                                                  float* __restrict__ Hout, int combine) {
     const int slot = blockIdx.y, b = blockIdx.z;
     const int64_t q = (int64_t)slot * t.batch + b;
     const int64_t total4 = (int64_t)t.n * t.ldr / 4;            // ldr is a multiple of 4
     const int first = ct.first[slot], count = ct.count[slot];
     float4* __restrict__ out = reinterpret_cast<float4*>(Hout + q * t.H_b);
+    const float* __restrict__ ome = t.coef + q * (3 * kMaxRank) + 2 * kMaxRank;
+    const float4* __restrict__ H4 = reinterpret_cast<const float4*>(t.H + q * t.H_b);
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total4; e += (int64_t)gridDim.x * 256) {
         float4 a = reinterpret_cast<const float4*>(P + ((int64_t)first * t.batch + b) * t.H_b)[e];
         for (int c = 1; c < count; ++c) {
             const float4 v = reinterpret_cast<const float4*>(P + ((int64_t)(first + c) * t.batch + b) * t.H_b)[e];
             a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
         }
+        if (combine) {
+            const int i = (int)((4 * e) % t.ldr);               // column of a.x; the four elements share a row
+            const float4 h = H4[e];
+            if (i + 0 < t.rank) a.x = h.x * ome[i + 0] - a.x;
+            if (i + 1 < t.rank) a.y = h.y * ome[i + 1] - a.y;
+            if (i + 2 < t.rank) a.z = h.z * ome[i + 2] - a.z;
+            if (i + 3 < t.rank) a.w = h.w * ome[i + 3] - a.w;
+        }
         out[e] = a;
-    }
-}
-
-// H2 <- H (I - E) - H2 for every slot
-__global__ __launch_bounds__(256) void ng_combine_slots_kernel(NgSlots t) {
-    const int slot = blockIdx.y, b = blockIdx.z;
-    const int64_t q = (int64_t)slot * t.batch + b;
-    const float* __restrict__ ome = t.coef + q * (3 * kMaxRank) + 2 * kMaxRank;
-    const float* __restrict__ H = t.H + q * t.H_b;
-    float* __restrict__ H2 = t.H2 + q * t.H_b;
-    const int64_t total = (int64_t)t.n * t.ldr;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int i = (int)(e % t.ldr);
-        if (i < t.rank) H2[e] = H[e] * ome[i] - H2[e];
     }
 }
 
@@ -679,8 +682,14 @@ struct NgAugTable {
     int d[kNgSlots / 2];
     int n;
 };
-__global__ __launch_bounds__(256) void ng_augment_slots_kernel(NgAugTable t) {
+// With `coef` set the launch has one more row of workgroups (blockIdx.y = the number of layers): workgroup x of that
+// row leaves the coefficients of slot x (see ng_coefficients), which depend on the states alone.
+__global__ __launch_bounds__(256) void ng_augment_slots_kernel(NgAugTable t, NgSlots sl, float alpha, float eta, int coef) {
     const int l = blockIdx.y, b = blockIdx.z;
+    if (coef && l == (int)gridDim.y - 1) {      // (uniform over the workgroup)
+        if ((int)blockIdx.x < sl.nslots) ng_coefficients(sl, blockIdx.x, b, alpha, eta);
+        return;
+    }
     const int64_t ldx = t.ldx[l], lda = t.lda[l];
     const int d = t.d[l];
     const float* __restrict__ A = t.A[l] + (int64_t)b * t.a_b[l];
@@ -797,7 +806,7 @@ int ng_slots_norms(const NgSlots& t, int which, float alpha, float eta, hipStrea
 
 // Hout = X R^T for every slot: one launch over the chunks of all contractions (P: [chunk][replica][n x ldr]
 // partial products), then their sums
-int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s) {
+int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s, bool combine = false) {
     GemmDesc g[kThinMaxProblems];
     NgChunkTable ct = {};
     int np = 0, pi = 0;                               // descriptors pending, problems so far
@@ -821,7 +830,7 @@ int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s) {
     if (np > 0) NG_CHECK(gemm_launch_grouped(g, np, s, true));
     int64_t gx = ((int64_t)t.n * t.ldr / 4 + 255) / 256;
     if (gx > 64) gx = 64;
-    hipLaunchKernelGGL(ng_sum_chunks_slots_kernel, dim3((unsigned)gx, t.nslots, t.batch), dim3(256), 0, s, t, ct, P, Hout);
+    hipLaunchKernelGGL(ng_sum_chunks_slots_kernel, dim3((unsigned)gx, t.nslots, t.batch), dim3(256), 0, s, t, ct, P, Hout, combine ? 1 : 0);
     NG_LAUNCHED();
     return 0;
 }
@@ -844,14 +853,6 @@ inline bool ng_parts_fit(const NgSlots& t) {
     int maxdim = 0;
     for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
     return (int64_t)((maxdim + 127) / 128) * ((t.n + 63) / 64) <= kNgParts;
-}
-
-int ng_slots_combine(const NgSlots& t, hipStream_t s) {
-    int64_t gx = ((int64_t)t.n * t.ldr + 255) / 256;
-    if (gx > 1024) gx = 1024;
-    hipLaunchKernelGGL(ng_combine_slots_kernel, dim3((unsigned)gx, t.nslots, t.batch), dim3(256), 0, s, t);
-    NG_LAUNCHED();
-    return 0;
 }
 
 int ng_run(const NgCall& c, hipStream_t s) {
@@ -913,8 +914,7 @@ int ng_run(const NgCall& c, hipStream_t s) {
     NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
     if (c.mode >= 1) NG_CHECK(gemm_Y());
     NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s));      // X1 = X - H R
-    NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s));           // H2 = X1 R^T  (what the first pass left inside the subspace)
-    NG_CHECK(ng_slots_combine(t, s));
+    NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s, true));     // H (I - E) - H2, H2 = X1 R^T  (what the first pass left inside the subspace)
     NG_CHECK(ng_slots_rank_update(t, 1, 1.f, s));       // Xh = X1 + (H (I - E) - H2) R
     NG_CHECK(ng_slots_norms(t, 1, c.alpha, c.eta, s));  // ||Xh||^2, gamma
     if (c.scale) {
@@ -1070,7 +1070,7 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
         NgAugTable au;
         au.A[0] = a.A_in; au.lda[0] = a.a_ld; au.a_b[0] = a.a_bstride; au.d[0] = a.d_in;
         au.X[0] = Xaug; au.ldx[0] = ld_in; au.x_b[0] = aug_b; au.n = a.n;
-        hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, 1, a.k), dim3(256), 0, s, au);
+        hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, 1, a.k), dim3(256), 0, s, au, NgSlots(), 0.f, 0.f, 0);
         NG_LAUNCHED();
     }
     NgCall c;
@@ -1100,7 +1100,7 @@ int ng_layer_update(const NgLayerArgs& a, hipStream_t s) {
 
 
 // The preconditioned update of every layer (steady state: one fold per minibatch), a fixed number of launches
-// whatever the depth: augment, ||X||^2 + coefficients, H, Y, X1, H2, combine, Xh, ||Xh||^2 + gamma, then the weight
+// whatever the depth: augment, ||X||^2 + coefficients, H, Y, X1, H2 (combined with H where its chunks are summed), Xh, ||Xh||^2 + gamma, then the weight
 // gradients of all layers as one grouped launch.  The folds stay pending until ng_dnn_finish.
 int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t state_stride, hipStream_t s) {
     const NgLayerArgs& a0 = layers[0];
@@ -1145,23 +1145,22 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
             t.state[2 * i + 1] = a.state_out; t.x[2 * i + 1] = a.delta; t.ldx[2 * i + 1] = a.ldd; t.x_b[2 * i + 1] = a.d_bstride;
             t.dim[2 * i + 1] = a.d_out;
         }
+        // The two rank updates take the norms with them (||X||^2 as the first one reads X, ||Xh||^2 as the second one
+        // writes it) whenever the per-workgroup partial sums fit their table: two passes over the matrices fewer.  Then
+        // the coefficients, which depend on the states alone, are left by one more row of workgroups of the launch
+        // that augments the inputs.
+        const bool fused = ng_parts_fit(t);
         {
             int64_t gx = (n + 3) / 4;         // a wavefront per row
             if (gx > 1024) gx = 1024;
-            hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, nl, k), dim3(256), 0, s, au);
+            if (gx < t.nslots) gx = t.nslots;
+            hipLaunchKernelGGL(ng_augment_slots_kernel, dim3((unsigned)gx, nl + (fused ? 1 : 0), k), dim3(256), 0, s, au, t,
+                               a0.alpha, a0.eta, fused ? 1 : 0);
             NG_LAUNCHED();
         }
         float* P = ws + lay.hp_off;                      // partial products [problem][replica][n x ldr]
-        // The two rank updates take the norms with them (||X||^2 as the first one reads X, ||Xh||^2 as the second one
-        // writes it) whenever the per-workgroup partial sums fit their table: two passes over the matrices fewer.
-        const bool fused = ng_parts_fit(t);
         int nparts = 0;
-        if (fused) {
-            hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, 0, a0.alpha, a0.eta, 0, 2);
-            NG_LAUNCHED();
-        } else {
-            NG_CHECK(ng_slots_norms(t, 0, a0.alpha, a0.eta, s));
-        }
+        if (!fused) NG_CHECK(ng_slots_norms(t, 0, a0.alpha, a0.eta, s));
         NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
         if (a0.mode >= 1) {   // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it
             GemmDesc g[kNgSlots];
@@ -1193,8 +1192,7 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
             const NgFoldTable tb = ng_dnn_fold_table(lay, a0.dims, L, k, ng_state, state_stride, ws, 0);
             NG_CHECK(ng_finish_zeig(tb, rank, n, a0.eta, false, Zf, Wtf, 1, side->stream));
         }
-        NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s));            // H2 = X1 R^T
-        NG_CHECK(ng_slots_combine(t, s));
+        NG_CHECK(ng_slots_gemm_H(t, P, t.H2, s, true));      // H (I - E) - H2, H2 = X1 R^T: combined where the chunks are summed
         NG_CHECK(ng_slots_rank_update(t, 1, 1.f, s, fused ? 2 : 0, &nparts));     // Xh = X1 + (H (I - E) - H2) R (, ||Xh||^2, last column)
         if (side) {      // R has been read for the last time: the fold may write it
             NG_CHECK(note_hip_error(hipEventRecord(side->ev[1], s)));
