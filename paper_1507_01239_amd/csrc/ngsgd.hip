@@ -106,6 +106,8 @@ __device__ __forceinline__ double block_sum_d(double v, double* sh) {
 
 // the eigen-solver runs 512 threads: 16 groups of 32 lanes, one group per rotation pair up to rank 32
 constexpr int kEigThreads = 512;
+constexpr int kEigSoloLds = 120 * 1024;      // bytes of LDS a solver workgroup asks for to have its compute unit to itself
+constexpr int kEigSoloMax = 64;              // ... in launches of at most this many workgroups
 __device__ __forceinline__ double block_sum_eig(double v, double* sh) {
     v = wave_sum(v);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
@@ -593,6 +595,9 @@ __global__ __launch_bounds__(256) void ng_sum_chunks_slots_kernel(NgSlots t, NgC
 // of 32; per tile it reads 32 x rank of Cm (16 contiguous floats per lane) and 32 x 32 of X, multiplies with
 // 16 KH v_mfma_f32_32x32x2_f32 and adds the product to X.  Contraction index of MFMA step s: k = 32 kh + s in
 // lanes 0-31 and 32 kh + 16 + s in lanes 32-63, zero operands beyond `rank`.  No LDS in the loop, no barrier.
+// (The other order - the block of Cm in registers, walking along the columns and reading a block of R per 32 x 32 of
+// X - was measured slower, 56 against 42 us for the 14 matrices of 512 rows of the 440-6x2048-8000 network: the blocks of R,
+// 3.4 MB in all, do not stay in the L2 beside the stream of X.)
 //
 // `fuse` folds the passes over the matrices that take the norms into the two rank updates of a preconditioning:
 //   0  nothing else;
@@ -603,33 +608,58 @@ __global__ __launch_bounds__(256) void ng_sum_chunks_slots_kernel(NgSlots t, NgC
 // (Summing the chunks of H2 and forming H (I - E) - H2 on the way in as well was measured slower: every one of the
 // up to 250 column blocks of a slot would redo that sum.)
 typedef float ng_floatx16 __attribute__((ext_vector_type(16)));
-template <int KH>
-__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows, int fuse) {
+// A pointer that is uniform over the wavefront, pinned to scalar registers: an access through it plus a 32-bit
+// per-lane offset takes the scalar-base form of the memory instructions, one offset register per access pattern
+// instead of a 64-bit address per access.  (The result is typed as a pointer to global memory: rebuilt from an
+// integer, a plain pointer would be accessed with flat instructions.)
+typedef __attribute__((address_space(1))) char ng_gchar;
+typedef __attribute__((address_space(1))) float ng_gfloat;
+__device__ __forceinline__ ng_gchar* ng_uniform_ptr(const char* p) {
+    const uint64_t x = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return reinterpret_cast<ng_gchar*>(((uint64_t)hi << 32) | lo);
+}
+template <int KH, int FUSE>
+__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows) {
+    constexpr int fuse = FUSE;
     __shared__ double sh[4];
     const int slot = blockIdx.z / t.batch, b = blockIdx.z - slot * t.batch;
     const int dim = t.dim[slot], n = t.n, rank = t.rank;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5, lc = lane & 31;
-    const int c0 = (blockIdx.x * 4 + wave) * 32;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, h = lane >> 5, lc = lane & 31;
+    const int c0 = (blockIdx.x * 4 + wave) * 32;        // (uniform over the wavefront)
     const int64_t q = (int64_t)slot * t.batch + b;
     float ssq = 0.f;
     if (c0 < dim) {                                     // the grid is as wide as the widest slot
         const int col = c0 + lc;
         const bool col_ok = col < dim;
+        const int lcc = min(lc, dim - 1 - c0);          // the lane's column of the block, clamped for the loads
         const int64_t ldR = ((int64_t)dim + 3) / 4 * 4, ldx = t.ldx[slot], ldc = t.ldr;
-        const float* __restrict__ R = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b);
+        const uint32_t ldx4 = (uint32_t)ldx * 4u, ldR4 = (uint32_t)ldR * 4u;       // bytes per row
+        const char* __restrict__ Rc = reinterpret_cast<const char*>(t.state[slot] + (int64_t)b * t.st_b) + (int64_t)c0 * 4;
         const float* __restrict__ C = (use_h2 ? t.H2 : t.H) + q * t.H_b;
         float* __restrict__ X = t.x[slot] + (int64_t)b * t.x_b[slot];
+        // the block of R: (uniform) row min(ku, rank - 1); a lane whose own row ku + 16 lies beyond R reads that row instead
+        const uint32_t offR0 = (uint32_t)lcc * 4u, offR1 = offR0 + (uint32_t)(16 * h) * ldR4;
         float bf[KH][16];
 #pragma unroll
         for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
             for (int s = 0; s < 16; ++s) {
-                const int k = 32 * kh + 16 * h + s;
-                bf[kh][s] = (k < rank && col_ok) ? R[(int64_t)k * ldR + col] : 0.f;
+                const int ku = min(32 * kh + s, rank - 1);
+                const ng_gchar* rowp = ng_uniform_ptr(Rc + (uint32_t)ku * ldR4);
+                bf[kh][s] = *reinterpret_cast<const ng_gfloat*>(rowp + (32 * kh + s + 16 < rank ? offR1 : offR0));
             }
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+            for (int s = 0; s < 16; ++s)
+                if (!(32 * kh + 16 * h + s < rank && col_ok)) bf[kh][s] = 0.f;
+        const uint32_t offX = (uint32_t)lcc * 4u + (uint32_t)(4 * h) * ldx4;
         const int rbeg = blockIdx.y * rows, rend = min(n, rbeg + rows);
         for (int r0 = rbeg; r0 < rend; r0 += 32) {
             const int row = r0 + lc;
+            const bool interior = r0 + 32 <= rend;      // (uniform) else per-lane addresses and row checks
+            const char* Xr = reinterpret_cast<const char*>(X + (int64_t)r0 * ldx) + (int64_t)c0 * 4;
             float af[KH][16];
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh)
@@ -644,26 +674,54 @@ __global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, in
                     af[kh][4 * j + 3] = (k4 + 3 < rank) ? v.w : 0.f;
                 }
             float old[16];
+            if (interior) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                old[v] = (rr < rend && col_ok) ? X[(int64_t)rr * ldx + col] : 0.f;
-                if (fuse == 1) ssq += old[v] * old[v];
+                for (int v = 0; v < 16; ++v)
+                    old[v] = *reinterpret_cast<const ng_gfloat*>(ng_uniform_ptr(Xr + (uint32_t)(8 * (v >> 2) + (v & 3)) * ldx4) + offX);
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (!col_ok) old[v] = 0.f;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    old[v] = (rr < rend && col_ok) ? X[(int64_t)rr * ldx + col] : 0.f;
+                }
+            }
+            if (fuse == 1) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) ssq += old[v] * old[v];
             }
             ng_floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh)
 #pragma unroll
                 for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(af[kh][s], bf[kh][s], acc, 0, 0, 0);
+            if (interior) {
+                if (col_ok) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (rr < rend && col_ok) {
-                    const float xn = old[v] + sign * acc[v];
-                    X[(int64_t)rr * ldx + col] = xn;
-                    if (fuse == 2) {
-                        ssq += xn * xn;
-                        if (col == dim - 1) t.wcol[q * n + rr] = xn;
+                    for (int v = 0; v < 16; ++v) {
+                        const float xn = old[v] + sign * acc[v];
+                        *reinterpret_cast<ng_gfloat*>(ng_uniform_ptr(Xr + (uint32_t)(8 * (v >> 2) + (v & 3)) * ldx4) + offX) = xn;
+                        if (fuse == 2) ssq += xn * xn;
+                        old[v] = xn;
+                    }
+                    if (fuse == 2 && col == dim - 1) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) t.wcol[q * n + r0 + 8 * (v >> 2) + (v & 3) + 4 * h] = old[v];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (rr < rend && col_ok) {
+                        const float xn = old[v] + sign * acc[v];
+                        X[(int64_t)rr * ldx + col] = xn;
+                        if (fuse == 2) {
+                            ssq += xn * xn;
+                            if (col == dim - 1) t.wcol[q * n + rr] = xn;
+                        }
                     }
                 }
             }
@@ -759,13 +817,22 @@ int ng_eig_smem_bytes(int rank) { return (4 * rank * ((rank + 1) & ~1) + 16) * 8
 // Z = Y Y^T and its eigen-decomposition, new (d, rho, t) and Wt for every (slot, replica) of the table: two launches.
 // Reads Y, the squared norms and the old d, rho; does not touch R.
 int ng_finish_zeig(const NgFoldTable& tb, int rank, int n, float eta, bool y64, double* Z, double* Wt, int bump, hipStream_t s) {
-    const int smem = ng_eig_smem_bytes(rank);
+    // A few workgroups (one per state) on a long chain of dependent LDS accesses and float64 operations, usually
+    // launched beside kernels that fill the chip: sharing its compute unit with their workgroups was measured to slow
+    // the solver twofold (350 against 180 us for 14 states of rank 30 beside the rank update and the weight-gradient
+    // GEMMs; 120 us with the chip to itself), so a launch of few workgroups asks for so much LDS (kEigSoloLds) that no
+    // workgroup of a GEMM fits beside it.
+    const int need = ng_eig_smem_bytes(rank);
+    const int smem = (tb.nslots * tb.batch <= kEigSoloMax && need < kEigSoloLds) ? kEigSoloLds : need;
     if (smem > 64 * 1024) {
-        static bool raised = false;     // idempotent; benign if two threads race to set the same value
-        if (!raised) {
+        constexpr int kMaxDev = 64;
+        static int raised[kMaxDev] = {};    // per device, the largest size allowed so far (benign if two threads race: the call is idempotent)
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) dev = -1;
+        if (dev < 0 || raised[dev] < smem) {
             NG_CHECK(note_hip_error(hipFuncSetAttribute(reinterpret_cast<const void*>(ng_eig_kernel),
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, smem)));
-            raised = true;
+            if (dev >= 0) raised[dev] = smem;
         }
     }
     const dim3 gz(rank * rank, tb.nslots, tb.batch);
@@ -835,24 +902,34 @@ int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s, bool
     return 0;
 }
 
+constexpr int kRuRows = 128;          // rows a wavefront of a rank update walks with its block of R in registers
+
 // X <- X + sign * (H or H2) R for every slot
 // fuse: see the kernel; *nparts (when asked for) receives the number of partial sums of squares per (slot, replica)
 // the launch leaves.
 int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s, int fuse = 0, int* nparts = nullptr) {
-    constexpr int kRows = 64;                        // rows a wavefront walks with its block of R in registers
     int maxdim = 0;
     for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
-    const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((t.n + kRows - 1) / kRows), (unsigned)(t.nslots * t.batch));
+    const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((t.n + kRuRows - 1) / kRuRows), (unsigned)(t.nslots * t.batch));
     if (nparts) *nparts = (int)(grid.x * grid.y);
-    if (t.rank <= 32) hipLaunchKernelGGL(ng_rank_update_slots_kernel<1>, grid, dim3(256), 0, s, t, use_h2, sign, kRows, fuse);
-    else hipLaunchKernelGGL(ng_rank_update_slots_kernel<2>, grid, dim3(256), 0, s, t, use_h2, sign, kRows, fuse);
+    auto launch = [&](auto khc, auto fusec) {
+        constexpr int KH = decltype(khc)::value, FUSE = decltype(fusec)::value;
+        hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, FUSE>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows);
+    };
+    auto launch_kh = [&](auto khc) {
+        if (fuse == 0) launch(khc, std::integral_constant<int, 0>{});
+        else if (fuse == 1) launch(khc, std::integral_constant<int, 1>{});
+        else launch(khc, std::integral_constant<int, 2>{});
+    };
+    if (t.rank <= 32) launch_kh(std::integral_constant<int, 1>{});
+    else launch_kh(std::integral_constant<int, 2>{});
     NG_LAUNCHED();
     return 0;
 }
 inline bool ng_parts_fit(const NgSlots& t) {
     int maxdim = 0;
     for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
-    return (int64_t)((maxdim + 127) / 128) * ((t.n + 63) / 64) <= kNgParts;
+    return (int64_t)((maxdim + 127) / 128) * ((t.n + kRuRows - 1) / kRuRows) <= kNgParts;
 }
 
 int ng_run(const NgCall& c, hipStream_t s) {
@@ -1112,7 +1189,10 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
     // is a chain of small, latency-bound launches (14 workgroups in the eigen-solver): with all layers in one pass it
     // runs on the internal stream beside the rest of the apply and the weight update, which occupy the whole chip.
     // Its last step, the only one that writes R, waits until the apply has read R for the last time; the caller's
-    // stream waits for it before this call's work is complete.
+    // stream waits for it before this call's work is complete.  (Forking only once, behind the second rank update,
+    // would spare the caller's stream one record of an event, about 6 us between two launches, but was measured
+    // slower by 90 us: a launch of the internal stream that arrives while the weight-gradient launch holds every
+    // compute unit gets its workgroups placed only as that launch drains.)
     SideStream* side = (a0.mode == 1 && L <= kNgSlots / 2) ? side_stream() : nullptr;
     double* Zf = reinterpret_cast<double*>(ws + lay.z_off);
     double* Wtf = reinterpret_cast<double*>(ws + lay.wt_off);
