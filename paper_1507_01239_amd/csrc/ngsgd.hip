@@ -619,8 +619,16 @@ __device__ __forceinline__ ng_gchar* ng_uniform_ptr(const char* p) {
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
     return reinterpret_cast<ng_gchar*>(((uint64_t)hi << 32) | lo);
 }
-template <int KH, int FUSE>
-__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows) {
+// Where Y of every slot goes (replica b at + b * y_b floats), and, for the rank update that takes Y's product with
+// it, where the partial products go: that of the rows of workgroup row c at P + c * p_chunk (+ b * y_b), laid out like Y.
+struct NgYTable { float* Y[kNgSlots]; int64_t y_b[kNgSlots]; float* P[kNgSlots]; int64_t p_chunk; };
+// WITHY (with fuse 1, Cm = H): the launch also leaves H^T X of its rows, X as it was read, for the fold of the
+// state (Y = alpha H^T X + diag(coef1) R, finished by ng_y_reduce_slots_kernel): X's block is in registers in the
+// layout of an MFMA B operand already (lane = column; MFMA step v multiplies row 8 (v / 4) + v % 4 in lanes 0-31 and
+// the row four further on in lanes 32-63), so the product costs 16 KH loads of H from the caches and 16 KH MFMAs
+// per block instead of a pass of its own over X.
+template <int KH, int FUSE, bool WITHY>
+__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows, NgYTable yt) {
     constexpr int fuse = FUSE;
     __shared__ double sh[4];
     const int slot = blockIdx.z / t.batch, b = blockIdx.z - slot * t.batch;
@@ -656,6 +664,14 @@ __global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, in
                 if (!(32 * kh + 16 * h + s < rank && col_ok)) bf[kh][s] = 0.f;
         const uint32_t offX = (uint32_t)lcc * 4u + (uint32_t)(4 * h) * ldx4;
         const int rbeg = blockIdx.y * rows, rend = min(n, rbeg + rows);
+        const uint32_t ldc4 = (uint32_t)ldc * 4u;
+        uint32_t offHy[KH];
+        ng_floatx16 yacc[KH];
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+            offHy[kh] = (uint32_t)min(32 * kh + lc, (int)ldc - 1) * 4u + (uint32_t)(4 * h) * ldc4;
+            yacc[kh] = ng_floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        }
         for (int r0 = rbeg; r0 < rend; r0 += 32) {
             const int row = r0 + lc;
             const bool interior = r0 + 32 <= rend;      // (uniform) else per-lane addresses and row checks
@@ -692,6 +708,29 @@ __global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, in
 #pragma unroll
                 for (int v = 0; v < 16; ++v) ssq += old[v] * old[v];
             }
+            if constexpr (WITHY) {       // H^T X of this block of rows: lane i of the A operand holds H(row of the step, i)
+                float hy[KH][16];
+                if (interior) {
+                    const char* Hr = reinterpret_cast<const char*>(C + (int64_t)r0 * ldc);
+#pragma unroll
+                    for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+                            hy[kh][v] = *reinterpret_cast<const ng_gfloat*>(ng_uniform_ptr(Hr + (uint32_t)(8 * (v >> 2) + (v & 3)) * ldc4) + offHy[kh]);
+                } else {
+#pragma unroll
+                    for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int rr = r0 + 8 * (v >> 2) + 4 * h + (v & 3);
+                            hy[kh][v] = (rr < rend && 32 * kh + lc < rank) ? C[(int64_t)rr * ldc + 32 * kh + lc] : 0.f;
+                        }
+                }
+#pragma unroll
+                for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) yacc[kh] = __builtin_amdgcn_mfma_f32_32x32x2f32(hy[kh][v], old[v], yacc[kh], 0, 0, 0);
+            }
             ng_floatx16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh)
@@ -726,11 +765,129 @@ __global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, in
                 }
             }
         }
+        if constexpr (WITHY) {
+            float* __restrict__ Pp = yt.P[slot] + (int64_t)blockIdx.y * yt.p_chunk + (int64_t)b * yt.y_b[slot];
+#pragma unroll
+            for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int i = 32 * kh + 8 * (v >> 2) + 4 * h + (v & 3);
+                    if (i < rank && col_ok) Pp[(int64_t)i * ldR + col] = yacc[kh][v];
+                }
+        }
     }
     if (fuse != 0) {      // (uniform over the workgroup: every wavefront reaches the barriers)
         const double tot = block_sum_d((double)ssq, sh);
         if (threadIdx.x == 0) t.part[q * kNgParts + blockIdx.y * gridDim.x + blockIdx.x] = tot;
     }
+}
+
+// Y = alpha (sum of the `nchunks` partial products H^T X the first rank update left) + diag(coef1) R for every slot
+__global__ __launch_bounds__(256) void ng_y_reduce_slots_kernel(NgSlots t, NgYTable yt, float alpha, int nchunks) {
+    const int slot = blockIdx.y, b = blockIdx.z;
+    const int dim = t.dim[slot], rank = t.rank;
+    const int64_t q = (int64_t)slot * t.batch + b;
+    const int ld = (dim + 3) / 4 * 4, ld4 = ld / 4;
+    const float* __restrict__ R = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b);
+    const float* __restrict__ cf = t.coef + q * (3 * kMaxRank) + kMaxRank;
+    const float* __restrict__ P = yt.P[slot] + (int64_t)b * yt.y_b[slot];
+    float* __restrict__ Y = yt.Y[slot] + (int64_t)b * yt.y_b[slot];
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < rank * ld4; e += gridDim.x * 256) {
+        const int i = e / ld4, col = (e - i * ld4) * 4;
+        float4 a = *reinterpret_cast<const float4*>(P + (int64_t)e * 4);
+        for (int c = 1; c < nchunks; ++c) {
+            const float4 v = *reinterpret_cast<const float4*>(P + (int64_t)c * yt.p_chunk + (int64_t)e * 4);
+            a.x += v.x; a.y += v.y; a.z += v.z; a.w += v.w;
+        }
+        const float4 r = *reinterpret_cast<const float4*>(R + (int64_t)e * 4);
+        const float ci = cf[i];
+        float* y = Y + (int64_t)e * 4;
+        if (col + 3 < dim) {
+            *reinterpret_cast<float4*>(y) = make_float4(alpha * a.x + ci * r.x, alpha * a.y + ci * r.y, alpha * a.z + ci * r.z, alpha * a.w + ci * r.w);
+        } else {        // the padding columns of a row are left alone (their partial products were never written)
+            if (col + 0 < dim) y[0] = alpha * a.x + ci * r.x;
+            if (col + 1 < dim) y[1] = alpha * a.y + ci * r.y;
+            if (col + 2 < dim) y[2] = alpha * a.z + ci * r.z;
+        }
+    }
+}
+
+// Y = alpha H^T X + diag(coef1) R for every slot (the matrix the fold of the state starts from; coef1 = the second
+// of the three coefficient vectors).  A workgroup owns 32 columns; its four wavefronts take every fourth tile of 32
+// rows: per tile 16 (x KH) v_mfma_f32_32x32x2_f32 with H^T as the A operand (lane i, MFMA step s: H(r0 + 16 h + s, i))
+// and X as the B operand (lane j: X(r0 + 16 h + s, c0 + j)), every load a whole 128-byte row segment of H or X per
+// half-wavefront through a scalar row pointer and one offset register per matrix.  The four partial products meet in
+// LDS and each wavefront finishes 8 of the 32 (x KH) rows.  X is read once, at the pace of the rank updates; the 14
+// products of the 440-6x2048-8000 network took two launches of the general GEMM (tiles of 64 rows for 30) and 38 us.
+// Columns and rank indices beyond the matrices are clamped for the loads: they reach only accumulator columns
+// and rows that are never stored.
+template <int KH>
+__global__ __launch_bounds__(256) void ng_y_slots_kernel(NgSlots t, NgYTable yt, float alpha) {
+    __shared__ float red[4][KH][16 * 64];
+    const int slot = blockIdx.y, b = blockIdx.z;
+    const int dim = t.dim[slot], n = t.n, rank = t.rank;
+    const int c0 = blockIdx.x * 32;
+    if (c0 >= dim) return;                              // the grid is as wide as the widest slot (uniform over the workgroup)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, h = lane >> 5, lc = lane & 31;
+    const int64_t q = (int64_t)slot * t.batch + b;
+    const int col = c0 + lc;
+    const bool col_ok = col < dim;
+    const int lcc = min(lc, dim - 1 - c0);
+    const int64_t ldR = ((int64_t)dim + 3) / 4 * 4, ldx = t.ldx[slot], ldc = t.ldr;
+    const uint32_t ldx4 = (uint32_t)ldx * 4u, ldc4 = (uint32_t)ldc * 4u;        // bytes per row
+    const float* __restrict__ X = t.x[slot] + (int64_t)b * t.x_b[slot];
+    const float* __restrict__ Hm = t.H + q * t.H_b;
+    const char* Xc = reinterpret_cast<const char*>(X) + (int64_t)c0 * 4;
+    const char* Hc = reinterpret_cast<const char*>(Hm);
+    const uint32_t offX = (uint32_t)lcc * 4u + (uint32_t)(16 * h) * ldx4;
+    uint32_t offH[KH];
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) offH[kh] = (uint32_t)min(32 * kh + lc, (int)ldc - 1) * 4u + (uint32_t)(16 * h) * ldc4;
+    ng_floatx16 acc[KH];
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh) acc[kh] = ng_floatx16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int r0 = wave * 32; r0 < n; r0 += 128) {
+        float bx[16], ah[KH][16];
+        if (r0 + 32 <= n) {                             // (uniform)
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                bx[s] = *reinterpret_cast<const ng_gfloat*>(ng_uniform_ptr(Xc + (int64_t)(r0 + s) * ldx4) + offX);
+#pragma unroll
+                for (int kh = 0; kh < KH; ++kh)
+                    ah[kh][s] = *reinterpret_cast<const ng_gfloat*>(ng_uniform_ptr(Hc + (int64_t)(r0 + s) * ldc4) + offH[kh]);
+            }
+        } else {                                        // the last, ragged tile: per-lane addresses and row checks
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                const int r = r0 + 16 * h + s;
+                bx[s] = (r < n && col_ok) ? X[(int64_t)r * ldx + col] : 0.f;
+#pragma unroll
+                for (int kh = 0; kh < KH; ++kh) ah[kh][s] = (r < n && 32 * kh + lc < rank) ? Hm[(int64_t)r * ldc + 32 * kh + lc] : 0.f;
+            }
+        }
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+            for (int s = 0; s < 16; ++s) acc[kh] = __builtin_amdgcn_mfma_f32_32x32x2f32(ah[kh][s], bx[s], acc[kh], 0, 0, 0);
+    }
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][kh][v * 64 + lane] = acc[kh][v];
+    __syncthreads();
+    // accumulator element v of a lane: rank index 32 kh + 8 (v / 4) + 4 h + v % 4, column c0 + lc; wavefront w finishes v / 4 = w
+    const float* __restrict__ R = reinterpret_cast<const float*>(t.state[slot] + (int64_t)b * t.st_b);
+    const float* __restrict__ cf = t.coef + q * (3 * kMaxRank) + kMaxRank;
+    float* __restrict__ Y = yt.Y[slot] + (int64_t)b * yt.y_b[slot];
+#pragma unroll
+    for (int kh = 0; kh < KH; ++kh)
+#pragma unroll
+        for (int vv = 0; vv < 4; ++vv) {
+            const int e = (4 * wave + vv) * 64 + lane;
+            const float sum = ((red[0][kh][e] + red[1][kh][e]) + red[2][kh][e]) + red[3][kh][e];
+            const int i = 32 * kh + 8 * wave + 4 * h + vv;
+            if (i < rank && col_ok) Y[(int64_t)i * ldR + col] = alpha * sum + cf[i] * R[(int64_t)i * ldR + col];
+        }
 }
 
 // Xaug_l[b](r, 0..d) = A_l[b](r, :), Xaug_l[b](r, d) = 1, padding columns 0, for up to kNgSlots / 2 layers
@@ -903,21 +1060,29 @@ int ng_slots_gemm_H(const NgSlots& t, float* P, float* Hout, hipStream_t s, bool
 }
 
 constexpr int kRuRows = 128;          // rows a wavefront of a rank update walks with its block of R in registers
+constexpr int kYChunksMax = 8;        // partial products H^T X (one per kRuRows rows) a backward pass keeps at most
+inline int ng_ru_row_chunks(int n) { return (n + kRuRows - 1) / kRuRows; }
 
 // X <- X + sign * (H or H2) R for every slot
 // fuse: see the kernel; *nparts (when asked for) receives the number of partial sums of squares per (slot, replica)
 // the launch leaves.
-int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s, int fuse = 0, int* nparts = nullptr) {
+int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s, int fuse = 0, int* nparts = nullptr,
+                         const NgYTable* yt = nullptr) {
     int maxdim = 0;
     for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
     const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((t.n + kRuRows - 1) / kRuRows), (unsigned)(t.nslots * t.batch));
     if (nparts) *nparts = (int)(grid.x * grid.y);
+    if (yt != nullptr && (fuse != 1 || use_h2 != 0)) return note_hip_error(hipErrorInvalidValue);
+    const NgYTable none = {};
     auto launch = [&](auto khc, auto fusec) {
         constexpr int KH = decltype(khc)::value, FUSE = decltype(fusec)::value;
-        hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, FUSE>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows);
+        hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, FUSE, false>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows, none);
     };
     auto launch_kh = [&](auto khc) {
+        constexpr int KH = decltype(khc)::value;
         if (fuse == 0) launch(khc, std::integral_constant<int, 0>{});
+        else if (fuse == 1 && yt != nullptr)
+            hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, 1, true>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows, *yt);
         else if (fuse == 1) launch(khc, std::integral_constant<int, 1>{});
         else launch(khc, std::integral_constant<int, 2>{});
     };
@@ -1021,6 +1186,7 @@ namespace {
 // that one layer's update reuses.
 struct NgDnnLayout {
     int64_t y_off[2 * 64], y_b[2 * 64];     // slot 2(l-1): input side of layer l, slot 2(l-1)+1: output side
+    int64_t y_total, py_off; int py_chunks;  // partial products H^T X per block of rows of the first rank update: py_chunks copies of the Y region (0: not kept)
     int64_t scal_off, z_off, wt_off, layer_off, layer_floats, total;
     // all layers at once: augmented inputs of every layer, then per-(slot, replica) H, H2, coefficients, partial
     // sums and gamma
@@ -1065,6 +1231,9 @@ NgDnnLayout ng_dnn_layout(const int* d, int L, int n, int k, int rank) {
     for (int l = 1; l <= L; ++l) nprob += ng_chunk_count(d[l - 1] + 1) + ng_chunk_count(d[l]);
     y.hp_off = off;    off += nprob * k * y.H_b;
     y.wcol_off = off;  off += round_up(q * n, 64);
+    y.y_total = y.scal_off;                            // the Y region starts the layout
+    y.py_chunks = ng_ru_row_chunks(n) <= kYChunksMax ? ng_ru_row_chunks(n) : 0;
+    y.py_off = off;    off += (int64_t)y.py_chunks * y.y_total;
     y.total = off;
     return y;
 }
@@ -1242,25 +1411,35 @@ int ng_dnn_update(const NgLayerArgs* layers, int L, char* ng_state, int64_t stat
         int nparts = 0;
         if (!fused) NG_CHECK(ng_slots_norms(t, 0, a0.alpha, a0.eta, s));
         NG_CHECK(ng_slots_gemm_H(t, P, t.H, s));
-        if (a0.mode >= 1) {   // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it
-            GemmDesc g[kNgSlots];
-            for (int j = 0; j < t.nslots; ++j) {
-                GemmDesc& q = g[j];
-                const int64_t ld = round_up(t.dim[j], 4);
-                q.M = rank; q.N = t.dim[j]; q.K = n; q.batch = k;
-                q.A = t.H + (int64_t)j * k * lay.H_b; q.lda = lay.ldr; q.a_bstride = lay.H_b; q.a_kc = false;
-                q.a_pad4 = true;        // rows of H are ldr = round_up(rank, 4) floats long
-                q.B = t.x[j]; q.ldb = t.ldx[j]; q.b_bstride = t.x_b[j]; q.b_kc = false;
-                q.b_pad4 = t.ldx[j] >= ld;
-                q.C = ws + lay.y_off[j0 + j]; q.ldc = ld; q.c_bstride = lay.y_b[j0 + j];
-                q.epi.kind = EPI_ROWSCALE_ADD; q.epi.alpha = a0.eta / (float)n;
-                q.epi.rowvec = t.coef + (int64_t)j * k * 3 * kMaxRank + kMaxRank; q.epi.rowvec_bstride = 3 * kMaxRank;
-                q.epi.aux = reinterpret_cast<const float*>(t.state[j]); q.epi.ldaux = ld; q.epi.aux_bstride = t.st_b / 4;
-            }
-            NG_CHECK(gemm_launch_grouped(g, t.nslots, s));
+        // Y = (eta/n) H^T X + (1-eta)(diag(d)+rho I) R for every slot, left where ng_dnn_finish expects it: the product
+        // is taken by the first rank update as it reads X (one partial product per block of kRuRows rows, summed by a
+        // small launch), or by a pass of its own where those partial products have no room.
+        NgYTable yt = {};
+        int maxdim = 0;
+        for (int j = 0; j < t.nslots; ++j) {
+            yt.Y[j] = ws + lay.y_off[j0 + j]; yt.y_b[j] = lay.y_b[j0 + j];
+            yt.P[j] = ws + lay.py_off + lay.y_off[j0 + j];
+            if (t.dim[j] > maxdim) maxdim = t.dim[j];
         }
-        if (fused) {                                         // X1 = X - H R, and ||X||^2
-            NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s, 1, &nparts));
+        yt.p_chunk = lay.y_total;
+        const bool with_y = a0.mode >= 1, fuse_y = with_y && fused && lay.py_chunks > 0;
+        if (with_y && !fuse_y) {
+            const dim3 gy((unsigned)((maxdim + 31) / 32), (unsigned)t.nslots, (unsigned)k);
+            if (rank <= 32) hipLaunchKernelGGL(ng_y_slots_kernel<1>, gy, dim3(256), 0, s, t, yt, a0.eta / (float)n);
+            else hipLaunchKernelGGL(ng_y_slots_kernel<2>, gy, dim3(256), 0, s, t, yt, a0.eta / (float)n);
+            NG_LAUNCHED();
+        }
+        // (Moving the two small launches that only the fold needs at this point - the sum of the partial products and
+        // the sum of the shares of ||X||^2 - to the internal stream as well was measured and made no difference.)
+        if (fused) {                                         // X1 = X - H R, and ||X||^2 (and H^T X)
+            NG_CHECK(ng_slots_rank_update(t, 0, -1.f, s, 1, &nparts, fuse_y ? &yt : nullptr));
+            if (fuse_y) {
+                int gx = (rank * ((maxdim + 3) / 4) + 255) / 256;
+                if (gx > 256) gx = 256;
+                hipLaunchKernelGGL(ng_y_reduce_slots_kernel, dim3((unsigned)gx, (unsigned)t.nslots, (unsigned)k), dim3(256), 0, s, t, yt,
+                                   a0.eta / (float)n, lay.py_chunks);
+                NG_LAUNCHED();
+            }
             hipLaunchKernelGGL(ng_sumsq_final_slots_kernel, dim3(t.nslots, t.batch), dim3(256), 0, s, t, 0, a0.alpha, a0.eta, nparts, 1);
             NG_LAUNCHED();
         } else {

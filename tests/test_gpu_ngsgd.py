@@ -280,6 +280,18 @@ def test_ng_training_with_folds_on_some_minibatches_only():
     _run_small_ng_case([70, 130, 96, 40], 2, 64, 0.05, 12, 0.2, 13, [True, True, False, False, True, False])
 
 
+def test_ng_training_step_ragged_row_tiles():
+    # 45 rows = one whole tile of 32 rows and a ragged one, in the rank update that also takes H^T X for the fold;
+    # widths 53 / 68 / 69 / 36 leave ragged column blocks as well
+    _run_small_ng_case([52, 68, 36], 2, 45, 0.05, 7, 0.2, 21, [True] * 3)
+
+
+def test_ng_training_step_many_row_blocks():
+    # 1100 rows: more blocks of rows than a backward pass keeps partial products H^T X for, so Y is formed by the
+    # pass of its own over X (and its last tile of rows is ragged)
+    _run_small_ng_case([30, 44, 20], 1, 1100, 0.05, 6, 0.2, 23, [True] * 2)
+
+
 def test_config5_ng_full_size_two_steps():
     # 440-6x2048-8000, minibatch 512, rank 30, one replica, two minibatches
     dims, n, lr, rank, seed = gen.CONFIG_FULL_DIMS, 512, 0.008, 30, 41
