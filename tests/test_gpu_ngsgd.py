@@ -286,6 +286,11 @@ def test_ng_training_step_ragged_row_tiles():
     _run_small_ng_case([52, 68, 36], 2, 45, 0.05, 7, 0.2, 21, [True] * 3)
 
 
+def test_ng_training_step_ragged_row_tiles_rank_above_32():
+    # the same with rank 34: two MFMA halves per operand in the rank updates and in the product H^T X
+    _run_small_ng_case([52, 100, 44], 1, 45, 0.05, 34, 0.2, 27, [True] * 2)
+
+
 def test_ng_training_step_many_row_blocks():
     # 1100 rows: more blocks of rows than a backward pass keeps partial products H^T X for, so Y is formed by the
     # pass of its own over X (and its last tile of rows is ragged)
