@@ -604,7 +604,8 @@ __global__ __launch_bounds__(256) void ng_sum_chunks_slots_kernel(NgSlots t, NgC
 //   1  (first update, X1 = X - H R) also leaves the workgroup's share of ||X||^2, of X as it was read;
 //   2  (second update) also leaves the workgroup's share of ||Xh||^2 of the result, and the result's last column in
 //      t.wcol.
-// The shares go to t.part[q][blockIdx.y * gridDim.x + blockIdx.x] (0 from workgroups beyond the slot's width).
+// The shares go to t.part[q][blockIdx.y * maxblk + (block of 128 columns)]; a slot's last workgroup of a row zeroes the
+// entries up to maxblk, so that every slot has the same number of shares to sum.
 // (Summing the chunks of H2 and forming H (I - E) - H2 on the way in as well was measured slower: every one of the
 // up to 250 column blocks of a slot would redo that sum.)
 typedef float ng_floatx16 __attribute__((ext_vector_type(16)));
@@ -627,17 +628,26 @@ struct NgYTable { float* Y[kNgSlots]; int64_t y_b[kNgSlots]; float* P[kNgSlots];
 // layout of an MFMA B operand already (lane = column; MFMA step v multiplies row 8 (v / 4) + v % 4 in lanes 0-31 and
 // the row four further on in lanes 32-63), so the product costs 16 KH loads of H from the caches and 16 KH MFMAs
 // per block instead of a pass of its own over X.
+// The launch's x dimension runs through the blocks of 128 columns of all slots, one slot after the other (slot j:
+// start[j] .. start[j + 1] - 1; a grid as wide as the widest slot for every slot had 70 % of its workgroups find
+// nothing to do on the 440-6x2048-8000 network, and they cost a third of the launch); maxblk = the widest slot's count.
+struct NgRuGrid { int start[kNgSlots + 1]; int maxblk; };
 template <int KH, int FUSE, bool WITHY>
-__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows, NgYTable yt) {
+__global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, int use_h2, float sign, int rows, NgYTable yt, NgRuGrid g) {
     constexpr int fuse = FUSE;
     __shared__ double sh[4];
-    const int slot = blockIdx.z / t.batch, b = blockIdx.z - slot * t.batch;
+    int slot = 0;
+#pragma unroll
+    for (int j = 1; j < kNgSlots; ++j)
+        if (j < t.nslots && (int)blockIdx.x >= g.start[j]) slot = j;
+    slot = __builtin_amdgcn_readfirstlane(slot);
+    const int xb = (int)blockIdx.x - g.start[slot], nblk = g.start[slot + 1] - g.start[slot], b = blockIdx.z;
     const int dim = t.dim[slot], n = t.n, rank = t.rank;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, h = lane >> 5, lc = lane & 31;
-    const int c0 = (blockIdx.x * 4 + wave) * 32;        // (uniform over the wavefront)
+    const int c0 = (xb * 4 + wave) * 32;                // (uniform over the wavefront)
     const int64_t q = (int64_t)slot * t.batch + b;
     float ssq = 0.f;
-    if (c0 < dim) {                                     // the grid is as wide as the widest slot
+    if (c0 < dim) {                                     // (the last block of a slot may have fewer than four wavefronts' worth)
         const int col = c0 + lc;
         const bool col_ok = col < dim;
         const int lcc = min(lc, dim - 1 - c0);          // the lane's column of the block, clamped for the loads
@@ -778,7 +788,10 @@ __global__ __launch_bounds__(256) void ng_rank_update_slots_kernel(NgSlots t, in
     }
     if (fuse != 0) {      // (uniform over the workgroup: every wavefront reaches the barriers)
         const double tot = block_sum_d((double)ssq, sh);
-        if (threadIdx.x == 0) t.part[q * kNgParts + blockIdx.y * gridDim.x + blockIdx.x] = tot;
+        double* __restrict__ pr = t.part + q * kNgParts + (int64_t)blockIdx.y * g.maxblk;
+        if (threadIdx.x == 0) pr[xb] = tot;
+        if (xb == nblk - 1)
+            for (int i = nblk + (int)threadIdx.x; i < g.maxblk; i += 256) pr[i] = 0.0;
     }
 }
 
@@ -1068,21 +1081,25 @@ inline int ng_ru_row_chunks(int n) { return (n + kRuRows - 1) / kRuRows; }
 // the launch leaves.
 int ng_slots_rank_update(const NgSlots& t, int use_h2, float sign, hipStream_t s, int fuse = 0, int* nparts = nullptr,
                          const NgYTable* yt = nullptr) {
-    int maxdim = 0;
-    for (int j = 0; j < t.nslots; ++j) if (t.dim[j] > maxdim) maxdim = t.dim[j];
-    const dim3 grid((unsigned)((maxdim + 127) / 128), (unsigned)((t.n + kRuRows - 1) / kRuRows), (unsigned)(t.nslots * t.batch));
-    if (nparts) *nparts = (int)(grid.x * grid.y);
+    NgRuGrid g = {};
+    for (int j = 0; j < t.nslots; ++j) {
+        const int nb = (t.dim[j] + 127) / 128;
+        g.start[j + 1] = g.start[j] + nb;
+        if (nb > g.maxblk) g.maxblk = nb;
+    }
+    const dim3 grid((unsigned)g.start[t.nslots], (unsigned)((t.n + kRuRows - 1) / kRuRows), (unsigned)t.batch);
+    if (nparts) *nparts = (int)(g.maxblk * grid.y);
     if (yt != nullptr && (fuse != 1 || use_h2 != 0)) return note_hip_error(hipErrorInvalidValue);
     const NgYTable none = {};
     auto launch = [&](auto khc, auto fusec) {
         constexpr int KH = decltype(khc)::value, FUSE = decltype(fusec)::value;
-        hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, FUSE, false>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows, none);
+        hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, FUSE, false>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows, none, g);
     };
     auto launch_kh = [&](auto khc) {
         constexpr int KH = decltype(khc)::value;
         if (fuse == 0) launch(khc, std::integral_constant<int, 0>{});
         else if (fuse == 1 && yt != nullptr)
-            hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, 1, true>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows, *yt);
+            hipLaunchKernelGGL((ng_rank_update_slots_kernel<KH, 1, true>), grid, dim3(256), 0, s, t, use_h2, sign, kRuRows, *yt, g);
         else if (fuse == 1) launch(khc, std::integral_constant<int, 1>{});
         else launch(khc, std::integral_constant<int, 2>{});
     };
