@@ -111,13 +111,38 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
     const int64_t tiles = (int64_t)((M + pl.bm - 1) / pl.bm) * ((N + pl.bn - 1) / pl.bn) * batch;
     int splits = cfg_kg(cfg) ? 1 : force_splits;      // these split the contraction inside the workgroup only
     if (splits <= 0) {
+        // A launch takes about as long as the workgroups of its fullest compute unit one after the other: in units of
+        // contraction steps, ceil(tiles * splits / compute units) * K / splits; a compute unit with a single, short
+        // workgroup (fewer than 6000 steps) has nothing to hide its prologue and epilogue behind (+ 20 %); the reducer
+        // costs 6 us (340 steps' worth at 64x64) and each split 8 bytes per element of C at about 4 TB/s.  Splits keep at
+        // least 16 k-tiles each, and a split must promise 5 % to be taken.  Measured with 64x64 tiles (us for the
+        // splits named, the model's choice marked):
+        //   28 tiles, K 2048:  6 / 8* / 10 / 16: 13.9 / 13.2 / 15.3 / 15.0       32 tiles, K 8000: 4 / 8* / 16: 37.5 / 25.8 / 27.6
+        //   96 tiles, K 8000:  2 / 3 / 4 / 5*: 68 / 84 / 66 / 58                 128 tiles, K 8000: 2 / 3 / 4* / 5: 81 / 86 / 72 / 79
+        //   160 tiles, K 2048: 1 / 2 / 3* / 4: 36 / 38 / 29 / 32                 192 tiles, K 2048: 1 / 2 / 3 / 4*: 36 - 39 / 38 / 39 / 34
+        //   224, 256 tiles, K 2048: 1* / 2: 36 / 38.5, 37 / 40                   256 tiles, K 8000: 1* / 2 / 4: 127 / 129 / 132
+        //   320 tiles, K 2048: 1 / 2: 63.5 / 55.9 (3* by the model)              384 tiles, K 2048: 1 / 2* / 3: 63.6 / 58.5 / 70.8
+        //   384 tiles, K 8000: 1 / 2*: 231 / 193                                 512 tiles, K 2048: 1* / 2: 67 / 75
+        //   500 and 625 tiles, K 2048: unsplit faster than split in two (no split is considered from 512 tiles on)
         splits = 1;
-        if (tiles <= kNumCU + kNumCU / 2) {                        // (500 tiles measured faster unsplit than split in two)
-            splits = (int)((2 * kNumCU + tiles - 1) / tiles);      // aim at two workgroups per compute unit
-            const int max_by_k = (K + 8 * bk - 1) / (8 * bk);       // keep >= 8 k-tiles per split
-            if (splits > max_by_k) splits = max_by_k;
-            if (splits > 16) splits = 16;
-            if (splits < 1) splits = 1;
+        if (tiles < 2 * kNumCU) {
+            const int ktiles = (K + bk - 1) / bk;
+            const double per_split = (double)M * N * batch * 1.14e-4;
+            auto cost = [&](int sp) {
+                const int64_t rounds = (tiles * sp + kNumCU - 1) / kNumCU;
+                const int steps = (ktiles + sp - 1) / sp * bk;
+                double c = (double)rounds * steps;
+                if (rounds == 1 && steps < 6000) c *= 1.2;
+                if (sp > 1) c += 340.0 + sp * per_split;
+                return c;
+            };
+            int smax = K / (16 * bk);
+            if (smax > 16) smax = 16;
+            double best = cost(1);
+            for (int sp = 2; sp <= smax; ++sp) {
+                const double c = cost(sp);
+                if (c < 0.95 * best) { best = c; splits = sp; }
+            }
         }
     }
     // contraction elements per split, rounded up to the k tile; drop empty trailing splits
