@@ -99,9 +99,11 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, int force_cfg, int force_spli
         // 26.9 us including the reducer (13.1 against 15.9 us for the 440-wide first layer).  Not at half or
         // twice that many tiles, nor for K = 8000 (measured).
         const int64_t t3264 = (int64_t)((M + 31) / 32) * ((N + 63) / 64) * batch;
-        if (cfg == CFG_64 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU + kNumCU / 8 && K >= 256 && K <= 4096) cfg = CFG_KG_32x64;
+        // (One workgroup of it fills a compute unit's LDS: past one tile per compute unit the launch takes two turns,
+        // 39 us at 272 or 288 rows against 29 us for 64x64 tiles split in three.)
+        if (cfg == CFG_64 && t3264 >= 3 * kNumCU / 4 && t3264 <= kNumCU && K >= 256 && K <= 4096) cfg = CFG_KG_32x64;
         // Half as many rows again (128 x 2048 x 2048): 32x32 tiles, one wavefront per k-group, no barrier in the
-        // loop: 18.0 against 19.8 us.
+        // loop: 18.0 against 19.8 us.  (Two of its workgroups share a compute unit.)
         const int64_t t3232 = (int64_t)((M + 31) / 32) * ((N + 31) / 32) * batch;
         if (cfg == CFG_64 && t3232 >= 3 * kNumCU / 4 && t3232 <= kNumCU + kNumCU / 8 && K >= 1024 && K <= 4096) cfg = CFG_KG_32x32;
     }
